@@ -1,0 +1,279 @@
+"""Pins for the hard-ECC CPU oracle (no GPU).
+
+The oracle has three independent derivations of the curve (literal Eq. 1-2
+count, cell-maximum histogram, per-vertex coefficient of Eq. 3) in numpy and
+one in plain C.  They are pinned to hand-worked examples, closed forms,
+invariants and each other, so that a dropped term, a wrong sign, a wrong
+tie-break or a transposed axis fails at least one test.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import ecc_oracle as O
+from oracle import ecc_oracle_c as OC
+
+
+def _read_golden(path):
+    blocks, cur = [], []
+    for line in open(path):
+        line = line.strip()
+        if line.startswith("#"):
+            if cur:
+                blocks.append(cur)
+                cur = []
+            continue
+        if line:
+            cur.append([int(v) for v in line.split()])
+    if cur:
+        blocks.append(cur)
+    return [np.array(b) for b in blocks]
+
+
+def _all_curves(X, t):
+    """Curves from the four derivations."""
+    return {
+        "brute": O.ecc_bruteforce(X, t),
+        "cellmax": O.ecc_cellmax(X, t),
+        "coeff": O.ecc_hard(X, t),
+        "c": OC.ecc_hard(X, t),
+    }
+
+
+@pytest.mark.parametrize("name", ["worked_3x3.txt", "frame_4x4.txt"])
+def test_golden_examples(golden_dir, name):
+    X, c, curve = _read_golden(os.path.join(golden_dir, name))
+    curve = curve.ravel()
+    t = O.thresholds_levels(len(curve))
+    X8 = X.astype(np.uint8)
+    np.testing.assert_array_equal(O.coeff(X8), c)
+    np.testing.assert_array_equal(OC.coeff(X8), c)
+    for k, v in _all_curves(X8, t).items():
+        np.testing.assert_array_equal(v, curve, err_msg=k)
+    # float input gives the same map and curve
+    np.testing.assert_array_equal(OC.coeff(X.astype(np.float32)), c)
+
+
+def test_exhaustive_three_level_3x3():
+    """All 3^9 grids over {0,1,2}: ties everywhere; every derivation agrees at
+    every level and sum c = 1."""
+    t = O.thresholds_levels(3)
+    for vals in itertools.product(range(3), repeat=9):
+        X = np.array(vals, dtype=np.uint8).reshape(3, 3)
+        ref = O.ecc_bruteforce(X, t)
+        c = O.coeff(X)
+        assert c.sum() == 1
+        np.testing.assert_array_equal(O.ecc_from_coeff(X, c, t), ref)
+        np.testing.assert_array_equal(O.ecc_cellmax(X, t), ref)
+        assert ref[-1] == 1
+
+
+def test_exhaustive_3x3_c_oracle_matches_numpy_coeff():
+    grids = np.array(list(itertools.product(range(3), repeat=9)), dtype=np.uint8).reshape(-1, 3, 3)
+    for X in grids[::7]:
+        np.testing.assert_array_equal(OC.coeff(X), O.coeff(X))
+
+
+def test_coefficient_range_extremes():
+    """The exact coefficient leaves {-1,0,1}: -3 in 2D when the four edge
+    neighbours are lower and the diagonals higher; -5 and +7 in 3D."""
+    X = np.array([[9, 0, 9], [0, 5, 0], [9, 0, 9]], dtype=np.uint8)
+    assert O.coeff(X)[1, 1] == -3 and OC.coeff(X)[1, 1] == -3
+    X3 = np.full((3, 3, 3), 9, dtype=np.uint8)
+    X3[1, 1, 1] = 5
+    for ax in range(3):
+        for d in (0, 2):
+            idx = [1, 1, 1]
+            idx[ax] = d
+            X3[tuple(idx)] = 0
+    assert O.coeff(X3)[1, 1, 1] == -5 and OC.coeff(X3)[1, 1, 1] == -5
+    # faces and edges lower, corners higher: 1 - 6 + 12 - 0 = 7
+    X3 = np.zeros((3, 3, 3), dtype=np.uint8)
+    X3[1, 1, 1] = 5
+    for cz, cy, cx in itertools.product((0, 2), repeat=3):
+        X3[cz, cy, cx] = 9
+    assert O.coeff(X3)[1, 1, 1] == 7 and OC.coeff(X3)[1, 1, 1] == 7
+
+
+@pytest.mark.parametrize("shape", [(2, 2, 2), (3, 4, 2), (4, 4, 4), (1, 5, 3), (2, 1, 4)])
+def test_random_small_3d_with_ties(shape):
+    rng = np.random.default_rng(7)
+    t = O.thresholds_levels(4)
+    for _ in range(40):
+        X = rng.integers(0, 4, size=shape, dtype=np.uint8)
+        cur = _all_curves(X, t)
+        for k, v in cur.items():
+            np.testing.assert_array_equal(v, cur["brute"], err_msg=k)
+        assert O.coeff(X).sum() == 1
+        np.testing.assert_array_equal(OC.coeff(X), O.coeff(X))
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (1, 7), (7, 1), (2, 2), (5, 9), (13, 6)])
+def test_random_small_2d_with_ties(shape):
+    rng = np.random.default_rng(11)
+    t = O.thresholds_levels(5)
+    for _ in range(40):
+        X = rng.integers(0, 5, size=shape, dtype=np.uint16)
+        cur = _all_curves(X, t)
+        for k, v in cur.items():
+            np.testing.assert_array_equal(v, cur["brute"], err_msg=k)
+        np.testing.assert_array_equal(OC.coeff(X), O.coeff(X))
+
+
+def test_constant_grid_tie_break():
+    for shape in [(4, 5), (3, 4, 5)]:
+        X = np.full(shape, 3, dtype=np.uint8)
+        expect = np.zeros(shape, dtype=np.int8)
+        expect.flat[0] = 1
+        np.testing.assert_array_equal(O.coeff(X), expect)
+        np.testing.assert_array_equal(OC.coeff(X), expect)
+        np.testing.assert_array_equal(OC.ecc_hard(X, O.thresholds_levels(5)), [0, 0, 0, 1, 1])
+
+
+def test_ramps_are_regular():
+    """Monotone ramps: only the first vertex is critical; ECC = 1 from the minimum up."""
+    X = np.arange(4 * 5 * 6, dtype=np.uint16).reshape(4, 5, 6)
+    for c in (O.coeff(X), OC.coeff(X)):
+        assert c.flat[0] == 1 and np.count_nonzero(c) == 1
+    z, y, x = np.meshgrid(np.arange(4), np.arange(5), np.arange(6), indexing="ij")
+    X = (x + y + z).astype(np.uint8)  # index ties on every anti-diagonal plane
+    for c in (O.coeff(X), OC.coeff(X)):
+        assert c.flat[0] == 1 and np.count_nonzero(c) == 1
+    # reversed ramp: the last vertex enters first
+    X = (200 - np.arange(4 * 5, dtype=np.int64)).astype(np.uint8).reshape(4, 5)
+    for c in (O.coeff(X), OC.coeff(X)):
+        assert c.flat[-1] == 1 and np.count_nonzero(c) == 1
+    np.testing.assert_array_equal(OC.ecc_hard(X, O.thresholds_levels(201))[181:], 1)
+
+
+def test_checkerboard():
+    y, x = np.meshgrid(np.arange(6), np.arange(7), indexing="ij")
+    X = ((x + y) % 2).astype(np.uint8)
+    t = O.thresholds_levels(2)
+    for k, v in _all_curves(X, t).items():
+        np.testing.assert_array_equal(v, [int((X == 0).sum()), 1], err_msg=k)
+
+
+def _shape_curve(mask):
+    """low (0) on the shape, high (1) elsewhere: ECC(0) = chi(shape)."""
+    X = np.where(mask, 0, 1).astype(np.uint8)
+    t = O.thresholds_levels(2)
+    cur = _all_curves(X, t)
+    for k, v in cur.items():
+        np.testing.assert_array_equal(v, cur["brute"], err_msg=k)
+    return cur["c"]
+
+
+def test_solid_shapes_known_euler_characteristic():
+    # filled box
+    m = np.zeros((7, 8), bool); m[2:5, 1:6] = True
+    np.testing.assert_array_equal(_shape_curve(m), [1, 1])
+    # square annulus
+    m = np.zeros((7, 8), bool); m[1:6, 1:7] = True; m[3, 3:5] = False
+    np.testing.assert_array_equal(_shape_curve(m), [0, 1])
+    # two boxes
+    m = np.zeros((7, 9), bool); m[1:3, 1:3] = True; m[4:6, 5:8] = True
+    np.testing.assert_array_equal(_shape_curve(m), [2, 1])
+    # 3D hollow shell: chi = 2
+    m = np.zeros((7, 7, 7), bool); m[1:6, 1:6, 1:6] = True; m[3, 3, 3] = False
+    np.testing.assert_array_equal(_shape_curve(m), [2, 1])
+    # 3D solid torus (a square ring extruded): chi = 0
+    m = np.zeros((5, 8, 8), bool); m[1:4, 1:7, 1:7] = True; m[1:4, 3:5, 3:5] = False
+    np.testing.assert_array_equal(_shape_curve(m), [0, 1])
+    # 3D solid ball-like box: chi = 1
+    m = np.zeros((5, 6, 7), bool); m[1:4, 1:5, 2:6] = True
+    np.testing.assert_array_equal(_shape_curve(m), [1, 1])
+
+
+def test_invariants_below_min_and_at_max():
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((9, 10, 11)).astype(np.float32)
+    lo, hi = float(X.min()), float(X.max())
+    t = np.array([lo - 1.0, np.nextafter(np.float32(lo), np.float32(-9)), lo, hi, hi + 1], dtype=np.float64)
+    cur = OC.ecc_hard(X, t)
+    assert cur[0] == 0 and cur[1] == 0 and cur[2] == 1 and cur[3] == 1 and cur[4] == 1
+    np.testing.assert_array_equal(O.ecc_cellmax(X, t), cur)
+
+
+def test_geometry_invariance_and_depth_one():
+    rng = np.random.default_rng(5)
+    X = rng.integers(0, 16, size=(6, 7, 8), dtype=np.uint8)
+    t = O.thresholds_levels(16)
+    ref = OC.ecc_hard(X, t)
+    np.testing.assert_array_equal(OC.ecc_hard(np.ascontiguousarray(X[::-1]), t), ref)
+    np.testing.assert_array_equal(OC.ecc_hard(np.ascontiguousarray(X[:, :, ::-1]), t), ref)
+    np.testing.assert_array_equal(OC.ecc_hard(np.ascontiguousarray(X.transpose(2, 0, 1)), t), ref)
+    X2 = X[0]
+    np.testing.assert_array_equal(OC.ecc_hard(X2[None], t), OC.ecc_hard(X2, t))
+    np.testing.assert_array_equal(OC.coeff(X2[None])[0], OC.coeff(X2))
+
+
+def test_iid_expectation_formula():
+    """For i.i.d. values each k-vertex cell is present with probability q^k:
+    E[ECC] = V q - E q^2 + F q^4 - C q^8 (cell counts of the full grid)."""
+    n, L = 48, 16
+    rng = np.random.default_rng(2024)
+    reps = 6
+    acc = np.zeros(L)
+    for _ in range(reps):
+        X = rng.integers(0, L, size=(n, n, n), dtype=np.uint16)
+        acc += OC.ecc_hard(X, O.thresholds_levels(L))
+    mean = acc / reps
+    q = (np.arange(L) + 1) / L
+    V, E, F, C = n ** 3, 3 * n * n * (n - 1), 3 * n * (n - 1) ** 2, (n - 1) ** 3
+    expect = V * q - E * q ** 2 + F * q ** 4 - C * q ** 8
+    # fluctuations of the mean are O(sqrt(V / reps)); sqrt(V) is ~3 % of the curve's scale
+    assert np.max(np.abs(mean - expect)) < np.sqrt(V)
+    assert np.max(np.abs(expect)) > 30 * np.sqrt(V)
+    n2 = 200
+    acc = np.zeros(L)
+    for _ in range(reps):
+        X = rng.integers(0, L, size=(n2, n2), dtype=np.uint8)
+        acc += OC.ecc_hard(X, O.thresholds_levels(L))
+    V, E, F = n2 * n2, 2 * n2 * (n2 - 1), (n2 - 1) ** 2
+    expect = V * q - E * q ** 2 + F * q ** 4
+    assert np.max(np.abs(acc / reps - expect)) < np.sqrt(V)
+
+
+def test_float_thresholds_and_binning():
+    t = O.thresholds_equal_width(-1.0, 3.0, 8)
+    np.testing.assert_allclose(t, np.linspace(-0.5, 3.0, 8))
+    assert t[-1] == 3.0
+    x = np.array([-2.0, -1.0, -0.5, -0.49, 3.0, 3.1])
+    np.testing.assert_array_equal(O.bin_index(x, t), [0, 0, 0, 1, 7, 8])
+    # degenerate range
+    t = O.thresholds_equal_width(2.0, 2.0, 4)
+    np.testing.assert_array_equal(t, 2.0)
+    # mid-size float field: curve ends at 1, starts with c of the minimum
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((37, 53)).astype(np.float32)
+    t = O.thresholds_equal_width(X.min(), X.max(), 64)
+    cur = _all_curves(X, t)
+    for k, v in cur.items():
+        np.testing.assert_array_equal(v, cur["brute"], err_msg=k)
+    assert cur["c"][-1] == 1
+
+
+def test_values_above_last_threshold_are_dropped():
+    X = np.array([[0, 9], [9, 1]], dtype=np.uint8)
+    t = O.thresholds_levels(2)
+    for k, v in _all_curves(X, t).items():
+        np.testing.assert_array_equal(v, [1, 2], err_msg=k)
+
+
+def test_mid_size_dtypes_and_batch():
+    rng = np.random.default_rng(17)
+    Xb = rng.integers(0, 300, size=(3, 19, 23, 29), dtype=np.uint16)
+    t = O.thresholds_levels(300)
+    got = OC.ecc_hard_batch(Xb, t)
+    for i in range(3):
+        np.testing.assert_array_equal(got[i], O.ecc_cellmax(Xb[i], t))
+    Xf = rng.standard_normal((2, 31, 17)).astype(np.float32)
+    Xf[0, 3:9, 4:8] = Xf[0, 3, 4]  # a plateau of exact ties
+    t = O.thresholds_equal_width(Xf.min(), Xf.max(), 50)
+    got = OC.ecc_hard_batch(Xf, t)
+    for i in range(2):
+        np.testing.assert_array_equal(got[i], O.ecc_cellmax(Xf[i], t))
+        np.testing.assert_array_equal(got[i], O.ecc_hard(Xf[i], t))
