@@ -1,0 +1,141 @@
+/*
+ * libecc_hip -- Euler Characteristic Curves of dense 2D/3D grids on MI355X (gfx950).
+ *
+ * C ABI.  Every array argument is a DEVICE pointer owned by the caller unless
+ * marked "host".  The library never allocates device memory, never
+ * synchronises, and enqueues work only on the HIP stream it is given
+ * (hip_stream is a hipStream_t passed as void*; NULL is the default stream).
+ * Scratch space is passed in as `workspace` (device memory, 256-byte aligned,
+ * at least ecc_workspace_bytes() long); two calls that may overlap in time
+ * must not share one workspace.
+ *
+ * Every entry point validates its arguments on the host BEFORE the first HIP
+ * call and returns an ecc_status; ecc_last_error() gives a message for the
+ * last failure on the calling thread.  Inputs must be finite (no NaN/Inf).
+ *
+ * Complex convention (the paper's Background section, Eq. 1-3, leaves it
+ * open; this library fixes it): grid points are the vertices of a cubical
+ * complex; an edge / square / cube (2 / 2x2 / 2x2x2 axis-adjacent points,
+ * inside the grid, no wrap-around) is present at threshold tau once ALL its
+ * vertices are <= tau; ECC(tau) = V - E + F - C.  In the per-vertex form
+ * ECC(tau) = sum_p c(p) 1[X(p) <= tau] each cell is charged to its last
+ * vertex under the order "smaller value first, equal values by C-order linear
+ * index", so c(p) = 1 - #edges + #squares - #cubes charged to p.
+ *
+ * Grid layout: C-contiguous [batch][D][H][W] (3D) or [batch][H][W] (2D), W
+ * fastest; `dims` lists one item's extents slowest-first.
+ */
+#ifndef ECC_H_
+#define ECC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { ECC_U8 = 0, ECC_U16 = 1, ECC_F32 = 2 } ecc_dtype;
+
+typedef enum {
+  ECC_OK = 0,
+  ECC_ERR_INVALID_ARG = -1, /* NULL pointer, bad ndim/dims/batch/bins/T/lambda/range/dtype */
+  ECC_ERR_UNSUPPORTED = -2, /* valid request outside the built limits (see ECC_MAX_*)       */
+  ECC_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than ecc_workspace_bytes()         */
+  ECC_ERR_DEVICE = -5       /* a HIP call failed; message holds hipGetErrorString           */
+} ecc_status;
+
+#define ECC_MAX_BINS 16384       /* per-block LDS histogram of int32 counters     */
+#define ECC_MAX_THRESHOLDS 4096  /* soft thresholds held in LDS                   */
+
+/* Message for the last non-OK status returned on this thread ("" if none). */
+const char* ecc_last_error(void);
+
+/* Library version string. */
+const char* ecc_version(void);
+
+/*
+ * Bytes of device workspace sufficient for any entry point called with these
+ * dims / batch and with bins (hard) or T (soft) = bins_or_T.  Host-only
+ * arithmetic; returns 0 on invalid arguments.
+ */
+size_t ecc_workspace_bytes(int ndim, const int64_t* dims /* host */, int64_t batch,
+                           int bins_or_T);
+
+/*
+ * Hard ECC (Eq. 3 of the paper, Methods "full sweep"): per-vertex coefficient
+ * c(p) from the 3x3 / 3x3x3 neighbourhood, histogram of c(p) over threshold
+ * bins, inclusive prefix sum.
+ *
+ *   grid    device, [batch] items of dims, element type `dtype`
+ *   ndim    2 or 3;  dims host array of ndim extents (slowest first, each >= 1)
+ *   bins    number of thresholds B, 1..ECC_MAX_BINS
+ *   range   host double[2] = {lo, hi} with lo <= hi, or NULL.
+ *           Thresholds t_0 <= ... <= t_{B-1}:
+ *             range given (any dtype): t_b = float32(lo + (b+1)(hi-lo)/B)
+ *               evaluated in float64, and t_{B-1} = float32(hi);
+ *             NULL, integer dtype:  t_b = b   (one bin per level);
+ *             NULL, ECC_F32:        lo, hi = min, max over the WHOLE batch
+ *               (one extra read pass over the grid), then as above.
+ *   curve   device out, int64 [batch][B]: curve[i][b] = ECC of item i at t_b.
+ *           A point with X(p) > t_{B-1} is in no sublevel set and is dropped;
+ *           a point with X(p) <= t_0 counts from bin 0.
+ * The curve is exact (integer arithmetic end to end) and does not depend on
+ * the tie-break.
+ */
+int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype,
+             int bins, const double* range, int64_t* curve, void* workspace,
+             size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The coefficient map itself (Eq. 3): c_out[batch][N] int8, values in
+ * [-3, 1] (2D) or [-5, 7] (3D).  Exposes the first step of ecc_hard and of
+ * the soft path for inspection and tests.  Needs no workspace.
+ */
+int ecc_coeff(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype,
+              int8_t* c_out, void* hip_stream);
+
+/*
+ * Soft single-direction ECC forward (Eq. 6):
+ *   chi[i][j] = sum_p c_i(p) sigma_lambda( tau_j - X_i(p) - alpha <u, p> ),
+ *   sigma_lambda(z) = 1 / (1 + exp(-lambda z)).
+ * c(p) is the integer coefficient of the raw grid X (as in ecc_coeff).
+ * p = (x, y[, z]) are 0-based integer grid coordinates with x the FASTEST
+ * axis (column), so for 2D <u,p> = u[0]*col + u[1]*row.  u is used as given
+ * (the caller keeps it on the unit sphere).
+ *
+ *   grid  device float32 [batch] items;  u device float32 [ndim]
+ *   tau   device float32 [T], 1 <= T <= ECC_MAX_THRESHOLDS, shared by the batch
+ *   lambda > 0 and finite;  alpha finite
+ *   chi   device out float32 [batch][T]
+ * Sigmoids are evaluated in float32 on an argument formed in float64; partial
+ * sums are combined in a fixed order, so results are run-to-run identical.
+ */
+int ecc_soft_fwd(const float* grid, int ndim, const int64_t* dims, int64_t batch,
+                 const float* u, float alpha, const float* tau, int T, float lambda,
+                 float* chi, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Soft ECC derivatives (Eq. 8, 9, 10 of the appendix; Eq. 7), with
+ * sigma' = lambda sigma (1 - sigma) and z_pj = tau_j - X(p) - alpha <u,p>:
+ *   grad_X[i][p]       = sum_j g[i][j] * ( -c_i(p) sigma'(z_pj) )       (Eq. 8, contracted)
+ *   dchi_dtau[i][j]    =  sum_p c_i(p) sigma'(z_pj)                     (Eq. 9)
+ *   dchi_du[i][j][k]   = -alpha sum_p c_i(p) sigma'(z_pj) p_k           (Eq. 10), k = x, y[, z]
+ * c(p) is treated as a constant (the paper differentiates through the
+ * sigmoid only); dchi_du is the unconstrained ambient derivative.
+ *
+ *   grad_chi  device float32 [batch][T] upstream g, or NULL for all ones
+ *   grad_X    device out float32 [batch][N]        (every element written)
+ *   dchi_dtau device out float32 [batch][T]
+ *   dchi_du   device out float32 [batch][T][ndim]
+ * Any of the three outputs may be NULL to skip it (not all three).
+ */
+int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch,
+                 const float* u, float alpha, const float* tau, int T, float lambda,
+                 const float* grad_chi, float* grad_X, float* dchi_dtau, float* dchi_du,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECC_H_ */

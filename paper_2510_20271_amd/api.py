@@ -1,0 +1,122 @@
+"""Thin Python binding of the C ABI in include/ecc.h: argument marshalling only.
+
+Tensors are torch CUDA(HIP) tensors; torch supplies device memory and the
+current stream, every step of the computation runs inside libecc_hip.so.
+"""
+from __future__ import annotations
+
+import ctypes
+
+import torch
+
+from . import _lib
+
+ECC_U8, ECC_U16, ECC_F32 = 0, 1, 2
+_DTYPES = {torch.uint8: ECC_U8, torch.uint16: ECC_U16, torch.int16: ECC_U16, torch.float32: ECC_F32}
+
+
+class EccError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"ecc status {status}: {message}")
+        self.status = status
+
+
+def ecc_last_error() -> str:
+    return _lib.load().ecc_last_error().decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise EccError(status, ecc_last_error())
+
+
+def _dims(shape):
+    arr = (ctypes.c_int64 * len(shape))(*shape)
+    return arr
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _need_device(*tensors):
+    for t in tensors:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def ecc_workspace_bytes(item_shape, batch: int, bins_or_T: int) -> int:
+    return int(_lib.load().ecc_workspace_bytes(len(item_shape), _dims(item_shape), batch, bins_or_T))
+
+
+def _workspace(item_shape, batch, n, device, workspace):
+    need = ecc_workspace_bytes(item_shape, batch, n)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, workspace=None):
+    """grid: [batch, (D,) H, W] device tensor (uint8 / uint16 / float32).
+    Returns the int64 curve [batch, bins]."""
+    _need_device(grid, curve, workspace)
+    if grid.dim() != ndim + 1:
+        raise ValueError("grid must be [batch, *item_shape]")
+    batch, item = grid.shape[0], tuple(grid.shape[1:])
+    if curve is None:
+        curve = torch.empty((batch, bins), dtype=torch.int64, device=grid.device)
+    workspace = _workspace(item, batch, max(bins, 1), grid.device, workspace)
+    rng = None
+    if range is not None:
+        rng = (ctypes.c_double * 2)(float(range[0]), float(range[1]))
+    _check(_lib.load().ecc_hard(_ptr(grid), ndim, _dims(item), batch, _DTYPES[grid.dtype], bins, rng,
+                                _ptr(curve), _ptr(workspace), workspace.numel(), _stream()))
+    return curve
+
+
+def ecc_coeff(grid: torch.Tensor, ndim: int, c_out=None):
+    _need_device(grid, c_out)
+    batch, item = grid.shape[0], tuple(grid.shape[1:])
+    if c_out is None:
+        c_out = torch.empty(grid.shape, dtype=torch.int8, device=grid.device)
+    _check(_lib.load().ecc_coeff(_ptr(grid), ndim, _dims(item), batch, _DTYPES[grid.dtype],
+                                 _ptr(c_out), _stream()))
+    return c_out
+
+
+def ecc_soft_fwd(grid, ndim, u, alpha, tau, lam, chi=None, workspace=None):
+    _need_device(grid, u, tau, chi, workspace)
+    batch, item = grid.shape[0], tuple(grid.shape[1:])
+    T = tau.numel()
+    if chi is None:
+        chi = torch.empty((batch, T), dtype=torch.float32, device=grid.device)
+    workspace = _workspace(item, batch, max(T, 1), grid.device, workspace)
+    _check(_lib.load().ecc_soft_fwd(_ptr(grid), ndim, _dims(item), batch, _ptr(u), float(alpha),
+                                    _ptr(tau), T, float(lam), _ptr(chi), _ptr(workspace),
+                                    workspace.numel(), _stream()))
+    return chi
+
+
+def ecc_soft_bwd(grid, ndim, u, alpha, tau, lam, grad_chi=None, grad_X=None, dchi_dtau=None,
+                 dchi_du=None, workspace=None):
+    """Returns (grad_X [batch,*item], dchi_dtau [batch,T], dchi_du [batch,T,ndim])."""
+    _need_device(grid, u, tau, grad_chi, grad_X, dchi_dtau, dchi_du, workspace)
+    batch, item = grid.shape[0], tuple(grid.shape[1:])
+    T = tau.numel()
+    dev = grid.device
+    if grad_X is None:
+        grad_X = torch.empty(grid.shape, dtype=torch.float32, device=dev)
+    if dchi_dtau is None:
+        dchi_dtau = torch.empty((batch, T), dtype=torch.float32, device=dev)
+    if dchi_du is None:
+        dchi_du = torch.empty((batch, T, ndim), dtype=torch.float32, device=dev)
+    workspace = _workspace(item, batch, max(T, 1), dev, workspace)
+    _check(_lib.load().ecc_soft_bwd(_ptr(grid), ndim, _dims(item), batch, _ptr(u), float(alpha),
+                                    _ptr(tau), T, float(lam), _ptr(grad_chi), _ptr(grad_X),
+                                    _ptr(dchi_dtau), _ptr(dchi_du), _ptr(workspace),
+                                    workspace.numel(), _stream()))
+    return grad_X, dchi_dtau, dchi_du

@@ -1,0 +1,183 @@
+// C ABI of libecc_hip: argument validation (host only, before any HIP call),
+// error strings, dispatch to the kernel launchers.
+#include "../../include/ecc.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "ecc_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+constexpr int64_t kMaxBatch = 65535;            // batch rides on gridDim.y
+constexpr int64_t kMaxVertices = (int64_t)1 << 40;
+
+// Fills `s`; returns ECC_OK or an error status with the message set.
+int make_shape(int ndim, const int64_t* dims, int64_t batch, ecc::Shape* s) {
+  if (ndim != 2 && ndim != 3) return fail(ECC_ERR_INVALID_ARG, "ndim must be 2 or 3, got %d", ndim);
+  if (!dims) return fail(ECC_ERR_INVALID_ARG, "dims is NULL");
+  if (batch < 1) return fail(ECC_ERR_INVALID_ARG, "batch must be >= 1, got %lld", (long long)batch);
+  int64_t n = 1;
+  for (int k = 0; k < ndim; ++k) {
+    if (dims[k] < 1)
+      return fail(ECC_ERR_INVALID_ARG, "dims[%d] must be >= 1, got %lld", k, (long long)dims[k]);
+    if (dims[k] > kMaxVertices / n)
+      return fail(ECC_ERR_UNSUPPORTED, "grid has more than 2^40 vertices");
+    n *= dims[k];
+  }
+  if (batch > kMaxBatch)
+    return fail(ECC_ERR_UNSUPPORTED, "batch %lld exceeds %lld", (long long)batch, (long long)kMaxBatch);
+  if (batch > kMaxVertices / n) return fail(ECC_ERR_UNSUPPORTED, "batch * vertices exceeds 2^40");
+  s->ndim = ndim;
+  s->D = ndim == 3 ? dims[0] : 1;
+  s->H = dims[ndim - 2];
+  s->W = dims[ndim - 1];
+  s->N = n;
+  s->batch = batch;
+  return ECC_OK;
+}
+
+int check_dtype(int dtype) {
+  if (dtype != ECC_U8 && dtype != ECC_U16 && dtype != ECC_F32)
+    return fail(ECC_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+  return ECC_OK;
+}
+
+int device_status(hipError_t e, const char* what) {
+  if (e == hipSuccess) return ECC_OK;
+  return fail(ECC_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+int check_soft_common(const float* grid, const float* u, float alpha, const float* tau, int T,
+                      float lambda) {
+  if (!grid) return fail(ECC_ERR_INVALID_ARG, "grid is NULL");
+  if (!u) return fail(ECC_ERR_INVALID_ARG, "u is NULL");
+  if (!tau) return fail(ECC_ERR_INVALID_ARG, "tau is NULL");
+  if (T < 1) return fail(ECC_ERR_INVALID_ARG, "T must be >= 1, got %d", T);
+  if (T > ECC_MAX_THRESHOLDS)
+    return fail(ECC_ERR_UNSUPPORTED, "T %d exceeds ECC_MAX_THRESHOLDS %d", T, ECC_MAX_THRESHOLDS);
+  if (!(lambda > 0.0f) || !std::isfinite(lambda))
+    return fail(ECC_ERR_INVALID_ARG, "lambda must be finite and > 0");
+  if (!std::isfinite(alpha)) return fail(ECC_ERR_INVALID_ARG, "alpha must be finite");
+  return ECC_OK;
+}
+
+int check_workspace(void* ws, size_t have, size_t need) {
+  if (!ws) return fail(ECC_ERR_WORKSPACE, "workspace is NULL (need %zu bytes)", need);
+  if (have < need) return fail(ECC_ERR_WORKSPACE, "workspace has %zu bytes, need %zu", have, need);
+  if (reinterpret_cast<uintptr_t>(ws) & 255)
+    return fail(ECC_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  return ECC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ecc_last_error(void) { return g_err; }
+
+const char* ecc_version(void) { return "libecc_hip 0.1 (gfx950)"; }
+
+size_t ecc_workspace_bytes(int ndim, const int64_t* dims, int64_t batch, int bins_or_T) {
+  ecc::Shape s;
+  if (make_shape(ndim, dims, batch, &s) != ECC_OK) return 0;
+  if (bins_or_T < 1) {
+    fail(ECC_ERR_INVALID_ARG, "bins_or_T must be >= 1");
+    return 0;
+  }
+  size_t a = ecc::hard_workspace_bytes(s, bins_or_T);
+  size_t b = ecc::soft_workspace_bytes(s, bins_or_T);
+  return a > b ? a : b;
+}
+
+int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
+             const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
+             void* hip_stream) {
+  ecc::Shape s;
+  int rc = make_shape(ndim, dims, batch, &s);
+  if (rc != ECC_OK) return rc;
+  if ((rc = check_dtype(dtype)) != ECC_OK) return rc;
+  if (!grid) return fail(ECC_ERR_INVALID_ARG, "grid is NULL");
+  if (!curve) return fail(ECC_ERR_INVALID_ARG, "curve is NULL");
+  if (bins < 1) return fail(ECC_ERR_INVALID_ARG, "bins must be >= 1, got %d", bins);
+  if (bins > ECC_MAX_BINS)
+    return fail(ECC_ERR_UNSUPPORTED, "bins %d exceeds ECC_MAX_BINS %d", bins, ECC_MAX_BINS);
+  double lo = 0.0, hi = 0.0;
+  if (range) {
+    lo = range[0];
+    hi = range[1];
+    if (!std::isfinite(lo) || !std::isfinite(hi) || lo > hi)
+      return fail(ECC_ERR_INVALID_ARG, "range must be finite with lo <= hi");
+  }
+  const size_t esz = dtype == ECC_U8 ? 1 : dtype == ECC_U16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(grid) % esz)
+    return fail(ECC_ERR_INVALID_ARG, "grid is not aligned to its element size");
+  if (reinterpret_cast<uintptr_t>(curve) % 8)
+    return fail(ECC_ERR_INVALID_ARG, "curve is not 8-byte aligned");
+  if ((rc = check_workspace(workspace, workspace_bytes, ecc::hard_workspace_bytes(s, bins))) != ECC_OK)
+    return rc;
+  return device_status(ecc::launch_hard(grid, s, dtype, bins, range != nullptr, lo, hi, curve,
+                                        workspace, static_cast<hipStream_t>(hip_stream)),
+                       "ecc_hard");
+}
+
+int ecc_coeff(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype,
+              int8_t* c_out, void* hip_stream) {
+  ecc::Shape s;
+  int rc = make_shape(ndim, dims, batch, &s);
+  if (rc != ECC_OK) return rc;
+  if ((rc = check_dtype(dtype)) != ECC_OK) return rc;
+  if (!grid) return fail(ECC_ERR_INVALID_ARG, "grid is NULL");
+  if (!c_out) return fail(ECC_ERR_INVALID_ARG, "c_out is NULL");
+  const size_t esz = dtype == ECC_U8 ? 1 : dtype == ECC_U16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(grid) % esz)
+    return fail(ECC_ERR_INVALID_ARG, "grid is not aligned to its element size");
+  return device_status(
+      ecc::launch_coeff(grid, s, dtype, c_out, static_cast<hipStream_t>(hip_stream)), "ecc_coeff");
+}
+
+int ecc_soft_fwd(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
+                 float alpha, const float* tau, int T, float lambda, float* chi, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  ecc::Shape s;
+  int rc = make_shape(ndim, dims, batch, &s);
+  if (rc != ECC_OK) return rc;
+  if ((rc = check_soft_common(grid, u, alpha, tau, T, lambda)) != ECC_OK) return rc;
+  if (!chi) return fail(ECC_ERR_INVALID_ARG, "chi is NULL");
+  if ((rc = check_workspace(workspace, workspace_bytes, ecc::soft_workspace_bytes(s, T))) != ECC_OK)
+    return rc;
+  return device_status(ecc::launch_soft_fwd(grid, s, u, alpha, tau, T, lambda, chi, workspace,
+                                            static_cast<hipStream_t>(hip_stream)),
+                       "ecc_soft_fwd");
+}
+
+int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
+                 float alpha, const float* tau, int T, float lambda, const float* grad_chi,
+                 float* grad_X, float* dchi_dtau, float* dchi_du, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  ecc::Shape s;
+  int rc = make_shape(ndim, dims, batch, &s);
+  if (rc != ECC_OK) return rc;
+  if ((rc = check_soft_common(grid, u, alpha, tau, T, lambda)) != ECC_OK) return rc;
+  if (!grad_X && !dchi_dtau && !dchi_du)
+    return fail(ECC_ERR_INVALID_ARG, "all three outputs are NULL");
+  if ((rc = check_workspace(workspace, workspace_bytes, ecc::soft_workspace_bytes(s, T))) != ECC_OK)
+    return rc;
+  return device_status(
+      ecc::launch_soft_bwd(grid, s, u, alpha, tau, T, lambda, grad_chi, grad_X, dchi_dtau, dchi_du,
+                           workspace, static_cast<hipStream_t>(hip_stream)),
+      "ecc_soft_bwd");
+}
+
+}  // extern "C"

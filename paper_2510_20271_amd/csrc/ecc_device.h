@@ -1,0 +1,114 @@
+// Device-side helpers shared by the HIP kernels of libecc_hip (gfx950 only).
+//
+// Order on vertices (per-vertex form of the curve, Eq. 3 of the paper): q comes
+// before p when X(q) < X(p), or X(q) == X(p) and q has the smaller C-order
+// linear index.  For a neighbour with a larger index that is a strict "<", for
+// a neighbour with a smaller index it is "<=".
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ecc {
+
+constexpr int kWave = 64;
+
+// ---- neighbourhood ring of the 3x3 stencil --------------------------------
+// bit k of an 8-bit ring mask: 0:(+x) 1:(+x,+y) 2:(+y) 3:(-x,+y) 4:(-x)
+// 5:(-x,-y) 6:(-y) 7:(+x,-y).  Even bits are edge neighbours, odd bits the
+// diagonal vertex of the square between its two ring neighbours.
+__device__ __forceinline__ int ring_bit(int dy, int dx) {
+  // dy,dx in {-1,0,1}, not both 0
+  constexpr int tab[3][3] = {{5, 6, 7}, {4, -1, 0}, {3, 2, 1}};
+  return tab[dy + 1][dx + 1];
+}
+
+// 2D coefficient from the ring of "neighbour comes before p" bits:
+// 1 - #edges + #squares, a square being charged to p when its three other
+// vertices all come before p.
+__device__ __forceinline__ int coeff_ring(unsigned m) {
+  unsigned w = m | (m << 8);
+  unsigned sq = m & (w >> 1) & (w >> 7) & 0xAAu;
+  return 1 - __popc(m & 0x55u) + __popc(sq);
+}
+
+// 3D coefficient.  a: ring of the in-plane neighbours; up/dn: rings of the 8
+// outer vertices of the plane above (+z) / below (-z); up0/dn0: the vertex
+// straight above / below.  A cell reaching into the upper plane is charged to
+// p iff the vertical edge is, and the cell's in-plane footprint is charged
+// with every footprint vertex ALSO preceding in the upper plane; its sign is
+// minus the sign of the footprint.  Hence
+//   c = ring(a) - up0 * ring(a & up) - dn0 * ring(a & dn).
+__device__ __forceinline__ int coeff_3d(unsigned a, unsigned up, bool up0, unsigned dn, bool dn0) {
+  int c = coeff_ring(a);
+  if (up0) c -= coeff_ring(a & up);
+  if (dn0) c -= coeff_ring(a & dn);
+  return c;
+}
+
+// Coefficient of the vertex (z,y,x) read straight from global memory, with
+// bounds checks; the reference path for every dtype and shape.
+template <typename T, int ND>
+__device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int64_t H, int64_t W,
+                                        int64_t z, int64_t y, int64_t x) {
+  const int64_t ip = (z * H + y) * W + x;
+  const T vp = g[ip];
+  unsigned ring[3] = {0u, 0u, 0u};
+  bool centre[3] = {false, false, false};
+  constexpr int z0 = (ND == 3) ? -1 : 0, z1 = (ND == 3) ? 1 : 0;
+#pragma unroll
+  for (int dz = z0; dz <= z1; ++dz) {
+#pragma unroll
+    for (int dy = -1; dy <= 1; ++dy) {
+#pragma unroll
+      for (int dx = -1; dx <= 1; ++dx) {
+        if (dz == 0 && dy == 0 && dx == 0) continue;
+        const int64_t qz = z + dz, qy = y + dy, qx = x + dx;
+        bool b = false;
+        if (qz >= 0 && qz < D && qy >= 0 && qy < H && qx >= 0 && qx < W) {
+          const T vq = g[(qz * H + qy) * W + qx];
+          const bool later = (dz > 0) || (dz == 0 && (dy > 0 || (dy == 0 && dx > 0)));
+          b = later ? (vq < vp) : (vq <= vp);
+        }
+        if (dy == 0 && dx == 0) centre[dz + 1] = b;
+        else ring[dz + 1] |= (b ? 1u : 0u) << ring_bit(dy, dx);
+      }
+    }
+  }
+  if (ND == 2) return coeff_ring(ring[1]);
+  return coeff_3d(ring[1], ring[2], centre[2], ring[0], centre[0]);
+}
+
+// ---- bins -----------------------------------------------------------------
+// Header at the start of the workspace of ecc_hard, followed by the threshold
+// table (float[bins]) at byte offset kTableOffset.
+struct HardHeader {
+  unsigned min_key;  // order-preserving uint encodings of the batch min / max
+  unsigned max_key;
+  float lo;          // float(lo) used for the bin guess
+  float scale;       // bins / (hi - lo), 0 when hi <= lo
+};
+constexpr size_t kTableOffset = 256;
+
+__device__ __forceinline__ unsigned float_key(float f) {
+  unsigned b = __float_as_uint(f);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_float(unsigned k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// bin(x) = min{ b : x <= t_b } on the float32 table; `bins` when x is above
+// every threshold.  The guess comes from float arithmetic, the answer from
+// comparisons with the table only, so it is the same on every machine.
+__device__ __forceinline__ int bin_from_table(float x, const float* __restrict__ t, int bins,
+                                              float lo, float scale) {
+  float f = (x - lo) * scale;
+  int b = (f > 0.0f) ? (int)fminf(f, (float)(bins - 1)) : 0;
+  while (b > 0 && x <= t[b - 1]) --b;
+  while (b < bins && x > t[b]) ++b;
+  return b;
+}
+
+template <typename T> __device__ __forceinline__ float as_float(T v) { return (float)v; }
+
+}  // namespace ecc

@@ -1,0 +1,256 @@
+// Hard Euler Characteristic Curve on gfx950: range pass, threshold table,
+// coefficient + LDS-privatised histogram sweep, global merge, prefix scan.
+//
+// Steps (Eq. 3 of the paper; Methods, "full sweep" kernel):
+//   range   : batch-global min/max of a float grid (only when no range given)
+//   prepare : threshold table t_b and zeroed global histogram
+//   sweep   : c(p) for every vertex, hist_block[bin(X(p))] += c(p) in LDS,
+//             block histogram merged into the global one with 64-bit atomics
+//   scan    : inclusive prefix sum of each item's histogram -> int64 curve
+#include "ecc_device.h"
+#include "ecc_internal.h"
+
+namespace ecc {
+
+constexpr int kBlock = 256;
+
+// ---------------------------------------------------------------------------
+// range pass
+// ---------------------------------------------------------------------------
+__global__ void init_header_kernel(HardHeader* h) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    h->min_key = 0xffffffffu;
+    h->max_key = 0u;
+  }
+}
+
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+
+__global__ __launch_bounds__(kBlock) void minmax_f32_kernel(const float* __restrict__ g, int64_t n,
+                                                            HardHeader* h) {
+  float lo = INFINITY, hi = -INFINITY;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  const int64_t n4 = n >> 2;
+  const float4* g4 = reinterpret_cast<const float4*>(g);
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += stride) {
+    float4 v = g4[i];
+    lo = fminf(fminf(lo, v.x), fminf(v.y, fminf(v.z, v.w)));
+    hi = fmaxf(fmaxf(hi, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
+  }
+  for (int64_t i = (n4 << 2) + (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+    float v = g[i];
+    lo = fminf(lo, v);
+    hi = fmaxf(hi, v);
+  }
+  lo = wave_min(lo);
+  hi = wave_max(hi);
+  __shared__ float slo[kBlock / kWave], shi[kBlock / kWave];
+  const int wv = threadIdx.x / kWave, ln = threadIdx.x % kWave;
+  if (ln == 0) { slo[wv] = lo; shi[wv] = hi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int k = 1; k < kBlock / kWave; ++k) { lo = fminf(lo, slo[k]); hi = fmaxf(hi, shi[k]); }
+    if (lo <= hi) {
+      atomicMin(&h->min_key, float_key(lo));
+      atomicMax(&h->max_key, float_key(hi));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// thresholds + zeroed histogram
+// ---------------------------------------------------------------------------
+// t_b = float32(lo + (b+1)(hi-lo)/B) in float64 with every operation rounded
+// on its own (no contraction), t_{B-1} = float32(hi).
+__global__ void prepare_kernel(HardHeader* h, float* __restrict__ table, int bins, int from_device,
+                               double lo_host, double hi_host, unsigned long long* hist,
+                               int64_t hist_len) {
+  double lo, hi;
+  if (from_device) {
+    lo = (double)key_float(h->min_key);
+    hi = (double)key_float(h->max_key);
+  } else {
+    lo = lo_host;
+    hi = hi_host;
+  }
+  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t b = tid; b < bins; b += stride) {
+    double w = __dsub_rn(hi, lo);
+    double t = __dadd_rn(lo, __ddiv_rn(__dmul_rn((double)(b + 1), w), (double)bins));
+    table[b] = (b == bins - 1) ? __double2float_rn(hi) : __double2float_rn(t);
+  }
+  for (int64_t i = tid; i < hist_len; i += stride) hist[i] = 0ull;
+  if (tid == 0) {
+    h->lo = __double2float_rn(lo);
+    double w = __dsub_rn(hi, lo);
+    h->scale = (w > 0.0) ? __double2float_rn(__ddiv_rn((double)bins, w)) : 0.0f;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// generic sweep: one thread per vertex, neighbours read through the caches
+// ---------------------------------------------------------------------------
+template <typename T, int ND, bool LEVELS>
+__global__ __launch_bounds__(kBlock) void sweep_generic_kernel(
+    const T* __restrict__ grid, int64_t D, int64_t H, int64_t W, int64_t N, int bins,
+    const HardHeader* __restrict__ hdr, const float* __restrict__ table,
+    unsigned long long* __restrict__ hist) {
+  extern __shared__ int lhist[];
+  for (int b = threadIdx.x; b < bins; b += kBlock) lhist[b] = 0;
+  __syncthreads();
+  const T* g = grid + (int64_t)blockIdx.y * N;
+  float lo = 0.f, scale = 0.f;
+  if (!LEVELS) { lo = hdr->lo; scale = hdr->scale; }
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < N; i += stride) {
+    const int64_t x = i % W;
+    const int64_t r = i / W;
+    const int64_t y = r % H;
+    const int64_t z = r / H;
+    const int c = coeff_at<T, ND>(g, D, H, W, z, y, x);
+    if (c != 0) {
+      const T v = g[i];
+      int b;
+      if (LEVELS) b = ((int64_t)v < (int64_t)bins) ? (int)v : bins;
+      else b = bin_from_table(as_float(v), table, bins, lo, scale);
+      if (b < bins) atomicAdd(&lhist[b], c);
+    }
+  }
+  __syncthreads();
+  unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
+  for (int b = threadIdx.x; b < bins; b += kBlock) {
+    const int v = lhist[b];
+    if (v != 0) atomicAdd(&out[b], (unsigned long long)(long long)v);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// inclusive prefix sum, one block per batch item, in place (int64)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void scan_kernel(long long* __restrict__ curve, int bins) {
+  long long* c = curve + (int64_t)blockIdx.x * bins;
+  const int per = (bins + kBlock - 1) / kBlock;
+  const int b0 = threadIdx.x * per;
+  const int b1 = min(b0 + per, bins);
+  long long s = 0;
+  for (int b = b0; b < b1; ++b) s += c[b];
+  __shared__ long long part[kBlock];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  // Hillis-Steele over the 256 thread sums
+  for (int o = 1; o < kBlock; o <<= 1) {
+    long long add = (threadIdx.x >= o) ? part[threadIdx.x - o] : 0;
+    __syncthreads();
+    part[threadIdx.x] += add;
+    __syncthreads();
+  }
+  long long run = part[threadIdx.x] - s;  // exclusive prefix of this thread's span
+  for (int b = b0; b < b1; ++b) {
+    run += c[b];
+    c[b] = run;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// coefficient map (inspection / tests)
+// ---------------------------------------------------------------------------
+template <typename T, int ND>
+__global__ __launch_bounds__(kBlock) void coeff_kernel(const T* __restrict__ grid, int64_t D,
+                                                       int64_t H, int64_t W, int64_t N,
+                                                       int8_t* __restrict__ out) {
+  const T* g = grid + (int64_t)blockIdx.y * N;
+  int8_t* o = out + (int64_t)blockIdx.y * N;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < N; i += stride) {
+    const int64_t x = i % W;
+    const int64_t r = i / W;
+    o[i] = (int8_t)coeff_at<T, ND>(g, D, H, W, r / H, r % H, x);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// host launchers
+// ---------------------------------------------------------------------------
+size_t hard_workspace_bytes(const Shape&, int bins) {
+  return kTableOffset + (((size_t)bins * sizeof(float) + 255) / 256) * 256;
+}
+
+static int blocks_for(int64_t N) {
+  int64_t nb = (N + kBlock - 1) / kBlock;
+  return (int)(nb < 1 ? 1 : (nb > 4096 ? 4096 : nb));
+}
+
+template <typename T>
+static void launch_sweep_generic(const void* grid, const Shape& s, bool levels, int bins,
+                                 const HardHeader* hdr, const float* table,
+                                 unsigned long long* hist, hipStream_t st) {
+  dim3 g(blocks_for(s.N), (unsigned)s.batch);
+  size_t lds = (size_t)bins * sizeof(int);
+  const T* p = static_cast<const T*>(grid);
+#define ECC_GO(ND, LV)                                                                        \
+  hipLaunchKernelGGL((sweep_generic_kernel<T, ND, LV>), g, dim3(kBlock), lds, st, p, s.D, s.H, \
+                     s.W, s.N, bins, hdr, table, hist)
+  if (s.ndim == 2) { if (levels) ECC_GO(2, true); else ECC_GO(2, false); }
+  else             { if (levels) ECC_GO(3, true); else ECC_GO(3, false); }
+#undef ECC_GO
+}
+
+hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
+                       double lo, double hi, int64_t* curve, void* ws, hipStream_t st) {
+  HardHeader* hdr = static_cast<HardHeader*>(ws);
+  float* table = reinterpret_cast<float*>(static_cast<char*>(ws) + kTableOffset);
+  unsigned long long* hist = reinterpret_cast<unsigned long long*>(curve);
+  const bool is_float = (dtype == 2);
+  const bool levels = !have_range && !is_float;
+  const bool device_range = !have_range && is_float;
+  const int64_t total = s.N * s.batch;
+  if (device_range) {
+    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, st, hdr);
+    int nb = (int)((total / 4 + kBlock - 1) / kBlock);
+    nb = nb < 1 ? 1 : (nb > 2048 ? 2048 : nb);
+    hipLaunchKernelGGL(minmax_f32_kernel, dim3(nb), dim3(kBlock), 0, st,
+                       static_cast<const float*>(grid), total, hdr);
+  }
+  {
+    const int64_t hist_len = s.batch * bins;
+    int nb = (int)((hist_len + kBlock - 1) / kBlock);
+    nb = nb > 1024 ? 1024 : nb;
+    hipLaunchKernelGGL(prepare_kernel, dim3(nb), dim3(kBlock), 0, st, hdr, table, bins,
+                       device_range ? 1 : 0, lo, hi, hist, hist_len);
+  }
+  switch (dtype) {
+    case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;
+    case 1: launch_sweep_generic<uint16_t>(grid, s, levels, bins, hdr, table, hist, st); break;
+    default: launch_sweep_generic<float>(grid, s, levels, bins, hdr, table, hist, st); break;
+  }
+  hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,
+                     reinterpret_cast<long long*>(curve), bins);
+  return hipGetLastError();
+}
+
+hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st) {
+  dim3 g(blocks_for(s.N), (unsigned)s.batch);
+#define ECC_GO(T, ND)                                                                          \
+  hipLaunchKernelGGL((coeff_kernel<T, ND>), g, dim3(kBlock), 0, st, static_cast<const T*>(grid), \
+                     s.D, s.H, s.W, s.N, c_out)
+  if (s.ndim == 2) {
+    if (dtype == 0) ECC_GO(uint8_t, 2); else if (dtype == 1) ECC_GO(uint16_t, 2); else ECC_GO(float, 2);
+  } else {
+    if (dtype == 0) ECC_GO(uint8_t, 3); else if (dtype == 1) ECC_GO(uint16_t, 3); else ECC_GO(float, 3);
+  }
+#undef ECC_GO
+  return hipGetLastError();
+}
+
+}  // namespace ecc

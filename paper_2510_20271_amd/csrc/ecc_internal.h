@@ -1,0 +1,33 @@
+// Host-side internal interface between the C-ABI layer (ecc_api.hip) and the
+// kernel launchers (ecc_hard.hip, ecc_soft.hip).  Arguments are already
+// validated when these are called.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ecc {
+
+struct Shape {
+  int ndim;          // 2 or 3
+  int64_t D, H, W;   // D == 1 for 2D
+  int64_t N;         // D*H*W
+  int64_t batch;
+};
+
+// ---- hard path ------------------------------------------------------------
+size_t hard_workspace_bytes(const Shape& s, int bins);
+hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
+                       double lo, double hi, int64_t* curve, void* ws, hipStream_t st);
+hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st);
+
+// ---- soft path ------------------------------------------------------------
+size_t soft_workspace_bytes(const Shape& s, int T);
+hipError_t launch_soft_fwd(const float* grid, const Shape& s, const float* u, float alpha,
+                           const float* tau, int T, float lambda, float* chi, void* ws,
+                           hipStream_t st);
+hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, float alpha,
+                           const float* tau, int T, float lambda, const float* g, float* grad_X,
+                           float* dtau, float* du, void* ws, hipStream_t st);
+
+}  // namespace ecc

@@ -1,0 +1,305 @@
+// Soft single-direction ECC on gfx950: forward (Eq. 6 of the paper) and the
+// analytic derivatives (Eq. 8-10 of its appendix).
+//
+// Every term of Eq. 6 and Eq. 8-10 carries the integer factor c(p), so only
+// vertices with c(p) != 0 contribute.  A block takes a tile of consecutive
+// vertices, computes c(p) with the same stencil as the hard path, compacts the
+// critical vertices (c != 0) into an LDS list in a fixed order, and then
+// evaluates the sigmoid only on list x thresholds pairs:
+//   - threshold-major loops (one thread per tau_j, running over the list)
+//     give the sums over p of Eq. 6 / Eq. 9 / Eq. 10 without any cross-lane
+//     reduction;
+//   - a vertex-major loop (one thread per list entry, running over tau_j)
+//     gives the contraction of Eq. 8 with the upstream gradient.
+// Block partials go to the workspace and are combined by a second kernel in a
+// fixed order in float64, so results are run-to-run identical.
+//
+// The sigmoid argument z = tau_j - X(p) - alpha <u,p> is formed in float64 and
+// rounded once; exp2 and reciprocal run on the float32 transcendental unit.
+#include "ecc_device.h"
+#include "ecc_internal.h"
+
+namespace ecc {
+
+constexpr int kSoftBlock = 256;
+constexpr int kPerThread = 8;
+constexpr int kTile = kSoftBlock * kPerThread;  // vertices per block
+
+struct SoftList {
+  double y[kTile];         // X(p) + alpha <u,p>
+  float c[kTile];          // c(p) as float
+  unsigned short loc[kTile];  // position of p inside the tile
+};
+
+__device__ __forceinline__ float exp_neg(float z, float kneg) {
+  // exp(-lambda z) = 2^(kneg z); clamped so the result stays finite
+  return __builtin_amdgcn_exp2f(fminf(kneg * z, 126.0f));
+}
+
+// Fill the list for this block's tile.  Returns the number of entries.  When
+// zero_out != nullptr, vertices with c == 0 get 0 written there.  rel (may be
+// null) receives the coordinates relative to the tile's first vertex.
+template <int ND>
+__device__ __forceinline__ int build_list(const float* __restrict__ g, int64_t D, int64_t H,
+                                          int64_t W, int64_t N, int64_t tile0,
+                                          const float* __restrict__ u, float alpha, SoftList& L,
+                                          float (*rel)[kTile], float* __restrict__ zero_out,
+                                          int* scratch /* kSoftBlock/64 + 1 ints */) {
+  const int tid = threadIdx.x;
+  int cs[kPerThread];
+  int n = 0;
+#pragma unroll
+  for (int k = 0; k < kPerThread; ++k) {
+    const int64_t i = tile0 + k * kSoftBlock + tid;
+    int c = 0;
+    if (i < N) {
+      const int64_t x = i % W, r = i / W;
+      c = coeff_at<float, ND>(g, D, H, W, r / H, r % H, x);
+      if (c == 0 && zero_out) zero_out[i] = 0.0f;
+    }
+    cs[k] = c;
+    n += (c != 0);
+  }
+  // exclusive scan of n over the block: wave scan + wave totals
+  int incl = n;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    int t = __shfl_up(incl, o);
+    if ((tid & (kWave - 1)) >= o) incl += t;
+  }
+  const int wv = tid / kWave;
+  if ((tid & (kWave - 1)) == kWave - 1) scratch[wv] = incl;
+  __syncthreads();
+  int base = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kSoftBlock / kWave; ++w) {
+    const int t = scratch[w];
+    if (w < wv) base += t;
+    total += t;
+  }
+  int pos = base + incl - n;
+  const double ux = (double)u[0], uy = (double)u[1], uz = (ND == 3) ? (double)u[2] : 0.0;
+  const int64_t x0 = tile0 % W, r0 = tile0 / W, y0 = r0 % H, z0 = r0 / H;
+#pragma unroll
+  for (int k = 0; k < kPerThread; ++k) {
+    if (cs[k] != 0) {
+      const int64_t i = tile0 + k * kSoftBlock + tid;
+      const int64_t x = i % W, r = i / W, y = r % H, z = r / H;
+      double dot = ux * (double)x + uy * (double)y;
+      if (ND == 3) dot += uz * (double)z;
+      L.y[pos] = (double)g[i] + (double)alpha * dot;
+      L.c[pos] = (float)cs[k];
+      L.loc[pos] = (unsigned short)(k * kSoftBlock + tid);
+      if (rel) {
+        rel[0][pos] = (float)(x - x0);
+        rel[1][pos] = (float)(y - y0);
+        if (ND == 3) rel[2][pos] = (float)(z - z0);
+      }
+      ++pos;
+    }
+  }
+  __syncthreads();
+  return total;
+}
+
+// ---------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------
+template <int ND>
+__global__ __launch_bounds__(kSoftBlock) void soft_fwd_kernel(
+    const float* __restrict__ grid, int64_t D, int64_t H, int64_t W, int64_t N,
+    const float* __restrict__ u, float alpha, const float* __restrict__ tau, int T, float kneg,
+    float* __restrict__ partial) {
+  __shared__ SoftList L;
+  __shared__ float red[kSoftBlock];
+  __shared__ int scratch[kSoftBlock / kWave + 1];
+  const float* g = grid + (int64_t)blockIdx.y * N;
+  const int64_t tile0 = (int64_t)blockIdx.x * kTile;
+  const int cnt = build_list<ND>(g, D, H, W, N, tile0, u, alpha, L, nullptr, nullptr, scratch);
+  float* out = partial + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * T;
+  const int tid = threadIdx.x;
+  for (int jc = 0; jc < T; jc += kSoftBlock) {
+    const int Tc = min(kSoftBlock, T - jc);
+    const int nparts = kSoftBlock / Tc;
+    const int part = tid / Tc, jl = tid - part * Tc;
+    float acc = 0.0f;
+    if (part < nparts) {
+      const double tj = (double)tau[jc + jl];
+      for (int e = part; e < cnt; e += nparts) {
+        const float z = (float)(tj - L.y[e]);
+        const float ex = exp_neg(z, kneg);
+        acc += L.c[e] * __builtin_amdgcn_rcpf(1.0f + ex);
+      }
+    }
+    red[tid] = acc;
+    __syncthreads();
+    if (tid < Tc) {
+      float s = 0.0f;
+      for (int p = 0; p < nparts; ++p) s += red[p * Tc + tid];
+      out[jc + tid] = s;
+    }
+    __syncthreads();
+  }
+}
+
+__global__ void soft_fwd_reduce_kernel(const float* __restrict__ partial, int ntiles, int T,
+                                       int64_t total /* batch*T */, float* __restrict__ chi) {
+  const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= total) return;
+  const int64_t item = k / T;
+  const int j = (int)(k - item * T);
+  const float* p = partial + item * ntiles * (int64_t)T + j;
+  double s = 0.0;
+  for (int t = 0; t < ntiles; ++t) s += (double)p[(int64_t)t * T];
+  chi[k] = (float)s;
+}
+
+// ---------------------------------------------------------------------------
+// backward
+// ---------------------------------------------------------------------------
+template <int ND>
+__global__ __launch_bounds__(kSoftBlock) void soft_bwd_kernel(
+    const float* __restrict__ grid, int64_t D, int64_t H, int64_t W, int64_t N,
+    const float* __restrict__ u, float alpha, const float* __restrict__ tau, int T, float kneg,
+    float lambda, const float* __restrict__ gup /* [batch][T] or null */,
+    float* __restrict__ grad_X /* or null */, float* __restrict__ partial /* or null */) {
+  __shared__ SoftList L;
+  __shared__ float rel[ND][kTile];
+  __shared__ float red[1 + ND][kSoftBlock];
+  __shared__ int scratch[kSoftBlock / kWave + 1];
+  const float* g = grid + (int64_t)blockIdx.y * N;
+  const int64_t tile0 = (int64_t)blockIdx.x * kTile;
+  float* gx = grad_X ? grad_X + (int64_t)blockIdx.y * N : nullptr;
+  const int cnt = build_list<ND>(g, D, H, W, N, tile0, u, alpha, L, rel, gx, scratch);
+  const int tid = threadIdx.x;
+
+  if (gx) {  // Eq. 8 contracted with the upstream gradient, one thread per critical vertex
+    const float* gj = gup ? gup + (int64_t)blockIdx.y * T : nullptr;
+    for (int e = tid; e < cnt; e += kSoftBlock) {
+      const double ye = L.y[e];
+      float acc = 0.0f;
+      for (int j = 0; j < T; ++j) {
+        const float z = (float)((double)tau[j] - ye);
+        const float ex = exp_neg(z, kneg);
+        const float s = __builtin_amdgcn_rcpf(1.0f + ex);
+        const float d = ex * s * s;  // sigma (1 - sigma)
+        acc += (gj ? gj[j] : 1.0f) * d;
+      }
+      gx[tile0 + L.loc[e]] = -lambda * L.c[e] * acc;
+    }
+  }
+
+  if (partial) {  // Eq. 9 and Eq. 10, one thread per threshold
+    float* out = partial + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (int64_t)T * 4;
+    for (int jc = 0; jc < T; jc += kSoftBlock) {
+      const int Tc = min(kSoftBlock, T - jc);
+      const int nparts = kSoftBlock / Tc;
+      const int part = tid / Tc, jl = tid - part * Tc;
+      float a0 = 0.0f, a[ND];
+#pragma unroll
+      for (int k = 0; k < ND; ++k) a[k] = 0.0f;
+      if (part < nparts) {
+        const double tj = (double)tau[jc + jl];
+        for (int e = part; e < cnt; e += nparts) {
+          const float z = (float)(tj - L.y[e]);
+          const float ex = exp_neg(z, kneg);
+          const float s = __builtin_amdgcn_rcpf(1.0f + ex);
+          const float cd = L.c[e] * (ex * s * s);
+          a0 += cd;
+#pragma unroll
+          for (int k = 0; k < ND; ++k) a[k] += cd * rel[k][e];
+        }
+      }
+      red[0][tid] = a0;
+#pragma unroll
+      for (int k = 0; k < ND; ++k) red[1 + k][tid] = a[k];
+      __syncthreads();
+      if (tid < Tc) {
+#pragma unroll
+        for (int q = 0; q < 1 + ND; ++q) {
+          float s = 0.0f;
+          for (int p = 0; p < nparts; ++p) s += red[q][p * Tc + tid];
+          out[(int64_t)(jc + tid) * 4 + q] = s;
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// dchi_dtau = lambda * sum A0;  dchi_du_k = -alpha lambda * sum (o_k A0 + A_k),
+// o = coordinates of the tile's first vertex.
+__global__ void soft_bwd_reduce_kernel(const float* __restrict__ partial, int ntiles, int T,
+                                       int64_t total, int nd, int64_t H, int64_t W, float alpha,
+                                       float lambda, float* __restrict__ dtau,
+                                       float* __restrict__ du) {
+  const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= total) return;
+  const int64_t item = k / T;
+  const int j = (int)(k - item * T);
+  const float* p = partial + (item * ntiles * (int64_t)T + j) * 4;
+  double s0 = 0.0, s[3] = {0.0, 0.0, 0.0};
+  for (int t = 0; t < ntiles; ++t) {
+    const float* q = p + (int64_t)t * T * 4;
+    const int64_t i0 = (int64_t)t * kTile;
+    const int64_t r0 = i0 / W;
+    const double o[3] = {(double)(i0 % W), (double)(r0 % H), (double)(r0 / H)};
+    const double a0 = (double)q[0];
+    s0 += a0;
+    for (int c = 0; c < nd; ++c) s[c] += o[c] * a0 + (double)q[1 + c];
+  }
+  if (dtau) dtau[k] = (float)((double)lambda * s0);
+  if (du)
+    for (int c = 0; c < nd; ++c) du[k * nd + c] = (float)(-(double)alpha * (double)lambda * s[c]);
+}
+
+// ---------------------------------------------------------------------------
+// host launchers
+// ---------------------------------------------------------------------------
+static int64_t tiles_of(const Shape& s) { return (s.N + kTile - 1) / kTile; }
+
+size_t soft_workspace_bytes(const Shape& s, int T) {
+  return (size_t)256 + (size_t)s.batch * (size_t)tiles_of(s) * (size_t)T * 4 * sizeof(float);
+}
+
+static float kneg_of(float lambda) { return (float)(-(double)lambda * 1.4426950408889634); }
+
+hipError_t launch_soft_fwd(const float* grid, const Shape& s, const float* u, float alpha,
+                           const float* tau, int T, float lambda, float* chi, void* ws,
+                           hipStream_t st) {
+  float* partial = static_cast<float*>(ws);
+  const int ntiles = (int)tiles_of(s);
+  dim3 g((unsigned)ntiles, (unsigned)s.batch);
+  if (s.ndim == 2)
+    hipLaunchKernelGGL(soft_fwd_kernel<2>, g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u,
+                       alpha, tau, T, kneg_of(lambda), partial);
+  else
+    hipLaunchKernelGGL(soft_fwd_kernel<3>, g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u,
+                       alpha, tau, T, kneg_of(lambda), partial);
+  const int64_t total = s.batch * T;
+  hipLaunchKernelGGL(soft_fwd_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                     st, partial, ntiles, T, total, chi);
+  return hipGetLastError();
+}
+
+hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, float alpha,
+                           const float* tau, int T, float lambda, const float* gup, float* grad_X,
+                           float* dtau, float* du, void* ws, hipStream_t st) {
+  float* partial = (dtau || du) ? static_cast<float*>(ws) : nullptr;
+  const int ntiles = (int)tiles_of(s);
+  dim3 g((unsigned)ntiles, (unsigned)s.batch);
+  if (s.ndim == 2)
+    hipLaunchKernelGGL(soft_bwd_kernel<2>, g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u,
+                       alpha, tau, T, kneg_of(lambda), lambda, gup, grad_X, partial);
+  else
+    hipLaunchKernelGGL(soft_bwd_kernel<3>, g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u,
+                       alpha, tau, T, kneg_of(lambda), lambda, gup, grad_X, partial);
+  if (partial) {
+    const int64_t total = s.batch * T;
+    hipLaunchKernelGGL(soft_bwd_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                       st, partial, ntiles, T, total, s.ndim, s.H, s.W, alpha, lambda, dtau, du);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace ecc

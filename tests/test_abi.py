@@ -1,0 +1,129 @@
+"""The C-ABI library loads, exports every symbol include/ecc.h declares, and
+rejects bad arguments on the host before any HIP call (so this runs without a
+GPU; no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_20271_amd import _lib
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)  # non-NULL, 256-aligned, never dereferenced: validation fails first
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "ecc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ecc_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_match_header():
+    lib = _lib.load()
+    names = _declared()
+    assert set(names) == set(_lib.SIGNATURES), names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_error_string():
+    lib = _lib.load()
+    assert b"gfx950" in lib.ecc_version()
+    assert isinstance(lib.ecc_last_error(), bytes)
+
+
+def _dims(*d):
+    return (ctypes.c_int64 * len(d))(*d)
+
+
+def test_workspace_bytes_host_only():
+    lib = _lib.load()
+    assert lib.ecc_workspace_bytes(2, _dims(256, 256), 1, 256) >= 256 + 4 * 256
+    assert lib.ecc_workspace_bytes(4, _dims(2, 2, 2, 2), 1, 8) == 0
+    assert lib.ecc_workspace_bytes(2, _dims(0, 5), 1, 8) == 0
+    assert lib.ecc_workspace_bytes(2, _dims(5, 5), 0, 8) == 0
+    assert lib.ecc_workspace_bytes(2, _dims(5, 5), 1, 0) == 0
+    # soft partials dominate for many tiles
+    big = lib.ecc_workspace_bytes(2, _dims(512, 512), 32, 128)
+    assert big >= 32 * 128 * 128 * 16
+
+
+INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+
+
+@pytest.mark.parametrize("kw,status,word", [
+    (dict(ndim=4), INVALID, "ndim"),
+    (dict(dims=(0, 4)), INVALID, "dims"),
+    (dict(batch=0), INVALID, "batch"),
+    (dict(batch=70000), UNSUPPORTED, "batch"),
+    (dict(dtype=7), INVALID, "dtype"),
+    (dict(grid=None), INVALID, "grid"),
+    (dict(curve=None), INVALID, "curve"),
+    (dict(bins=0), INVALID, "bins"),
+    (dict(bins=1 << 20), UNSUPPORTED, "bins"),
+    (dict(range=(2.0, 1.0)), INVALID, "range"),
+    (dict(range=(float("nan"), 1.0)), INVALID, "range"),
+    (dict(ws=None), WORKSPACE, "workspace"),
+    (dict(ws_bytes=8), WORKSPACE, "workspace"),
+    (dict(ws=ctypes.c_void_p(0x1004)), WORKSPACE, "aligned"),
+    (dict(grid=ctypes.c_void_p(0x1001), dtype=2), INVALID, "aligned"),
+])
+def test_hard_rejects_bad_arguments(kw, status, word):
+    lib = _lib.load()
+    a = dict(grid=FAKE, ndim=2, dims=(4, 4), batch=1, dtype=0, bins=8, range=None, curve=FAKE, ws=FAKE,
+             ws_bytes=1 << 20)
+    a.update(kw)
+    rng = None if a["range"] is None else (ctypes.c_double * 2)(*a["range"])
+    rc = lib.ecc_hard(a["grid"], a["ndim"], _dims(*a["dims"]), a["batch"], a["dtype"], a["bins"], rng,
+                      a["curve"], a["ws"], a["ws_bytes"], None)
+    assert rc == status
+    assert word in lib.ecc_last_error().decode()
+
+
+def test_hard_rejects_null_dims():
+    lib = _lib.load()
+    rc = lib.ecc_hard(FAKE, 2, None, 1, 0, 8, None, FAKE, FAKE, 1 << 20, None)
+    assert rc == INVALID and "dims" in lib.ecc_last_error().decode()
+
+
+@pytest.mark.parametrize("kw,status,word", [
+    (dict(ndim=1), INVALID, "ndim"),
+    (dict(u=None), INVALID, "u is"),
+    (dict(tau=None), INVALID, "tau"),
+    (dict(T=0), INVALID, "T must"),
+    (dict(T=1 << 20), UNSUPPORTED, "T "),
+    (dict(lam=0.0), INVALID, "lambda"),
+    (dict(lam=float("inf")), INVALID, "lambda"),
+    (dict(alpha=float("nan")), INVALID, "alpha"),
+    (dict(out=None), INVALID, "NULL"),
+    (dict(ws_bytes=16), WORKSPACE, "workspace"),
+])
+def test_soft_rejects_bad_arguments(kw, status, word):
+    lib = _lib.load()
+    a = dict(grid=FAKE, ndim=2, dims=(4, 4), batch=1, u=FAKE, alpha=0.1, tau=FAKE, T=4, lam=2.0, out=FAKE,
+             ws=FAKE, ws_bytes=1 << 20)
+    a.update(kw)
+    rc = lib.ecc_soft_fwd(a["grid"], a["ndim"], _dims(*a["dims"]), a["batch"], a["u"], a["alpha"], a["tau"],
+                          a["T"], a["lam"], a["out"], a["ws"], a["ws_bytes"], None)
+    assert rc == status, lib.ecc_last_error()
+    assert word in lib.ecc_last_error().decode()
+    rc = lib.ecc_soft_bwd(a["grid"], a["ndim"], _dims(*a["dims"]), a["batch"], a["u"], a["alpha"], a["tau"],
+                          a["T"], a["lam"], None, a["out"], None, None, a["ws"], a["ws_bytes"], None)
+    assert rc == status, lib.ecc_last_error()
+
+
+def test_coeff_rejects_bad_arguments():
+    lib = _lib.load()
+    assert lib.ecc_coeff(None, 2, _dims(4, 4), 1, 0, FAKE, None) == INVALID
+    assert lib.ecc_coeff(FAKE, 2, _dims(4, 4), 1, 0, None, None) == INVALID
+    assert lib.ecc_coeff(FAKE, 5, _dims(4, 4), 1, 0, FAKE, None) == INVALID
+
+
+def test_product_package_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2510_20271_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("CPU oracle", ""), f

@@ -1,0 +1,110 @@
+"""GPU parity of the soft single-direction ECC (forward and derivatives)
+against the float64 CPU oracle, through the C ABI.
+
+Tolerance (per output array and batch item): max|gpu - oracle| <= tol *
+max|oracle|, tol = 1e-4 for chi and 1e-3 for each derivative array.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import ecc_oracle as O
+from paper_2510_20271_amd import api, synth
+from tests.gpu_util import dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _close(got, ref, tol, what):
+    got = np.asarray(got, dtype=np.float64)
+    scale = np.max(np.abs(ref))
+    err = np.max(np.abs(got - ref))
+    assert err <= tol * max(scale, 1e-30), f"{what}: err {err:.3e} scale {scale:.3e}"
+
+
+def _run_case(Xb, u, alpha, tau, lam, G):
+    nd = Xb.ndim - 1
+    g, ud, td = dev(Xb), dev(u), dev(tau)
+    chi = host(api.ecc_soft_fwd(g, nd, ud, alpha, td, lam))
+    gx, dt, du = api.ecc_soft_bwd(g, nd, ud, alpha, td, lam, grad_chi=None if G is None else dev(G))
+    gx, dt, du = host(gx), host(dt), host(du)
+    ref_chi = O.soft_fwd_batch(Xb, u, alpha, tau, lam)
+    rgx, rdt, rdu = O.soft_bwd_batch(Xb, u, alpha, tau, lam, G)
+    for i in range(Xb.shape[0]):
+        _close(chi[i], ref_chi[i], 1e-4, f"chi[{i}]")
+        _close(gx[i], rgx[i], 1e-3, f"grad_X[{i}]")
+        _close(dt[i], rdt[i], 1e-3, f"dchi_dtau[{i}]")
+        _close(du[i], rdu[i], 1e-3, f"dchi_du[{i}]")
+    return chi, gx, dt, du
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (1, 9), (9, 1), (7, 13), (64, 64), (100, 259), (45, 2048), (3, 5000)])
+def test_soft_2d_shapes(shape):
+    B, T = 2, 9
+    Xb = np.stack([synth.grf(shape, 1.5, 40 + i) if min(shape) > 1 else
+                   np.random.default_rng(i).standard_normal(shape).astype(np.float32) for i in range(B)])
+    tau = np.linspace(Xb.min() - 0.1, Xb.max() + 0.5, T).astype(np.float32)
+    u = np.array([np.cos(0.3), np.sin(0.3)], np.float32)
+    G = np.random.default_rng(1).standard_normal((B, T)).astype(np.float32)
+    _run_case(Xb, u, np.float32(0.01), tau, np.float32(20.0), G)
+
+
+@pytest.mark.parametrize("shape", [(2, 2, 2), (5, 6, 7), (9, 30, 70), (3, 33, 129)])
+def test_soft_3d_shapes(shape):
+    B, T = 2, 5
+    Xb = np.stack([synth.grf(shape, 1.0, 50 + i) for i in range(B)])
+    tau = np.linspace(Xb.min(), Xb.max() + 1.0, T).astype(np.float32)
+    u = np.array([0.48, -0.6, 0.64], np.float32)
+    G = np.random.default_rng(2).standard_normal((B, T)).astype(np.float32)
+    _run_case(Xb, u, np.float32(0.02), tau, np.float32(8.0), G)
+
+
+def test_soft_dense_coefficients_and_many_thresholds():
+    # white noise: c != 0 on most vertices (full lists), T above one block's width
+    rng = np.random.default_rng(3)
+    Xb = rng.standard_normal((1, 70, 90)).astype(np.float32)
+    tau = np.linspace(-3, 3, 300).astype(np.float32)
+    u = np.array([0.6, 0.8], np.float32)
+    _run_case(Xb, u, np.float32(0.005), tau, np.float32(4.0), None)
+
+
+def test_soft_extreme_arguments_stay_finite():
+    Xb = synth.grf((32, 40), 1.5, 9)[None]
+    tau = np.array([-1e4, -50.0, 0.0, 50.0, 1e4], np.float32)
+    u = np.array([1.0, 0.0], np.float32)
+    chi, gx, dt, du = _run_case(Xb, u, np.float32(0.0), tau, np.float32(30.0), None)
+    assert np.all(np.isfinite(chi)) and np.all(np.isfinite(gx)) and np.all(np.isfinite(dt))
+    np.testing.assert_allclose(chi[0, [0, -1]], [0.0, 1.0], atol=1e-6)
+
+
+def test_soft_large_lambda_matches_hard_curve():
+    X = synth.grf((60, 70), 2.0, 21)
+    vals = np.unique(X)
+    tau = ((vals[:-1] + vals[1:]) / 2)[:: max(1, len(vals) // 50)].astype(np.float32)
+    gaps = np.min(np.abs(tau[:, None].astype(np.float64) - vals[None, :].astype(np.float64)))
+    lam = np.float32(min(60.0 / gaps, 3e7))
+    u = np.array([1.0, 0.0], np.float32)
+    chi = host(api.ecc_soft_fwd(dev(X[None]), 2, dev(u), 0.0, dev(tau), lam))[0]
+    hard = O.ecc_cellmax(X, tau.astype(np.float64))
+    np.testing.assert_allclose(chi, hard, atol=1e-3)
+
+
+def test_soft_optional_outputs_and_determinism():
+    Xb = synth.grf_batch(2, (50, 60), 1.5, 5)
+    p = synth.soft_params_c5(Xb, T=16)
+    g, ud, td = dev(Xb), dev(p["u"]), dev(p["tau"])
+    a = api.ecc_soft_bwd(g, 2, ud, p["alpha"], td, p["lam"])
+    b = api.ecc_soft_bwd(g, 2, ud, p["alpha"], td, p["lam"])
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    c1 = api.ecc_soft_fwd(g, 2, ud, p["alpha"], td, p["lam"])
+    c2 = api.ecc_soft_fwd(g, 2, ud, p["alpha"], td, p["lam"])
+    assert torch.equal(c1, c2)
+
+
+def test_config_c5_full():
+    Xb = synth.config_c5()
+    p = synth.soft_params_c5(Xb)
+    G = synth.upstream_grad(Xb.shape[0], len(p["tau"]))
+    _run_case(Xb, p["u"], p["alpha"], p["tau"], p["lam"], G)
