@@ -135,6 +135,20 @@ int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch
                  const float* grad_chi, float* grad_X, float* dchi_dtau, float* dchi_du,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Measurement aid (not part of the method; Experiments section reports
+ * "kernel execution times"): between ecc_profile_begin() and
+ * ecc_profile_end() every ecc_hard call records a pair of HIP events around
+ * its sweep kernel (the coefficient + histogram pass that dominates the
+ * path) on the call's own stream.  ecc_profile_end() waits for the recorded
+ * events, stores the mean kernel duration in milliseconds and the number of
+ * launches measured, destroys the events and switches recording off.
+ * max_launches in 1..4096; launches beyond it are not recorded.  Host-side
+ * state is process-global: do not use it from two threads at once.
+ */
+int ecc_profile_begin(int max_launches);
+int ecc_profile_end(float* mean_ms /* host */, int* launches /* host */);
+
 #ifdef __cplusplus
 }
 #endif

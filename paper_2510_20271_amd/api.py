@@ -120,3 +120,14 @@ def ecc_soft_bwd(grid, ndim, u, alpha, tau, lam, grad_chi=None, grad_X=None, dch
                                     _ptr(dchi_dtau), _ptr(dchi_du), _ptr(workspace),
                                     workspace.numel(), _stream()))
     return grad_X, dchi_dtau, dchi_du
+
+
+def ecc_profile_begin(max_launches: int = 256):
+    _check(_lib.load().ecc_profile_begin(int(max_launches)))
+
+
+def ecc_profile_end():
+    """Returns (mean sweep-kernel milliseconds, launches measured)."""
+    ms, n = ctypes.c_float(0), ctypes.c_int(0)
+    _check(_lib.load().ecc_profile_end(ctypes.byref(ms), ctypes.byref(n)))
+    return float(ms.value), int(n.value)

@@ -180,4 +180,15 @@ int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch
       "ecc_soft_bwd");
 }
 
+int ecc_profile_begin(int max_launches) {
+  if (max_launches < 1 || max_launches > 4096)
+    return fail(ECC_ERR_INVALID_ARG, "max_launches must be in 1..4096");
+  return device_status(ecc::profile_begin(max_launches), "ecc_profile_begin");
+}
+
+int ecc_profile_end(float* mean_ms, int* launches) {
+  if (!mean_ms || !launches) return fail(ECC_ERR_INVALID_ARG, "output pointer is NULL");
+  return device_status(ecc::profile_end(mean_ms, launches), "ecc_profile_end");
+}
+
 }  // extern "C"

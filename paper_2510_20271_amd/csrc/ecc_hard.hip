@@ -180,6 +180,60 @@ __global__ __launch_bounds__(kBlock) void coeff_kernel(const T* __restrict__ gri
 }
 
 // ---------------------------------------------------------------------------
+// sweep-kernel timing with HIP events on the caller's stream
+// ---------------------------------------------------------------------------
+namespace {
+struct Profile {
+  bool on = false;
+  int cap = 0, used = 0;
+  hipEvent_t* ev = nullptr;  // 2 per launch
+} g_prof;
+}  // namespace
+
+hipError_t profile_begin(int max_launches) {
+  if (g_prof.on) return hipErrorInvalidValue;
+  g_prof.ev = new hipEvent_t[2 * (size_t)max_launches];
+  for (int i = 0; i < 2 * max_launches; ++i) {
+    hipError_t e = hipEventCreate(&g_prof.ev[i]);
+    if (e != hipSuccess) {
+      for (int k = 0; k < i; ++k) (void)hipEventDestroy(g_prof.ev[k]);
+      delete[] g_prof.ev;
+      g_prof.ev = nullptr;
+      return e;
+    }
+  }
+  g_prof.cap = max_launches;
+  g_prof.used = 0;
+  g_prof.on = true;
+  return hipSuccess;
+}
+
+void profile_mark(hipStream_t st, bool after) {
+  if (!g_prof.on || g_prof.used >= g_prof.cap) return;
+  (void)hipEventRecord(g_prof.ev[2 * g_prof.used + (after ? 1 : 0)], st);
+  if (after) ++g_prof.used;
+}
+
+hipError_t profile_end(float* mean_ms, int* launches) {
+  if (!g_prof.on) return hipErrorInvalidValue;
+  hipError_t rc = hipSuccess;
+  double sum = 0.0;
+  for (int i = 0; i < g_prof.used; ++i) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(g_prof.ev[2 * i + 1]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]);
+    if (e != hipSuccess) rc = e;
+    sum += ms;
+  }
+  *launches = g_prof.used;
+  *mean_ms = g_prof.used ? (float)(sum / g_prof.used) : 0.f;
+  for (int i = 0; i < 2 * g_prof.cap; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+  delete[] g_prof.ev;
+  g_prof = Profile();
+  return rc;
+}
+
+// ---------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------
 size_t hard_workspace_bytes(const Shape&, int bins) {
@@ -229,11 +283,13 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     hipLaunchKernelGGL(prepare_kernel, dim3(nb), dim3(kBlock), 0, st, hdr, table, bins,
                        device_range ? 1 : 0, lo, hi, hist, hist_len);
   }
+  profile_mark(st, false);
   switch (dtype) {
     case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;
     case 1: launch_sweep_generic<uint16_t>(grid, s, levels, bins, hdr, table, hist, st); break;
     default: launch_sweep_generic<float>(grid, s, levels, bins, hdr, table, hist, st); break;
   }
+  profile_mark(st, true);
   hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,
                      reinterpret_cast<long long*>(curve), bins);
   return hipGetLastError();

@@ -21,6 +21,11 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
                        double lo, double hi, int64_t* curve, void* ws, hipStream_t st);
 hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st);
 
+// ---- sweep-kernel timing (measurement aid) ----------------------------------
+hipError_t profile_begin(int max_launches);
+hipError_t profile_end(float* mean_ms, int* launches);
+void profile_mark(hipStream_t st, bool after);  // no-op unless recording
+
 // ---- soft path ------------------------------------------------------------
 size_t soft_workspace_bytes(const Shape& s, int T);
 hipError_t launch_soft_fwd(const float* grid, const Shape& s, const float* u, float alpha,
