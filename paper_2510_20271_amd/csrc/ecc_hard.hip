@@ -10,6 +10,8 @@
 #include "ecc_device.h"
 #include "ecc_internal.h"
 
+#include <cstdlib>
+
 namespace ecc {
 
 constexpr int kBlock = 256;
@@ -283,7 +285,12 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     hipLaunchKernelGGL(prepare_kernel, dim3(nb), dim3(kBlock), 0, st, hdr, table, bins,
                        device_range ? 1 : 0, lo, hi, hist, hist_len);
   }
+  // ECC_FORCE_GENERIC=1 routes every shape through the plain one-thread-per-vertex sweep
+  static const bool force_generic = getenv("ECC_FORCE_GENERIC") != nullptr;
   profile_mark(st, false);
+  if (!force_generic && sweep2d_supported(s)) {
+    launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st);
+  } else
   switch (dtype) {
     case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;
     case 1: launch_sweep_generic<uint16_t>(grid, s, levels, bins, hdr, table, hist, st); break;

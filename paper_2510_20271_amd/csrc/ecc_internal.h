@@ -21,6 +21,13 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
                        double lo, double hi, int64_t* curve, void* ws, hipStream_t st);
 hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st);
 
+// fast sweeps (one wave per column strip, lane-mask stencil)
+struct HardHeader;
+bool sweep2d_supported(const Shape& s);
+void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
+                    const HardHeader* hdr, const float* table, unsigned long long* hist,
+                    hipStream_t st);
+
 // ---- sweep-kernel timing (measurement aid) ----------------------------------
 hipError_t profile_begin(int max_launches);
 hipError_t profile_end(float* mean_ms, int* launches);
