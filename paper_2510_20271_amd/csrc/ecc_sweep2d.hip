@@ -2,35 +2,44 @@
 // one wavefront per column strip, marching down the rows.
 //
 // Layout.  A wave owns a strip of 62 output columns; its 64 lanes hold columns
-// xs-1 .. xs+62 (one halo column each side), one float per lane per row, so a
+// xs-1 .. xs+62 (one halo column each side), one value per lane per row, so a
 // row is a single coalesced 256-byte load and the rows of the strip stream
-// through registers (current row, next row, kPF rows in flight).  Nothing is
-// staged in LDS: a vertex is loaded from HBM once per strip plus the 2/62 halo.
+// through registers.  Nothing is staged in LDS: a vertex is read from HBM once
+// per strip plus the 2/62 halo.
 //
-// Stencil on lane masks.  "q comes before p" is a strict "<" towards the four
-// later neighbours (+x, and the three in the next row).  Those four compares
-// give four 64-bit lane masks per row (one bit per column).  The four earlier
-// neighbours need no compare: [q before p] = not [p before q], and
-// [p before q] is the mask the row above / the lane to the left produced for
-// its later neighbour, so they are complements of shifted masks.  Vertices
-// outside the grid read as +inf, which makes every bit that involves them
-// come out right ("never before p") with no boundary masks.
+// Stencil, bit-sliced down the rows.  "q comes before p" is a strict "<"
+// towards the four later neighbours (+x and the three in the next row): the
+// sign bit of the float difference q - p (zeros are made +0 on load so that
+// equal values give +0).  Each lane shifts those sign bits into four 32-bit
+// words, one bit per row, so after 32 rows a lane holds the four later-
+// neighbour relations of 32 vertices of its column.  The four earlier
+// neighbours need no compare: [q before p] = not [p before q], which is the
+// bit the row above (word shifted by one bit) or the lane to the left / right
+// (word moved by one lane) produced for ITS later neighbour.  Vertices outside
+// the grid read as +inf, which makes every bit that involves them come out
+// right ("never before p") with no boundary cases.  All the Boolean work of
+// the coefficient then runs on whole words: 32 vertices per lane per
+// instruction.
 //
-// Coefficient from run starts.  The vertices before p cut the 8-ring around p
+// Coefficient from arc starts.  The vertices before p cut the 8-ring around p
 // into arcs; a diagonal joins its two edge neighbours only if all three come
 // before p.  c(p) = 1 - (#arcs), and an arc starts at edge neighbour k when k
 // comes before p but not both its clockwise predecessors:
 //     start_k = r_k & ~(r_{k-1} & r_{k-2}),   c = 1 - sum_k start_k.
-// Four start masks, a handful of scalar ops on 64 columns at a time.  Lanes
-// with exactly one start have c = 0 (regular vertices: almost all of a smooth
-// field) and never reach the histogram code.
+// Vertices with exactly one start have c = 0 (regular vertices: almost all of
+// a smooth field).  Only the others are walked bit by bit; their value is
+// re-read (an L2 hit) and binned into the block's LDS histogram.
+//
+// A chunk is 32 consecutive rows r0 .. r0+31; the first row only supplies the
+// "row above" bits, rows r0+1 .. r0+31 produce output, and the next chunk
+// starts at r0+31.
 #include "ecc_device.h"
 #include "ecc_internal.h"
 
 namespace ecc {
 
 constexpr int kStripOut = 62;
-constexpr int kPF = 4;  // rows prefetched ahead of the row being compared
+constexpr int kPF = 8;  // rows in flight ahead of the row being compared
 
 __device__ __forceinline__ float lane_from_right(float v) {  // lane i <- lane i+1 (lane 63 <- 0)
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130,
@@ -40,9 +49,36 @@ __device__ __forceinline__ float lane_from_left(float v) {  // lane i <- lane i-
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x138,
                                                                0xf, 0xf, true));
 }
+__device__ __forceinline__ unsigned word_from_right(unsigned v) {
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x130, 0xf, 0xf, true);
+}
+__device__ __forceinline__ unsigned word_from_left(unsigned v) {
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x138, 0xf, 0xf, true);
+}
 __device__ __forceinline__ unsigned long long ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
-__device__ __forceinline__ bool lane_bit(unsigned long long m) {
-  return __builtin_amdgcn_inverse_ballot_w64(m);
+
+// w <- (w << 1) | [q < p]
+__device__ __forceinline__ unsigned push_lt(unsigned w, float q, float p) {
+  return __builtin_amdgcn_alignbit(w, __float_as_uint(q - p), 31);
+}
+__device__ __forceinline__ unsigned push_sign(unsigned w, float d) {
+  return __builtin_amdgcn_alignbit(w, __float_as_uint(d), 31);
+}
+
+// The three differences whose left operand comes from a neighbouring lane, as
+// DPP-modified subtractions (no separate lane move):
+//   dE[i] = cur[i+1] - cur[i], dNE[i] = nxt[i+1] - cur[i], dNW[i] = nxt[i-1] - cur[i].
+// Lanes without a source lane read 0; their bits are never used (halo lanes).
+// The leading s_nop covers the two wait states a DPP read needs after a VALU
+// write of its source register.
+__device__ __forceinline__ void side_differences(float cur, float nxt, float& dE, float& dNE,
+                                                 float& dNW) {
+  asm("s_nop 1\n\t"
+      "v_sub_f32_dpp %0, %3, %3 wave_shl:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_sub_f32_dpp %1, %4, %3 wave_shl:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_sub_f32_dpp %2, %4, %3 wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+      : "=&v"(dE), "=&v"(dNE), "=&v"(dNW)
+      : "v"(cur), "v"(nxt));
 }
 
 template <bool LEVELS, bool TLDS>
@@ -60,88 +96,138 @@ __device__ __forceinline__ void add_to_hist(float v, int c, int bins, float lo, 
   if (b < bins) atomicAdd(&lhist[b], c);
 }
 
-// Rows ya..yb (all inside the grid) are streamed; row r is "current" for
-// r = ya..y1-1 and produces output when r >= y0.  The masks of the row above
-// the first current row start as all ones, which is exact for the grid's first
-// row (no vertex above comes before p) and is overwritten by the warm-up row
-// otherwise.
+// Raw buffer loads: wave-uniform resource + scalar row offset + constant lane
+// offset, so addressing costs no vector instruction, and reads past the end of
+// the item return 0 instead of faulting.
+template <typename T> struct RowLoad;
+template <> struct RowLoad<float> {
+  static __device__ __forceinline__ float get(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+  }
+};
+template <> struct RowLoad<uint16_t> {
+  static __device__ __forceinline__ uint16_t get(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0);
+  }
+};
+template <> struct RowLoad<uint8_t> {
+  static __device__ __forceinline__ uint8_t get(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return (uint8_t)__builtin_amdgcn_raw_buffer_load_b8(r, voff, soff, 0);
+  }
+};
+
+// One strip, output rows y0 .. y1-1 (y0 < y1 <= H).
+//
+// Rows are "current" one after the other; a step pushes the four later-
+// neighbour bits of the current row into the words.  A chunk is up to 32
+// steps; the bits of the row above a chunk's first row are bit 0 of the
+// previous chunk's words (one warm-up step on row y0-1 provides them for the
+// first chunk; above the grid they are all ones, i.e. "never before p").
 template <typename T, bool LEVELS, bool TLDS, bool EDGE>
-__device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int H, int W, int xs, int y0,
-                                            int y1, int bins, float lo, float scale,
+__device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t item_elems, int H, int W,
+                                            int xs, int y0, int y1, int bins, float lo, float scale,
                                             const float* __restrict__ gtable, const float* ltable,
                                             int* lhist) {
   const int lane = threadIdx.x & (kWave - 1);
   const int x = xs + lane;
   const bool inb = !EDGE || (x >= 0 && x < W);
-  const unsigned long long out_mask = ballot(lane >= 1 && lane <= kStripOut && x >= 0 && x < W);
-  const int ya = max(y0 - 1, 0), yb = min(y1, H - 1);
-  const unsigned xoff = EDGE ? (inb ? (unsigned)x : 0u) : (unsigned)lane;
-  const T* base = EDGE ? g : g + xs;   // wave-uniform
-  const T* rowp = base + (int64_t)ya * W;
-  int r = ya;  // row rowp points at
+  const bool out_lane = lane >= 1 && lane <= kStripOut && x >= 0 && x < W;
+  const unsigned voff = (EDGE ? (inb ? (unsigned)x : 0u) : (unsigned)lane) * (unsigned)sizeof(T);
 
-  auto fetch = [&]() -> float {  // value of row r for this lane, then advance (clamped at yb)
-    float v = (float)rowp[xoff];
+  // resource starts at the first streamed row (and at column xs for interior strips)
+  const int ya = max(y0 - 1, 0);
+  const int64_t first = (int64_t)ya * W + (EDGE ? 0 : xs);
+  const int64_t left = (item_elems - first) * (int64_t)sizeof(T);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<T*>(g + first), 0, (int)(left > 0x7fffffff ? 0x7fffffff : left), 0x00020000);
+  const unsigned row_bytes = (unsigned)W * (unsigned)sizeof(T);
+  unsigned soff = 0;  // byte offset of the next row to load
+  auto load_raw = [&]() -> T {
+    const T v = RowLoad<T>::get(rsrc, voff, soff);
+    soff += row_bytes;
+    return v;
+  };
+  auto fix = [&](T raw) -> float {
+    float v = (float)raw;
+    if (sizeof(T) == 4) v += 0.0f;  // -0 -> +0 so that equal values differ by +0
     if (EDGE) v = inb ? v : INFINITY;
-    const bool more = r < yb;  // wave-uniform
-    rowp += more ? W : 0;
-    r += more ? 1 : 0;
     return v;
   };
 
-  float cur = fetch();
-  float nxt = fetch();
-  float pf[kPF];
+  float cur = fix(load_raw());
+  float nxt = fix(load_raw());
+  T pf[kPF];
 #pragma unroll
-  for (int k = 0; k < kPF; ++k) pf[k] = fetch();
-  float curR = lane_from_right(cur);
-  unsigned long long pN = ~0ull, pNE = ~0ull, pNW = ~0ull;
+  for (int k = 0; k < kPF; ++k) pf[k] = load_raw();
 
-  auto step = [&](bool output, bool refill) {
-    const float nxtL = lane_from_left(nxt);
-    const float nxtR = lane_from_right(nxt);
-    const unsigned long long PE = ballot(curR < cur);
-    const unsigned long long PN = ballot(nxt < cur);
-    const unsigned long long PNE = ballot(nxtR < cur);
-    const unsigned long long PNW = ballot(nxtL < cur);
-    if (output) {
-      const unsigned long long sE = PE & ((pNW >> 1) | pN);
-      const unsigned long long sN = PN & ~(PNE & PE);
-      const unsigned long long sW = ~((PE << 1) | (PNW & PN));
-      const unsigned long long sS = ((pNE | PE) << 1) & ~pN;
-      const unsigned long long x1 = sE ^ sN, c1 = sE & sN, x2 = sW ^ sS, c2 = sW & sS;
-      const unsigned long long one = (x1 ^ x2) & ~(c1 | c2);
-      const unsigned long long nz = out_mask & ~one;
-      if (lane_bit(nz)) {
-        const int c = 1 - (int)lane_bit(sE) - (int)lane_bit(sN) - (int)lane_bit(sW) - (int)lane_bit(sS);
-        add_to_hist<LEVELS, TLDS>(cur, c, bins, lo, scale, gtable, ltable, lhist);
-      }
-    }
-    pN = PN;
-    pNE = PNE;
-    pNW = PNW;
+  unsigned wE = 0, wN = 0, wNE = 0, wNW = 0;
+  auto step = [&]() {
+    float dE, dNE, dNW;
+    side_differences(cur, nxt, dE, dNE, dNW);
+    wE = push_sign(wE, dE);
+    wN = push_lt(wN, nxt, cur);
+    wNE = push_sign(wNE, dNE);
+    wNW = push_sign(wNW, dNW);
     cur = nxt;
-    curR = nxtR;
-    nxt = pf[0];
+    nxt = fix(pf[0]);
 #pragma unroll
-    for (int k = 0; k + 1 < kPF; ++k) pf[k] = pf[k + 1];
-    if (refill) pf[kPF - 1] = fetch();
+    for (int q = 0; q + 1 < kPF; ++q) pf[q] = pf[q + 1];
+    pf[kPF - 1] = load_raw();
   };
 
-  int y = ya;
-  if (ya < y0) {  // warm-up row: masks only
-    step(false, true);
-    ++y;
+  unsigned oN = 1, oNE = 1, oNW = 1;  // bit 0: the row above the first output row
+  if (y0 > 0) {
+    step();  // warm-up on row y0-1
+    oN = wN;
+    oNE = wNE;
+    oNW = wNW;
   }
-  // steady state: current rows y .. y1-2 have a real next row
-  for (; y + kPF <= y1 - 1; y += kPF) {
+
+  for (int r = y0; r < y1; r += 32) {
+    const int n = min(32, y1 - r);
+    wE = wN = wNE = wNW = 0;
+    int k = 0;
+    for (; k + kPF <= n; k += kPF) {
 #pragma unroll
-    for (int k = 0; k < kPF; ++k) step(true, true);
+      for (int q = 0; q < kPF; ++q) step();
+    }
+    for (; k < n; ++k) step();
+    if (r + n >= H) {  // the grid's last row has nothing below it
+      wN &= ~1u;
+      wNE &= ~1u;
+      wNW &= ~1u;
+    }
+    const int pad = 32 - n;  // row r+j sits at bit 31-j
+    const unsigned E = wE << pad, N = wN << pad, NE = wNE << pad, NW = wNW << pad;
+
+    // earlier neighbours: the row above is one bit up (bit 31 from the previous
+    // chunk), the side columns are the neighbouring lanes
+    const unsigned pN = __builtin_amdgcn_alignbit(oN, N, 1);
+    const unsigned pNE = __builtin_amdgcn_alignbit(oNE, NE, 1);
+    const unsigned pNW = __builtin_amdgcn_alignbit(oNW, NW, 1);
+    oN = wN;
+    oNE = wNE;
+    oNW = wNW;
+    const unsigned sE = E & (word_from_right(pNW) | pN);
+    const unsigned sN = N & ~(NE & E);
+    const unsigned sW = ~(word_from_left(E) | (NW & N));
+    const unsigned sS = word_from_left(pNE | E) & ~pN;
+    const unsigned x1 = sE ^ sN, c1 = sE & sN, x2 = sW ^ sS, c2 = sW & sS;
+    const unsigned one = (x1 ^ x2) & ~(c1 | c2);
+    const unsigned rows = 0xffffffffu << pad;
+    unsigned nz = out_lane ? (~one & rows) : 0u;
+    while (ballot(nz != 0)) {
+      if (nz != 0) {
+        const int b = 31 - __clz(nz);
+        nz &= ~(1u << b);
+        const int c = 1 - (int)((sE >> b) & 1u) - (int)((sN >> b) & 1u) - (int)((sW >> b) & 1u) -
+                      (int)((sS >> b) & 1u);
+        const int rr = r + 31 - b - ya;  // row relative to the resource
+        const float v = (float)RowLoad<T>::get(rsrc, voff + (unsigned)rr * row_bytes, 0);  // L2 hit
+        add_to_hist<LEVELS, TLDS>(v, c, bins, lo, scale, gtable, ltable, lhist);
+      }
+    }
   }
-  for (; y < y1 - 1; ++y) step(true, true);
-  // last row of the segment: below it is either a real row or the outside
-  if (y1 >= H) nxt = INFINITY;
-  step(true, false);
 }
 
 // Work unit of a wave: (segment of rows) x (strip of columns) of one item;
@@ -170,9 +256,9 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
     const int y1 = min(y0 + rows_per_seg, H);
     const bool edge = (xs < 0) || (xs + kWave > W);
     if (edge)
-      sweep_strip<T, LEVELS, TLDS, true>(g, H, W, xs, y0, y1, bins, lo, scale, table, ltable, lhist);
+      sweep_strip<T, LEVELS, TLDS, true>(g, N, H, W, xs, y0, y1, bins, lo, scale, table, ltable, lhist);
     else
-      sweep_strip<T, LEVELS, TLDS, false>(g, H, W, xs, y0, y1, bins, lo, scale, table, ltable, lhist);
+      sweep_strip<T, LEVELS, TLDS, false>(g, N, H, W, xs, y0, y1, bins, lo, scale, table, ltable, lhist);
   }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
@@ -193,7 +279,12 @@ static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, 
   const int64_t max_seg = (H + 31) / 32;
   if (nseg > max_seg) nseg = max_seg;
   if (nseg < 1) nseg = 1;
-  const int rows_per_seg = (int)((H + nseg - 1) / nseg);
+  // whole chunks of 32 rows per segment; segment + prefetch must stay below 2^31 bytes
+  int64_t rows = ((H + nseg - 1) / nseg + 31) / 32 * 32;
+  const int64_t row_bytes = (int64_t)W * (int64_t)sizeof(T);
+  const int64_t cap = ((((int64_t)1 << 31) / row_bytes - 16) / 32) * 32;
+  if (rows > cap) rows = cap;
+  const int rows_per_seg = (int)rows;
   nseg = (H + rows_per_seg - 1) / rows_per_seg;
   const int units = nstrip * (int)nseg;
   dim3 g((unsigned)((units + 3) / 4), (unsigned)s.batch);
@@ -210,7 +301,7 @@ static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, 
 }
 
 bool sweep2d_supported(const Shape& s) {
-  return s.D == 1 && s.W >= 8 && s.W <= (1 << 30) && s.H <= (1 << 30);
+  return s.D == 1 && s.W >= 8 && s.W <= (1 << 22) && s.H <= (1 << 30);
 }
 
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
