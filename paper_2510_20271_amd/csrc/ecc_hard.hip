@@ -290,6 +290,8 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
   profile_mark(st, false);
   if (!force_generic && sweep2d_supported(s)) {
     launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st);
+  } else if (!force_generic && sweep3d_supported(s)) {
+    launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st);
   } else
   switch (dtype) {
     case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;

@@ -28,6 +28,11 @@ void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, in
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st);
 
+bool sweep3d_supported(const Shape& s);
+void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
+                    const HardHeader* hdr, const float* table, unsigned long long* hist,
+                    hipStream_t st);
+
 // ---- sweep-kernel timing (measurement aid) ----------------------------------
 hipError_t profile_begin(int max_launches);
 hipError_t profile_end(float* mean_ms, int* launches);

@@ -1,0 +1,468 @@
+// 3D sweep for gfx950: coefficient c(p) (Eq. 3 of the paper) + LDS histogram.
+//
+// Layout.  A wave owns a tube of 62 output columns (64 lanes: one halo column
+// each side) x R output rows (plus one halo row above and below) and marches
+// through the planes z.  One plane step loads R+2 rows of 256 bytes, each a
+// single coalesced buffer load; values live in registers, nothing is staged in
+// LDS.  A vertex is read from HBM once per tube, plus the halo.
+//
+// Stencil, bit-sliced along z.  "q comes before p" is a strict "<" towards the
+// 13 later neighbours of p (+x; the three in the next row; the nine in the next
+// plane) and is the sign bit of the float difference q - p (zeros are made +0
+// on load).  Every lane shifts each of those sign bits into its own 32-bit
+// word, one bit per plane, so a word holds one neighbour relation for 32
+// consecutive vertices of the lane's column.  The 13 earlier neighbours need
+// no compare: [q before p] = not [p before q], which is the word that q's
+// column holds for ITS later neighbour p -- a word of another row (register),
+// of a side column (one lane over), or of the plane below (one bit up).
+// Vertices outside the grid read as +inf, so every bit that involves them comes
+// out as "never before p".  All Boolean work then runs on whole words: 32
+// vertices per lane per instruction.
+//
+// Coefficient.  With a = ring of the 8 in-plane neighbours before p, up / dn =
+// rings of the planes above / below, up0 / dn0 = the vertices straight above /
+// below:   c = ring(a) - up0 ring(a & up) - dn0 ring(a & dn),
+// ring(m) = 1 - #arcs(m), an arc starting at edge neighbour k when
+// m_k & ~(m_{k-1} & m_{k-2}).  Hence c = P - Q with
+//   P = 1 + arcs(a & up)[up0] + arcs(a & dn)[dn0],   Q = arcs(a) + up0 + dn0,
+// both summed with bit-sliced full adders.  Only vertices with P != Q (the
+// critical ones) are walked bit by bit; their value is re-read (an L2 hit) and
+// binned into the block's LDS histogram.
+//
+// A chunk is up to 31 planes.  Bit 31 of the next-plane words belongs to the
+// plane below the chunk's first plane (replayed from registers, or all ones
+// below the grid).
+#include "ecc_device.h"
+#include "ecc_internal.h"
+
+namespace ecc {
+
+namespace s3 {
+
+constexpr int kOut = 62;   // output columns per wave
+constexpr int kChunk = 31;  // output planes per chunk
+
+__device__ __forceinline__ unsigned from_right(unsigned v) {  // lane i <- lane i+1
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x130, 0xf, 0xf, true);
+}
+__device__ __forceinline__ unsigned from_left(unsigned v) {  // lane i <- lane i-1
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x138, 0xf, 0xf, true);
+}
+__device__ __forceinline__ unsigned long long ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+// w <- (w << 1) | signbit(d)
+__device__ __forceinline__ unsigned push(unsigned w, float d) {
+  return __builtin_amdgcn_alignbit(w, __float_as_uint(d), 31);
+}
+// Differences with the left operand taken from the lane to the right / left:
+//   dr[i] = q[i+1] - p[i],  dl[i] = q[i-1] - p[i].
+// DPP-modified subtractions; lanes without a source lane read 0 (their bits
+// belong to halo lanes and are never used).  The s_nop covers the two wait
+// states a DPP read needs after a VALU write of its source register.
+__device__ __forceinline__ void diff_sides(float q, float p, float& dr, float& dl) {
+  asm("s_nop 1\n\t"
+      "v_sub_f32_dpp %0, %2, %3 wave_shl:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_sub_f32_dpp %1, %2, %3 wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+      : "=&v"(dr), "=&v"(dl)
+      : "v"(q), "v"(p));
+}
+__device__ __forceinline__ float diff_right(float q, float p) {
+  float dr;
+  asm("s_nop 1\n\t"
+      "v_sub_f32_dpp %0, %1, %2 wave_shl:1 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+      : "=&v"(dr)
+      : "v"(q), "v"(p));
+  return dr;
+}
+
+__device__ __forceinline__ unsigned xor3(unsigned a, unsigned b, unsigned c) { return a ^ b ^ c; }
+__device__ __forceinline__ unsigned maj3(unsigned a, unsigned b, unsigned c) {
+  return (a & b) | (c & (a | b));
+}
+
+template <typename T> struct Load;
+template <> struct Load<float> {
+  static __device__ __forceinline__ float get(__amdgpu_buffer_rsrc_t r, unsigned v, unsigned s) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, v, s, 0));
+  }
+};
+template <> struct Load<uint16_t> {
+  static __device__ __forceinline__ uint16_t get(__amdgpu_buffer_rsrc_t r, unsigned v, unsigned s) {
+    return (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, v, s, 0);
+  }
+};
+template <> struct Load<uint8_t> {
+  static __device__ __forceinline__ uint8_t get(__amdgpu_buffer_rsrc_t r, unsigned v, unsigned s) {
+    return (uint8_t)__builtin_amdgcn_raw_buffer_load_b8(r, v, s, 0);
+  }
+};
+
+// index of the next-plane word for the neighbour (a, b) of a centre
+__device__ __forceinline__ constexpr int ui(int a, int b) { return (b + 1) * 3 + (a + 1); }
+
+template <int R>
+struct Words {
+  unsigned E[R + 2];                          // centre rows 1..R
+  unsigned N[R + 2], NE[R + 2], NW[R + 2];    // centre rows 0..R (towards row +1)
+  unsigned U[R + 2][9];                       // centre rows 0..R+1 (towards the plane above)
+};
+
+// Is the next-plane relation (centre row jc, neighbour row offset b) needed?
+template <int R>
+__device__ __forceinline__ constexpr bool need_u(int jc, int b) {
+  return (jc >= 1 && jc <= R) || (jc == 0 && b == 1) || (jc == R + 1 && b == -1);
+}
+
+// Push the next-plane bits of plane v (centres) against plane u.
+template <int R>
+__device__ __forceinline__ void push_up(Words<R>& w, const float (&v)[R + 2], const float (&u)[R + 2]) {
+#pragma unroll
+  for (int jc = 0; jc <= R + 1; ++jc) {
+#pragma unroll
+    for (int b = -1; b <= 1; ++b) {
+      if (!need_u<R>(jc, b)) continue;
+      const int jq = jc + b;
+      float dr, dl;
+      diff_sides(u[jq], v[jc], dr, dl);
+      w.U[jc][ui(0, b)] = push(w.U[jc][ui(0, b)], u[jq] - v[jc]);
+      w.U[jc][ui(1, b)] = push(w.U[jc][ui(1, b)], dr);
+      w.U[jc][ui(-1, b)] = push(w.U[jc][ui(-1, b)], dl);
+    }
+  }
+}
+
+// Push the in-plane bits of plane v.
+template <int R>
+__device__ __forceinline__ void push_plane(Words<R>& w, const float (&v)[R + 2]) {
+#pragma unroll
+  for (int jc = 0; jc <= R; ++jc) {
+    if (jc >= 1) w.E[jc] = push(w.E[jc], diff_right(v[jc], v[jc]));
+    float dr, dl;
+    diff_sides(v[jc + 1], v[jc], dr, dl);
+    w.N[jc] = push(w.N[jc], v[jc + 1] - v[jc]);
+    w.NE[jc] = push(w.NE[jc], dr);
+    w.NW[jc] = push(w.NW[jc], dl);
+  }
+}
+
+// Bit-sliced P = 1 + sum of 8 bits (4-bit result), Q = sum of 6 bits (3-bit result);
+// returns the word of vertices with P != Q and the slices for later extraction.
+struct Slices {
+  unsigned p0, p1, p2, p3, q0, q1, q2;
+};
+__device__ __forceinline__ unsigned count_pq(const unsigned (&s)[8], const unsigned (&t)[6], Slices& o) {
+  const unsigned x1 = xor3(s[0], s[1], s[2]), c1 = maj3(s[0], s[1], s[2]);
+  const unsigned x2 = xor3(s[3], s[4], s[5]), c2 = maj3(s[3], s[4], s[5]);
+  const unsigned x3 = ~(s[6] ^ s[7]), c3 = s[6] | s[7];  // third input is the constant 1
+  o.p0 = xor3(x1, x2, x3);
+  const unsigned c4 = maj3(x1, x2, x3);
+  const unsigned y1 = xor3(c1, c2, c3), d1 = maj3(c1, c2, c3);
+  o.p1 = y1 ^ c4;
+  const unsigned d2 = y1 & c4;
+  o.p2 = d1 ^ d2;
+  o.p3 = d1 & d2;
+  const unsigned u1 = xor3(t[0], t[1], t[2]), e1 = maj3(t[0], t[1], t[2]);
+  const unsigned u2 = xor3(t[3], t[4], t[5]), e2 = maj3(t[3], t[4], t[5]);
+  o.q0 = u1 ^ u2;
+  const unsigned e3 = u1 & u2;
+  o.q1 = xor3(e1, e2, e3);
+  o.q2 = maj3(e1, e2, e3);
+  return (o.p0 ^ o.q0) | (o.p1 ^ o.q1) | (o.p2 ^ o.q2) | o.p3;
+}
+
+// arcs of the ring m (order E, NE, N, NW, W, SW, S, SE), gated by g
+__device__ __forceinline__ void arc_starts(const unsigned (&m)[8], unsigned g, unsigned* out) {
+  out[0] = g & m[0] & ~(m[7] & m[6]);
+  out[1] = g & m[2] & ~(m[1] & m[0]);
+  out[2] = g & m[4] & ~(m[3] & m[2]);
+  out[3] = g & m[6] & ~(m[5] & m[4]);
+}
+
+template <bool LEVELS, bool TLDS>
+__device__ __forceinline__ void add_to_hist(float v, int c, int bins, float lo, float scale,
+                                            const float* __restrict__ gtable, const float* ltable,
+                                            int* lhist) {
+  int b;
+  if (LEVELS) {
+    b = (v < (float)bins) ? (int)v : bins;
+  } else if (TLDS) {
+    b = bin_from_table(v, ltable, bins, lo, scale);
+  } else {
+    b = bin_from_table(v, gtable, bins, lo, scale);
+  }
+  if (b < bins) atomicAdd(&lhist[b], c);
+}
+
+// One tube: columns xs .. xs+63 (outputs xs+1 .. xs+62), output rows
+// yb .. yb+R-1, output planes z0 .. z1-1.  SAFE: some lane or row of the tube
+// lies outside the grid (those read as +inf).
+template <typename T, int R, bool LEVELS, bool TLDS, bool SAFE>
+__device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item_elems, int D, int H,
+                                           int W, int xs, int yb, int z0, int z1, int bins, float lo,
+                                           float scale, const float* __restrict__ gtable,
+                                           const float* ltable, int* lhist) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int x = xs + lane;
+  const bool inb = !SAFE || (x >= 0 && x < W);
+  const bool out_lane = lane >= 1 && lane <= kOut && x >= 0 && x < W;
+  const unsigned voff = (SAFE ? (inb ? (unsigned)x : 0u) : (unsigned)lane) * (unsigned)sizeof(T);
+
+  // resource starts at plane zs = max(z0-1, 0), row 0, column xs (0 for SAFE tubes)
+  const int zs = max(z0 - 1, 0);
+  const int64_t plane = (int64_t)H * W;
+  const int64_t first = (int64_t)zs * plane + (SAFE ? 0 : xs);
+  const int64_t left = (item_elems - first) * (int64_t)sizeof(T);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<T*>(g + first), 0, (int)(left > 0x7fffffff ? 0x7fffffff : left), 0x00020000);
+  const unsigned plane_bytes = (unsigned)(plane * (int64_t)sizeof(T));
+  unsigned roff[R + 2];  // byte offset of tube row j inside a plane (clamped into the grid)
+  bool rok[R + 2];       // row j is inside the grid
+#pragma unroll
+  for (int j = 0; j <= R + 1; ++j) {
+    const int y = yb - 1 + j;
+    rok[j] = y >= 0 && y < H;
+    roff[j] = (unsigned)min(max(y, 0), H - 1) * (unsigned)W * (unsigned)sizeof(T);
+  }
+  unsigned poff = 0;  // byte offset of the next plane to load
+  auto load_plane = [&](T (&raw)[R + 2]) {
+#pragma unroll
+    for (int j = 0; j <= R + 1; ++j) raw[j] = Load<T>::get(rsrc, voff, poff + roff[j]);
+    poff += plane_bytes;
+  };
+  auto fix = [&](float (&dst)[R + 2], const T (&raw)[R + 2]) {
+#pragma unroll
+    for (int j = 0; j <= R + 1; ++j) {
+      float f = (float)raw[j];
+      if (sizeof(T) == 4) f += 0.0f;  // -0 -> +0 so that equal values differ by +0
+      if (SAFE) f = (inb && rok[j]) ? f : INFINITY;
+      dst[j] = f;
+    }
+  };
+
+  Words<R> w;
+  float v[R + 2], u[R + 2];
+  T rawa[R + 2], rawb[R + 2];  // two planes in flight
+  // first planes of the stream
+  {
+    T r0[R + 2];
+    load_plane(r0);
+    load_plane(rawa);
+    load_plane(rawb);
+    fix(v, r0);
+  }
+  // bit 0 of the next-plane words <- relations between plane z0-1 and plane z0
+#pragma unroll
+  for (int jc = 0; jc <= R + 1; ++jc)
+#pragma unroll
+    for (int q = 0; q < 9; ++q) w.U[jc][q] = 1u;  // below the grid: "never before p" after complement
+  if (z0 > 0) {
+    // v = plane z0-1, next = plane z0
+    fix(u, rawa);
+#pragma unroll
+    for (int j = 0; j <= R + 1; ++j) rawa[j] = rawb[j];
+    load_plane(rawb);
+    push_up<R>(w, v, u);
+#pragma unroll
+    for (int j = 0; j <= R + 1; ++j) v[j] = u[j];
+  }
+  // now v = plane z0; rawa = plane z0+1, rawb = plane z0+2 (in flight)
+
+  float keep[R + 2];  // plane below v, for the replay at a chunk boundary
+  for (int z = z0; z < z1; z += kChunk) {
+    const int n = min(kChunk, z1 - z);
+    if (z > z0) {  // replay: next-plane bits of the plane below this chunk
+#pragma unroll
+      for (int jc = 0; jc <= R + 1; ++jc)
+#pragma unroll
+        for (int q = 0; q < 9; ++q) w.U[jc][q] = 0u;
+      push_up<R>(w, keep, v);
+    }
+#pragma unroll
+    for (int j = 0; j <= R + 1; ++j) w.E[j] = w.N[j] = w.NE[j] = w.NW[j] = 0u;
+    for (int k = 0; k < n; ++k) {
+      fix(u, rawa);
+#pragma unroll
+      for (int j = 0; j <= R + 1; ++j) rawa[j] = rawb[j];
+      load_plane(rawb);
+      push_plane<R>(w, v);
+      push_up<R>(w, v, u);
+#pragma unroll
+      for (int j = 0; j <= R + 1; ++j) {
+        keep[j] = v[j];
+        v[j] = u[j];
+      }
+    }
+    if (z + n >= D) {  // the grid's last plane has nothing above it
+#pragma unroll
+      for (int jc = 1; jc <= R; ++jc)
+#pragma unroll
+        for (int q = 0; q < 9; ++q) w.U[jc][q] &= ~1u;
+    }
+    // plane z+i sits at bit n-1-i of every word; the plane below the chunk at bit n of U
+    const unsigned planes = (n >= 32) ? 0xffffffffu : ((1u << n) - 1u);
+
+#pragma unroll
+    for (int j = 1; j <= R; ++j) {
+      // in-plane ring of row j: E NE N NW W SW S SE
+      unsigned a[8];
+      a[0] = w.E[j];
+      a[1] = w.NE[j];
+      a[2] = w.N[j];
+      a[3] = w.NW[j];
+      a[4] = ~from_left(w.E[j]);
+      a[5] = ~from_left(w.NE[j - 1]);
+      a[6] = ~w.N[j - 1];
+      a[7] = ~from_right(w.NW[j - 1]);
+      // plane above: relation of (x+a, j+b, z+1) to p
+      unsigned mu[8];
+      mu[0] = a[0] & w.U[j][ui(1, 0)];
+      mu[1] = a[1] & w.U[j][ui(1, 1)];
+      mu[2] = a[2] & w.U[j][ui(0, 1)];
+      mu[3] = a[3] & w.U[j][ui(-1, 1)];
+      mu[4] = a[4] & w.U[j][ui(-1, 0)];
+      mu[5] = a[5] & w.U[j][ui(-1, -1)];
+      mu[6] = a[6] & w.U[j][ui(0, -1)];
+      mu[7] = a[7] & w.U[j][ui(1, -1)];
+      const unsigned up0 = w.U[j][ui(0, 0)];
+      // plane below: neighbour (x+a, j+b, z-1) comes before p unless p came before it,
+      // which is the word of that neighbour's column towards (-a, -b, +1), one plane down
+      unsigned md[8];
+      md[0] = a[0] & ~(from_right(w.U[j][ui(-1, 0)]) >> 1);
+      md[1] = a[1] & ~(from_right(w.U[j + 1][ui(-1, -1)]) >> 1);
+      md[2] = a[2] & ~(w.U[j + 1][ui(0, -1)] >> 1);
+      md[3] = a[3] & ~(from_left(w.U[j + 1][ui(1, -1)]) >> 1);
+      md[4] = a[4] & ~(from_left(w.U[j][ui(1, 0)]) >> 1);
+      md[5] = a[5] & ~(from_left(w.U[j - 1][ui(1, 1)]) >> 1);
+      md[6] = a[6] & ~(w.U[j - 1][ui(0, 1)] >> 1);
+      md[7] = a[7] & ~(from_right(w.U[j - 1][ui(-1, 1)]) >> 1);
+      const unsigned dn0 = ~(w.U[j][ui(0, 0)] >> 1);
+
+      unsigned s[8], t[6];
+      arc_starts(mu, up0, &s[0]);
+      arc_starts(md, dn0, &s[4]);
+      arc_starts(a, 0xffffffffu, &t[0]);
+      t[4] = up0;
+      t[5] = dn0;
+      Slices sl;
+      unsigned nz = count_pq(s, t, sl) & planes;
+      const bool row_ok = !SAFE || rok[j];
+      if (!(out_lane && row_ok)) nz = 0u;
+      while (ballot(nz != 0)) {
+        if (nz != 0) {
+          const int b = 31 - __clz(nz);
+          nz &= ~(1u << b);
+          const int P = (int)((sl.p0 >> b) & 1u) + 2 * (int)((sl.p1 >> b) & 1u) +
+                        4 * (int)((sl.p2 >> b) & 1u) + 8 * (int)((sl.p3 >> b) & 1u);
+          const int Q = (int)((sl.q0 >> b) & 1u) + 2 * (int)((sl.q1 >> b) & 1u) +
+                        4 * (int)((sl.q2 >> b) & 1u);
+          const int zr = z + (n - 1 - b) - zs;  // plane relative to the resource
+          const float val = (float)Load<T>::get(rsrc, voff + (unsigned)zr * plane_bytes + roff[j], 0);
+          add_to_hist<LEVELS, TLDS>(val, P - Q, bins, lo, scale, gtable, ltable, lhist);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace s3
+
+// Work unit of a wave: (z segment, row group, column strip) of one item;
+// blockIdx.y is the item; the four waves of a block take consecutive row groups
+// of one strip, so their halo rows meet in the CU's vector cache.
+template <typename T, int R, bool LEVELS, bool TLDS>
+__global__ __launch_bounds__(256) void sweep3d_kernel(
+    const T* __restrict__ grid, int D, int H, int W, int64_t N, int bins, int nstrip, int ngroup,
+    int nseg, int planes_per_seg, const HardHeader* __restrict__ hdr,
+    const float* __restrict__ table, unsigned long long* __restrict__ hist) {
+  extern __shared__ int smem[];
+  int* lhist = smem;
+  float* ltable = reinterpret_cast<float*>(smem + bins);
+  for (int b = threadIdx.x; b < bins; b += 256) {
+    lhist[b] = 0;
+    if (TLDS) ltable[b] = table[b];
+  }
+  __syncthreads();
+  float lo = 0.f, scale = 0.f;
+  if (!LEVELS) { lo = hdr->lo; scale = hdr->scale; }
+  const T* g = grid + (int64_t)blockIdx.y * N;
+  // unit = ((seg * nstrip) + strip) * ngroup4 + group, group fastest
+  const int ngroup4 = (ngroup + 3) & ~3;
+  const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform
+  const int group = unit % ngroup4;
+  const int rest = unit / ngroup4;
+  const int strip = rest % nstrip;
+  const int seg = rest / nstrip;
+  if (group < ngroup && seg < nseg) {
+    const int xs = strip * s3::kOut - 1;
+    const int yb = group * R;
+    const int z0 = seg * planes_per_seg;
+    const int z1 = min(z0 + planes_per_seg, D);
+    const bool safe = (xs < 0) || (xs + kWave > W) || (yb == 0) || (yb + R + 1 > H);
+    if (safe)
+      s3::sweep_tube<T, R, LEVELS, TLDS, true>(g, N, D, H, W, xs, yb, z0, z1, bins, lo, scale, table,
+                                               ltable, lhist);
+    else
+      s3::sweep_tube<T, R, LEVELS, TLDS, false>(g, N, D, H, W, xs, yb, z0, z1, bins, lo, scale, table,
+                                                ltable, lhist);
+  }
+  __syncthreads();
+  unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
+  for (int b = threadIdx.x; b < bins; b += 256) {
+    const int v = lhist[b];
+    if (v != 0) atomicAdd(&out[b], (unsigned long long)(long long)v);
+  }
+}
+
+constexpr int kRows3d = 4;
+
+template <typename T>
+static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
+                       const float* table, unsigned long long* hist, hipStream_t st) {
+  constexpr int R = kRows3d;
+  const int D = (int)s.D, H = (int)s.H, W = (int)s.W;
+  const int nstrip = (W + s3::kOut - 1) / s3::kOut;
+  const int ngroup = (H + R - 1) / R;
+  const int ngroup4 = (ngroup + 3) & ~3;
+  const int64_t per_seg = (int64_t)nstrip * ngroup * s.batch;
+  int64_t nseg = (8192 + per_seg - 1) / per_seg;
+  const int64_t max_seg = (D + s3::kChunk - 1) / s3::kChunk;
+  if (nseg > max_seg) nseg = max_seg;
+  if (nseg < 1) nseg = 1;
+  // whole chunks per segment; segment + planes in flight must stay below 2^31 bytes
+  int64_t planes = ((D + nseg - 1) / nseg + s3::kChunk - 1) / s3::kChunk * s3::kChunk;
+  const int64_t plane_bytes = (int64_t)H * W * (int64_t)sizeof(T);
+  const int64_t cap = ((((int64_t)1 << 31) / plane_bytes - 6) / s3::kChunk) * s3::kChunk;
+  if (planes > cap) planes = cap;
+  const int planes_per_seg = (int)planes;
+  nseg = (D + planes_per_seg - 1) / planes_per_seg;
+  const int64_t units = nseg * nstrip * ngroup4;
+  dim3 g((unsigned)(units / 4), (unsigned)s.batch);
+  const bool tlds = !levels && (size_t)bins * 8 <= 48 * 1024;
+  const size_t lds = (size_t)bins * (tlds ? 8 : 4);
+  const T* p = static_cast<const T*>(grid);
+#define ECC_GO(LV, TL)                                                                              \
+  hipLaunchKernelGGL((sweep3d_kernel<T, R, LV, TL>), g, dim3(256), lds, st, p, D, H, W, s.N, bins, \
+                     nstrip, ngroup, (int)nseg, planes_per_seg, hdr, table, hist)
+  if (levels) ECC_GO(true, false);
+  else if (tlds) ECC_GO(false, true);
+  else ECC_GO(false, false);
+#undef ECC_GO
+}
+
+bool sweep3d_supported(const Shape& s) {
+  // a plane must fit 37 times in 2^31 bytes (31-plane chunk + planes in flight), worst element size 4
+  return s.ndim == 3 && s.D >= 2 && s.W >= 8 && s.W <= (1 << 22) && s.H <= (1 << 22) &&
+         s.H * s.W * 4 * 37 < ((int64_t)1 << 31) && s.D <= (1 << 30);
+}
+
+void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
+                    const HardHeader* hdr, const float* table, unsigned long long* hist,
+                    hipStream_t st) {
+  switch (dtype) {
+    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;
+    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st); break;
+    default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st); break;
+  }
+}
+
+}  // namespace ecc
