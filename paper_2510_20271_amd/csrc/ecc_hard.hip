@@ -288,7 +288,7 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
   // ECC_FORCE_GENERIC=1 routes every shape through the plain one-thread-per-vertex sweep
   static const bool force_generic = getenv("ECC_FORCE_GENERIC") != nullptr;
   profile_mark(st, false);
-  if (!force_generic && sweep2d_supported(s)) {
+  if (!force_generic && sweep2d_supported(s, bins)) {
     launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st);
   } else if (!force_generic && sweep3d_supported(s)) {
     launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st);

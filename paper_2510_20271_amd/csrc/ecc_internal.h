@@ -23,7 +23,7 @@ hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_o
 
 // fast sweeps (one wave per column strip, lane-mask stencil)
 struct HardHeader;
-bool sweep2d_supported(const Shape& s);
+bool sweep2d_supported(const Shape& s, int bins);
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st);
