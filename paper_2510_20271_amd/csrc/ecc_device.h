@@ -111,4 +111,61 @@ __device__ __forceinline__ int bin_from_table(float x, const float* __restrict__
 
 template <typename T> __device__ __forceinline__ float as_float(T v) { return (float)v; }
 
+// ---- critical-vertex queue of a wave ----------------------------------------
+// Critical vertices (c != 0) turn up a few lanes at a time.  Instead of running
+// the binning code with most lanes idle, a wave appends (value, c) to a small
+// LDS queue (lane-compacted with a ballot) and drains it 64 entries at a time
+// with every lane busy.
+struct HistSink {  // drain target: the block's LDS histogram
+  int* lhist;
+  const float* table;  // float[bins] thresholds (LDS or global), unused for LEVELS
+  int bins;
+  float lo, scale;
+};
+
+template <bool LEVELS>
+__device__ __forceinline__ void sink_add(const HistSink& s, float v, int c) {
+  int b;
+  if (LEVELS) b = (v < (float)s.bins) ? (int)v : s.bins;
+  else b = bin_from_table(v, s.table, s.bins, s.lo, s.scale);
+  if (b < s.bins) atomicAdd(&s.lhist[b], c);
+}
+
+constexpr int kQueueCap = 128;  // entries per wave (float2 each)
+
+template <bool LEVELS>
+struct WaveQueue {
+  float2* buf;  // wave-private LDS, kQueueCap entries
+  int count;    // wave-uniform
+  HistSink sink;
+
+  __device__ __forceinline__ void drain64() {
+    const int lane = threadIdx.x & (kWave - 1);
+    const float2 e = buf[lane];
+    sink_add<LEVELS>(sink, e.x, __float_as_int(e.y));
+    const int rest = count - kWave;  // < 64
+    float2 m = make_float2(0.f, 0.f);
+    if (lane < rest) m = buf[lane + kWave];
+    if (lane < rest) buf[lane] = m;
+    count = rest;
+  }
+  // every lane calls; `active` lanes append (v, c)
+  __device__ __forceinline__ void push(bool active, float v, int c) {
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(active);
+    const int idx = count + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
+                                                           __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+    if (active) buf[idx] = make_float2(v, __int_as_float(c));
+    count += __builtin_popcountll(m);
+    if (count >= kWave) drain64();
+  }
+  __device__ __forceinline__ void flush() {
+    const int lane = threadIdx.x & (kWave - 1);
+    if (lane < count) {
+      const float2 e = buf[lane];
+      sink_add<LEVELS>(sink, e.x, __float_as_int(e.y));
+    }
+    count = 0;
+  }
+};
+
 }  // namespace ecc

@@ -73,21 +73,6 @@ __device__ __forceinline__ void lane_edge_differences(float cur_first, float cur
       : "v"(cur_first), "v"(cur_last), "v"(nxt_first), "v"(nxt_last));
 }
 
-template <bool LEVELS, bool TLDS>
-__device__ __forceinline__ void add_to_hist(float v, int c, int bins, float lo, float scale,
-                                            const float* __restrict__ gtable, const float* ltable,
-                                            int* lhist) {
-  int b;
-  if (LEVELS) {
-    b = (v < (float)bins) ? (int)v : bins;
-  } else if (TLDS) {
-    b = bin_from_table(v, ltable, bins, lo, scale);
-  } else {
-    b = bin_from_table(v, gtable, bins, lo, scale);
-  }
-  if (b < bins) atomicAdd(&lhist[b], c);
-}
-
 // Raw buffer loads: wave-uniform resource + scalar row offset + constant lane
 // offset, so addressing costs no vector instruction, and reads past the end of
 // the item return 0 instead of faulting.
@@ -171,11 +156,10 @@ template <typename T> struct RowRegs<T, true> {
 // of the previous chunk's words (one warm-up step on row y0-1 provides them
 // for the first chunk; above the grid they are all ones, i.e. "never before
 // p" once complemented).
-template <typename T, bool LEVELS, bool TLDS, bool EDGE>
+template <typename T, bool LEVELS, bool EDGE>
 __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t item_elems, int H, int W,
-                                            int c0, int y0, int y1, int bins, float lo, float scale,
-                                            const float* __restrict__ gtable, const float* ltable,
-                                            int* lhist, float* ring /* [kChunkRows][64][kNC] */) {
+                                            int c0, int y0, int y1, WaveQueue<LEVELS>& queue,
+                                            float* ring /* [kChunkRows][64][kNC] */) {
   const int lane = threadIdx.x & (kWave - 1);
   bool ok[kNC];         // column inside the grid
   unsigned voff[kNC];   // byte offset of the column inside a row (clamped into the row)
@@ -312,17 +296,17 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
       const unsigned one = (x1 ^ x2) & ~(c1 | c2);
       unsigned nz = (out_lane && ok[e]) ? (~one & rows) : 0u;
       while (ballot(nz != 0)) {
-        if (nz != 0) {
-          const int b = 31 - __clz(nz);
-          nz &= ~(1u << b);
-          const int c = 1 - (int)((sE >> b) & 1u) - (int)((sN >> b) & 1u) - (int)((sW >> b) & 1u) -
-                        (int)((sS >> b) & 1u);
-          const float v = ring[((31 - b) * kWave + lane) * kNC + e];
-          add_to_hist<LEVELS, TLDS>(v, c, bins, lo, scale, gtable, ltable, lhist);
-        }
+        const bool active = nz != 0;
+        const int b = active ? 31 - __clz(nz) : 0;
+        nz &= ~(1u << b);
+        const int c = 1 - (int)((sE >> b) & 1u) - (int)((sN >> b) & 1u) - (int)((sW >> b) & 1u) -
+                      (int)((sS >> b) & 1u);
+        const float v = ring[((31 - b) * kWave + lane) * kNC + e];
+        queue.push(active, v, c);
       }
     }
   }
+  queue.flush();
 }
 
 // Work unit of a wave: (segment of rows) x (strip of columns) of one item;
@@ -333,9 +317,11 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
     const HardHeader* __restrict__ hdr, const float* __restrict__ table,
     unsigned long long* __restrict__ hist) {
   extern __shared__ int smem[];
-  // [4 waves][kChunkRows][64][kNC] floats of value ring, then the histogram, then the table
-  float* ring = reinterpret_cast<float*>(smem) + (threadIdx.x >> 6) * (kChunkRows * kWave * kNC);
-  int* lhist = smem + 4 * kChunkRows * kWave * kNC;
+  // [4 waves][kChunkRows][64][kNC] floats of value ring, [4 waves] queues, histogram, table
+  const int wv = threadIdx.x >> 6;
+  float* ring = reinterpret_cast<float*>(smem) + wv * (kChunkRows * kWave * kNC);
+  float2* qbuf = reinterpret_cast<float2*>(smem + 4 * kChunkRows * kWave * kNC) + wv * kQueueCap;
+  int* lhist = smem + 4 * kChunkRows * kWave * kNC + 4 * kQueueCap * 2;
   float* ltable = reinterpret_cast<float*>(lhist + bins);
   for (int b = threadIdx.x; b < bins; b += 256) {
     lhist[b] = 0;
@@ -354,10 +340,18 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
     // 4-element loads need every column in the grid and 4-element alignment of the rows
     const bool edge = (c0 < 0) || (c0 + kNC * kWave > W) || (W % kNC != 0) ||
                       ((reinterpret_cast<uintptr_t>(g) & (kNC * sizeof(T) - 1)) != 0);
+    WaveQueue<LEVELS> queue;
+    queue.buf = qbuf;
+    queue.count = 0;
+    queue.sink.lhist = lhist;
+    queue.sink.table = TLDS ? ltable : table;
+    queue.sink.bins = bins;
+    queue.sink.lo = lo;
+    queue.sink.scale = scale;
     if (edge)
-      sweep_strip<T, LEVELS, TLDS, true>(g, N, H, W, c0, y0, y1, bins, lo, scale, table, ltable, lhist, ring);
+      sweep_strip<T, LEVELS, true>(g, N, H, W, c0, y0, y1, queue, ring);
     else
-      sweep_strip<T, LEVELS, TLDS, false>(g, N, H, W, c0, y0, y1, bins, lo, scale, table, ltable, lhist, ring);
+      sweep_strip<T, LEVELS, false>(g, N, H, W, c0, y0, y1, queue, ring);
   }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
@@ -387,7 +381,7 @@ static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, 
   nseg = (H + rows_per_seg - 1) / rows_per_seg;
   const int units = nstrip * (int)nseg;
   dim3 g((unsigned)((units + 3) / 4), (unsigned)s.batch);
-  const size_t ring_bytes = (size_t)4 * kChunkRows * kWave * kNC * sizeof(float);
+  const size_t ring_bytes = (size_t)4 * kChunkRows * kWave * kNC * sizeof(float) + 4 * kQueueCap * sizeof(float2);
   const bool tlds = !levels && (size_t)bins * 8 + ring_bytes <= 64 * 1024;
   const size_t lds = ring_bytes + (size_t)bins * (tlds ? 8 : 4);
   const T* p = static_cast<const T*>(grid);
@@ -401,8 +395,8 @@ static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, 
 }
 
 bool sweep2d_supported(const Shape& s, int bins) {
-  // value ring (32 KiB) + histogram must fit the 64 KiB of LDS a block may ask for
-  return bins <= 8192 && s.D == 1 && s.W >= 8 && s.W <= (1 << 22) && s.H <= (1 << 30);
+  // value ring (32 KiB) + queues (4 KiB) + histogram must fit the 64 KiB of LDS a block may ask for
+  return bins <= 7168 && s.D == 1 && s.W >= 8 && s.W <= (1 << 22) && s.H <= (1 << 30);
 }
 
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
