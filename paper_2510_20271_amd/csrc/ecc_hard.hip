@@ -290,7 +290,7 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
   profile_mark(st, false);
   if (!force_generic && sweep2d_supported(s, bins)) {
     launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st);
-  } else if (!force_generic && sweep3d_supported(s)) {
+  } else if (!force_generic && sweep3d_supported(s, bins)) {
     launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st);
   } else
   switch (dtype) {

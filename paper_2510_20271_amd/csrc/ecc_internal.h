@@ -28,7 +28,7 @@ void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, in
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st);
 
-bool sweep3d_supported(const Shape& s);
+bool sweep3d_supported(const Shape& s, int bins);
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st);

@@ -29,7 +29,7 @@
 // critical ones) are walked bit by bit; their value is re-read (an L2 hit) and
 // binned into the block's LDS histogram.
 //
-// A chunk is up to 31 planes.  Bit 31 of the next-plane words belongs to the
+// A chunk is up to 30 planes.  The top bit of the next-plane words belongs to the
 // plane below the chunk's first plane (replayed from registers, or all ones
 // below the grid).
 #include "ecc_device.h"
@@ -40,7 +40,7 @@ namespace ecc {
 namespace s3 {
 
 constexpr int kOut = 62;   // output columns per wave
-constexpr int kChunk = 31;  // output planes per chunk
+constexpr int kChunk = 30;  // output planes per chunk (even: the two plane buffers swap roles each step)
 
 __device__ __forceinline__ unsigned from_right(unsigned v) {  // lane i <- lane i+1
   return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x130, 0xf, 0xf, true);
@@ -178,29 +178,13 @@ __device__ __forceinline__ void arc_starts(const unsigned (&m)[8], unsigned g, u
   out[3] = g & m[6] & ~(m[5] & m[4]);
 }
 
-template <bool LEVELS, bool TLDS>
-__device__ __forceinline__ void add_to_hist(float v, int c, int bins, float lo, float scale,
-                                            const float* __restrict__ gtable, const float* ltable,
-                                            int* lhist) {
-  int b;
-  if (LEVELS) {
-    b = (v < (float)bins) ? (int)v : bins;
-  } else if (TLDS) {
-    b = bin_from_table(v, ltable, bins, lo, scale);
-  } else {
-    b = bin_from_table(v, gtable, bins, lo, scale);
-  }
-  if (b < bins) atomicAdd(&lhist[b], c);
-}
-
 // One tube: columns xs .. xs+63 (outputs xs+1 .. xs+62), output rows
 // yb .. yb+R-1, output planes z0 .. z1-1.  SAFE: some lane or row of the tube
 // lies outside the grid (those read as +inf).
-template <typename T, int R, bool LEVELS, bool TLDS, bool SAFE>
+template <typename T, int R, bool LEVELS, bool SAFE>
 __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item_elems, int D, int H,
-                                           int W, int xs, int yb, int z0, int z1, int bins, float lo,
-                                           float scale, const float* __restrict__ gtable,
-                                           const float* ltable, int* lhist) {
+                                           int W, int xs, int yb, int z0, int z1,
+                                           WaveQueue<LEVELS>& queue) {
   const int lane = threadIdx.x & (kWave - 1);
   const int x = xs + lane;
   const bool inb = !SAFE || (x >= 0 && x < W);
@@ -240,15 +224,16 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
   };
 
   Words<R> w;
-  float v[R + 2], u[R + 2];
-  T rawa[R + 2], rawb[R + 2];  // two planes in flight
-  // first planes of the stream
+  // Two plane buffers swap the roles "current plane" / "plane above" every step,
+  // and two raw buffers swap the roles "next to convert" / "in flight".
+  float pa[R + 2], pb[R + 2];
+  T rawx[R + 2], rawy[R + 2];
   {
     T r0[R + 2];
     load_plane(r0);
-    load_plane(rawa);
-    load_plane(rawb);
-    fix(v, r0);
+    load_plane(rawx);
+    load_plane(rawy);
+    fix(pa, r0);
   }
   // bit 0 of the next-plane words <- relations between plane z0-1 and plane z0
 #pragma unroll
@@ -256,41 +241,43 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 #pragma unroll
     for (int q = 0; q < 9; ++q) w.U[jc][q] = 1u;  // below the grid: "never before p" after complement
   if (z0 > 0) {
-    // v = plane z0-1, next = plane z0
-    fix(u, rawa);
+    // pa = plane z0-1, rawx = plane z0
+    fix(pb, rawx);
 #pragma unroll
-    for (int j = 0; j <= R + 1; ++j) rawa[j] = rawb[j];
-    load_plane(rawb);
-    push_up<R>(w, v, u);
+    for (int j = 0; j <= R + 1; ++j) rawx[j] = rawy[j];
+    load_plane(rawy);
+    push_up<R>(w, pa, pb);
 #pragma unroll
-    for (int j = 0; j <= R + 1; ++j) v[j] = u[j];
+    for (int j = 0; j <= R + 1; ++j) pa[j] = pb[j];
   }
-  // now v = plane z0; rawa = plane z0+1, rawb = plane z0+2 (in flight)
+  // now pa = plane z0; rawx = plane z0+1, rawy = plane z0+2 (in flight)
 
-  float keep[R + 2];  // plane below v, for the replay at a chunk boundary
   for (int z = z0; z < z1; z += kChunk) {
     const int n = min(kChunk, z1 - z);
-    if (z > z0) {  // replay: next-plane bits of the plane below this chunk
+    if (z > z0) {  // replay: next-plane bits of the plane below this chunk (pb) against pa
 #pragma unroll
       for (int jc = 0; jc <= R + 1; ++jc)
 #pragma unroll
         for (int q = 0; q < 9; ++q) w.U[jc][q] = 0u;
-      push_up<R>(w, keep, v);
+      push_up<R>(w, pb, pa);
     }
 #pragma unroll
     for (int j = 0; j <= R + 1; ++j) w.E[j] = w.N[j] = w.NE[j] = w.NW[j] = 0u;
-    for (int k = 0; k < n; ++k) {
-      fix(u, rawa);
-#pragma unroll
-      for (int j = 0; j <= R + 1; ++j) rawa[j] = rawb[j];
-      load_plane(rawb);
-      push_plane<R>(w, v);
-      push_up<R>(w, v, u);
-#pragma unroll
-      for (int j = 0; j <= R + 1; ++j) {
-        keep[j] = v[j];
-        v[j] = u[j];
-      }
+    int k = 0;
+    for (; k + 2 <= n; k += 2) {
+      fix(pb, rawx);  // plane above pa
+      load_plane(rawx);
+      push_plane<R>(w, pa);
+      push_up<R>(w, pa, pb);
+      fix(pa, rawy);  // plane above pb
+      load_plane(rawy);
+      push_plane<R>(w, pb);
+      push_up<R>(w, pb, pa);
+    }
+    if (k < n) {  // odd tail: only in the last chunk of the segment
+      fix(pb, rawx);
+      push_plane<R>(w, pa);
+      push_up<R>(w, pa, pb);
     }
     if (z + n >= D) {  // the grid's last plane has nothing above it
 #pragma unroll
@@ -348,20 +335,21 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
       const bool row_ok = !SAFE || rok[j];
       if (!(out_lane && row_ok)) nz = 0u;
       while (ballot(nz != 0)) {
-        if (nz != 0) {
-          const int b = 31 - __clz(nz);
-          nz &= ~(1u << b);
-          const int P = (int)((sl.p0 >> b) & 1u) + 2 * (int)((sl.p1 >> b) & 1u) +
-                        4 * (int)((sl.p2 >> b) & 1u) + 8 * (int)((sl.p3 >> b) & 1u);
-          const int Q = (int)((sl.q0 >> b) & 1u) + 2 * (int)((sl.q1 >> b) & 1u) +
-                        4 * (int)((sl.q2 >> b) & 1u);
-          const int zr = z + (n - 1 - b) - zs;  // plane relative to the resource
-          const float val = (float)Load<T>::get(rsrc, voff + (unsigned)zr * plane_bytes + roff[j], 0);
-          add_to_hist<LEVELS, TLDS>(val, P - Q, bins, lo, scale, gtable, ltable, lhist);
-        }
+        const bool active = nz != 0;
+        const int b = active ? 31 - __clz(nz) : 0;
+        nz &= ~(1u << b);
+        const int P = (int)((sl.p0 >> b) & 1u) + 2 * (int)((sl.p1 >> b) & 1u) +
+                      4 * (int)((sl.p2 >> b) & 1u) + 8 * (int)((sl.p3 >> b) & 1u);
+        const int Q = (int)((sl.q0 >> b) & 1u) + 2 * (int)((sl.q1 >> b) & 1u) +
+                      4 * (int)((sl.q2 >> b) & 1u);
+        const int zr = z + (n - 1 - b) - zs;  // plane relative to the resource
+        float val = 0.f;
+        if (active) val = (float)Load<T>::get(rsrc, voff + (unsigned)zr * plane_bytes + roff[j], 0);
+        queue.push(active, val, P - Q);
       }
     }
   }
+  queue.flush();
 }
 
 }  // namespace s3
@@ -375,8 +363,9 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
     int nseg, int planes_per_seg, const HardHeader* __restrict__ hdr,
     const float* __restrict__ table, unsigned long long* __restrict__ hist) {
   extern __shared__ int smem[];
-  int* lhist = smem;
-  float* ltable = reinterpret_cast<float*>(smem + bins);
+  float2* qbuf = reinterpret_cast<float2*>(smem) + (threadIdx.x >> 6) * kQueueCap;
+  int* lhist = smem + 4 * kQueueCap * 2;
+  float* ltable = reinterpret_cast<float*>(lhist + bins);
   for (int b = threadIdx.x; b < bins; b += 256) {
     lhist[b] = 0;
     if (TLDS) ltable[b] = table[b];
@@ -398,12 +387,18 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
     const int z0 = seg * planes_per_seg;
     const int z1 = min(z0 + planes_per_seg, D);
     const bool safe = (xs < 0) || (xs + kWave > W) || (yb == 0) || (yb + R + 1 > H);
+    WaveQueue<LEVELS> queue;
+    queue.buf = qbuf;
+    queue.count = 0;
+    queue.sink.lhist = lhist;
+    queue.sink.table = TLDS ? ltable : table;
+    queue.sink.bins = bins;
+    queue.sink.lo = lo;
+    queue.sink.scale = scale;
     if (safe)
-      s3::sweep_tube<T, R, LEVELS, TLDS, true>(g, N, D, H, W, xs, yb, z0, z1, bins, lo, scale, table,
-                                               ltable, lhist);
+      s3::sweep_tube<T, R, LEVELS, true>(g, N, D, H, W, xs, yb, z0, z1, queue);
     else
-      s3::sweep_tube<T, R, LEVELS, TLDS, false>(g, N, D, H, W, xs, yb, z0, z1, bins, lo, scale, table,
-                                                ltable, lhist);
+      s3::sweep_tube<T, R, LEVELS, false>(g, N, D, H, W, xs, yb, z0, z1, queue);
   }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
@@ -437,8 +432,9 @@ static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, 
   nseg = (D + planes_per_seg - 1) / planes_per_seg;
   const int64_t units = nseg * nstrip * ngroup4;
   dim3 g((unsigned)(units / 4), (unsigned)s.batch);
-  const bool tlds = !levels && (size_t)bins * 8 <= 48 * 1024;
-  const size_t lds = (size_t)bins * (tlds ? 8 : 4);
+  const size_t qbytes = (size_t)4 * kQueueCap * sizeof(float2);
+  const bool tlds = !levels && (size_t)bins * 8 + qbytes <= 60 * 1024;
+  const size_t lds = qbytes + (size_t)bins * (tlds ? 8 : 4);
   const T* p = static_cast<const T*>(grid);
 #define ECC_GO(LV, TL)                                                                              \
   hipLaunchKernelGGL((sweep3d_kernel<T, R, LV, TL>), g, dim3(256), lds, st, p, D, H, W, s.N, bins, \
@@ -449,9 +445,9 @@ static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, 
 #undef ECC_GO
 }
 
-bool sweep3d_supported(const Shape& s) {
+bool sweep3d_supported(const Shape& s, int bins) {
   // a plane must fit 37 times in 2^31 bytes (31-plane chunk + planes in flight), worst element size 4
-  return s.ndim == 3 && s.D >= 2 && s.W >= 8 && s.W <= (1 << 22) && s.H <= (1 << 22) &&
+  return bins <= 15360 && s.ndim == 3 && s.D >= 2 && s.W >= 8 && s.W <= (1 << 22) && s.H <= (1 << 22) &&
          s.H * s.W * 4 * 37 < ((int64_t)1 << 31) && s.D <= (1 << 30);
 }
 
