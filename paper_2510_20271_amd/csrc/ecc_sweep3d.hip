@@ -29,9 +29,9 @@
 // critical ones) are walked bit by bit; their value is re-read (an L2 hit) and
 // binned into the block's LDS histogram.
 //
-// A chunk is up to 30 planes.  The top bit of the next-plane words belongs to the
-// plane below the chunk's first plane (replayed from registers, or all ones
-// below the grid).
+// A chunk is up to 30 planes; the words keep shifting across chunks, so the bit
+// above a chunk's first plane is the last plane of the previous chunk (all ones
+// below the grid: "never before p" once complemented).
 #include "ecc_device.h"
 #include "ecc_internal.h"
 
@@ -252,17 +252,13 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
   }
   // now pa = plane z0; rawx = plane z0+1, rawy = plane z0+2 (in flight)
 
+#pragma unroll
+  for (int j = 0; j <= R + 1; ++j) w.E[j] = w.N[j] = w.NE[j] = w.NW[j] = 0u;
   for (int z = z0; z < z1; z += kChunk) {
     const int n = min(kChunk, z1 - z);
-    if (z > z0) {  // replay: next-plane bits of the plane below this chunk (pb) against pa
-#pragma unroll
-      for (int jc = 0; jc <= R + 1; ++jc)
-#pragma unroll
-        for (int q = 0; q < 9; ++q) w.U[jc][q] = 0u;
-      push_up<R>(w, pb, pa);
-    }
-#pragma unroll
-    for (int j = 0; j <= R + 1; ++j) w.E[j] = w.N[j] = w.NE[j] = w.NW[j] = 0u;
+    // The words are shift registers that are never cleared: after the n pushes of
+    // this chunk, bit i holds plane z+n-1-i, so bit n of a next-plane word still
+    // holds the relation of the plane below the chunk's first plane.
     int k = 0;
     for (; k + 2 <= n; k += 2) {
       fix(pb, rawx);  // plane above pa
