@@ -40,6 +40,7 @@ namespace ecc {
 namespace s3 {
 
 constexpr int kOut = 62;   // output columns per wave
+constexpr int kXchWords = 9;  // halo words a wave publishes per chunk
 constexpr int kChunk = 30;  // output planes per chunk (even: the two plane buffers swap roles each step)
 
 __device__ __forceinline__ unsigned from_right(unsigned v) {  // lane i <- lane i+1
@@ -115,9 +116,12 @@ __device__ __forceinline__ constexpr bool need_u(int jc, int b) {
 
 // Push the next-plane bits of plane v (centres) against plane u.
 template <int R>
-__device__ __forceinline__ void push_up(Words<R>& w, const float (&v)[R + 2], const float (&u)[R + 2]) {
+__device__ __forceinline__ void push_up(Words<R>& w, const float (&v)[R + 2], const float (&u)[R + 2],
+                                        bool skip_top, bool skip_bottom) {
 #pragma unroll
   for (int jc = 0; jc <= R + 1; ++jc) {
+    if (jc == 0 && skip_top) continue;         // wave-uniform: the wave above supplies these words
+    if (jc == R + 1 && skip_bottom) continue;  // the wave below supplies them
 #pragma unroll
     for (int b = -1; b <= 1; ++b) {
       if (!need_u<R>(jc, b)) continue;
@@ -133,9 +137,10 @@ __device__ __forceinline__ void push_up(Words<R>& w, const float (&v)[R + 2], co
 
 // Push the in-plane bits of plane v.
 template <int R>
-__device__ __forceinline__ void push_plane(Words<R>& w, const float (&v)[R + 2]) {
+__device__ __forceinline__ void push_plane(Words<R>& w, const float (&v)[R + 2], bool skip_top) {
 #pragma unroll
   for (int jc = 0; jc <= R; ++jc) {
+    if (jc == 0 && skip_top) continue;  // wave-uniform: the wave above supplies these words
     if (jc >= 1) w.E[jc] = push(w.E[jc], diff_right(v[jc], v[jc]));
     float dr, dl;
     diff_sides(v[jc + 1], v[jc], dr, dl);
@@ -181,10 +186,11 @@ __device__ __forceinline__ void arc_starts(const unsigned (&m)[8], unsigned g, u
 // One tube: columns xs .. xs+63 (outputs xs+1 .. xs+62), output rows
 // yb .. yb+R-1, output planes z0 .. z1-1.  SAFE: some lane or row of the tube
 // lies outside the grid (those read as +inf).
-template <typename T, int R, bool LEVELS, bool SAFE>
+template <typename T, int R, bool LEVELS, bool SAFE, bool SKIP_TOP, bool SKIP_BOTTOM>
 __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item_elems, int D, int H,
                                            int W, int xs, int yb, int z0, int z1,
-                                           WaveQueue<LEVELS>& queue) {
+                                           WaveQueue<LEVELS>& queue, unsigned* xch) {
+  constexpr bool skip_top = SKIP_TOP, skip_bottom = SKIP_BOTTOM;
   const int lane = threadIdx.x & (kWave - 1);
   const int x = xs + lane;
   const bool inb = !SAFE || (x >= 0 && x < W);
@@ -246,7 +252,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 #pragma unroll
     for (int j = 0; j <= R + 1; ++j) rawx[j] = rawy[j];
     load_plane(rawy);
-    push_up<R>(w, pa, pb);
+    push_up<R>(w, pa, pb, false, false);
 #pragma unroll
     for (int j = 0; j <= R + 1; ++j) pa[j] = pb[j];
   }
@@ -263,17 +269,50 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
     for (; k + 2 <= n; k += 2) {
       fix(pb, rawx);  // plane above pa
       load_plane(rawx);
-      push_plane<R>(w, pa);
-      push_up<R>(w, pa, pb);
+      push_plane<R>(w, pa, skip_top);
+      push_up<R>(w, pa, pb, skip_top, skip_bottom);
       fix(pa, rawy);  // plane above pb
       load_plane(rawy);
-      push_plane<R>(w, pb);
-      push_up<R>(w, pb, pa);
+      push_plane<R>(w, pb, skip_top);
+      push_up<R>(w, pb, pa, skip_top, skip_bottom);
     }
     if (k < n) {  // odd tail: only in the last chunk of the segment
       fix(pb, rawx);
-      push_plane<R>(w, pa);
-      push_up<R>(w, pa, pb);
+      push_plane<R>(w, pa, skip_top);
+      push_up<R>(w, pa, pb, skip_top, skip_bottom);
+    }
+    // Halo words: the waves of a block own consecutive row groups, so the words a
+    // wave would compute for its halo rows are words its neighbours hold for their
+    // own first / last row.  Swap them through LDS (double-buffered by chunk
+    // parity, one barrier per chunk) instead of computing them twice.
+    {
+      const int wv = threadIdx.x >> 6;
+      unsigned* mine = xch + (((z - z0) / kChunk & 1) * 4 + wv) * (kXchWords * kWave) + lane;
+      mine[0 * kWave] = w.N[R];
+      mine[1 * kWave] = w.NE[R];
+      mine[2 * kWave] = w.NW[R];
+      mine[3 * kWave] = w.U[R][ui(-1, 1)];
+      mine[4 * kWave] = w.U[R][ui(0, 1)];
+      mine[5 * kWave] = w.U[R][ui(1, 1)];
+      mine[6 * kWave] = w.U[1][ui(-1, -1)];
+      mine[7 * kWave] = w.U[1][ui(0, -1)];
+      mine[8 * kWave] = w.U[1][ui(1, -1)];
+      __syncthreads();
+      if (skip_top) {
+        const unsigned* up = mine - kXchWords * kWave;
+        w.N[0] = up[0 * kWave];
+        w.NE[0] = up[1 * kWave];
+        w.NW[0] = up[2 * kWave];
+        w.U[0][ui(-1, 1)] = up[3 * kWave];
+        w.U[0][ui(0, 1)] = up[4 * kWave];
+        w.U[0][ui(1, 1)] = up[5 * kWave];
+      }
+      if (skip_bottom) {
+        const unsigned* dn = mine + kXchWords * kWave;
+        w.U[R + 1][ui(-1, -1)] = dn[6 * kWave];
+        w.U[R + 1][ui(0, -1)] = dn[7 * kWave];
+        w.U[R + 1][ui(1, -1)] = dn[8 * kWave];
+      }
     }
     if (z + n >= D) {  // the grid's last plane has nothing above it
 #pragma unroll
@@ -359,8 +398,10 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
     int nseg, int planes_per_seg, const HardHeader* __restrict__ hdr,
     const float* __restrict__ table, unsigned long long* __restrict__ hist) {
   extern __shared__ int smem[];
-  float2* qbuf = reinterpret_cast<float2*>(smem) + (threadIdx.x >> 6) * kQueueCap;
-  int* lhist = smem + 4 * kQueueCap * 2;
+  // [2][4 waves][9][64] exchange words, [4 waves] queues, histogram, table
+  unsigned* xch = reinterpret_cast<unsigned*>(smem);
+  float2* qbuf = reinterpret_cast<float2*>(smem + 2 * 4 * s3::kXchWords * kWave) + (threadIdx.x >> 6) * kQueueCap;
+  int* lhist = smem + 2 * 4 * s3::kXchWords * kWave + 4 * kQueueCap * 2;
   float* ltable = reinterpret_cast<float*>(lhist + bins);
   for (int b = threadIdx.x; b < bins; b += 256) {
     lhist[b] = 0;
@@ -377,11 +418,14 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
   const int rest = unit / ngroup4;
   const int strip = rest % nstrip;
   const int seg = rest / nstrip;
+  const int z0 = seg * planes_per_seg;
+  const int z1 = min(z0 + planes_per_seg, D);
   if (group < ngroup && seg < nseg) {
     const int xs = strip * s3::kOut - 1;
     const int yb = group * R;
-    const int z0 = seg * planes_per_seg;
-    const int z1 = min(z0 + planes_per_seg, D);
+    // the four waves of a block are four consecutive row groups of one strip and segment
+    const bool skip_top = (unit & 3) != 0;
+    const bool skip_bottom = (unit & 3) != 3 && group + 1 < ngroup;
     const bool safe = (xs < 0) || (xs + kWave > W) || (yb == 0) || (yb + R + 1 > H);
     WaveQueue<LEVELS> queue;
     queue.buf = qbuf;
@@ -391,10 +435,20 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
     queue.sink.bins = bins;
     queue.sink.lo = lo;
     queue.sink.scale = scale;
+    // tubes touching the grid boundary compute their own halo words (one variant fewer)
     if (safe)
-      s3::sweep_tube<T, R, LEVELS, true>(g, N, D, H, W, xs, yb, z0, z1, queue);
+      s3::sweep_tube<T, R, LEVELS, true, false, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
+    else if (skip_top && skip_bottom)
+      s3::sweep_tube<T, R, LEVELS, false, true, true>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
+    else if (skip_top)
+      s3::sweep_tube<T, R, LEVELS, false, true, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
+    else if (skip_bottom)
+      s3::sweep_tube<T, R, LEVELS, false, false, true>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
     else
-      s3::sweep_tube<T, R, LEVELS, false>(g, N, D, H, W, xs, yb, z0, z1, queue);
+      s3::sweep_tube<T, R, LEVELS, false, false, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
+  } else {
+    // a wave without a row group still meets the block's one barrier per chunk
+    for (int z = z0; z < z1; z += s3::kChunk) __syncthreads();
   }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
@@ -428,7 +482,7 @@ static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, 
   nseg = (D + planes_per_seg - 1) / planes_per_seg;
   const int64_t units = nseg * nstrip * ngroup4;
   dim3 g((unsigned)(units / 4), (unsigned)s.batch);
-  const size_t qbytes = (size_t)4 * kQueueCap * sizeof(float2);
+  const size_t qbytes = (size_t)4 * kQueueCap * sizeof(float2) + (size_t)2 * 4 * s3::kXchWords * kWave * 4;
   const bool tlds = !levels && (size_t)bins * 8 + qbytes <= 60 * 1024;
   const size_t lds = qbytes + (size_t)bins * (tlds ? 8 : 4);
   const T* p = static_cast<const T*>(grid);
@@ -443,7 +497,7 @@ static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, 
 
 bool sweep3d_supported(const Shape& s, int bins) {
   // a plane must fit 37 times in 2^31 bytes (31-plane chunk + planes in flight), worst element size 4
-  return bins <= 15360 && s.ndim == 3 && s.D >= 2 && s.W >= 8 && s.W <= (1 << 22) && s.H <= (1 << 22) &&
+  return bins <= 10240 && s.ndim == 3 && s.D >= 2 && s.W >= 8 && s.W <= (1 << 22) && s.H <= (1 << 22) &&
          s.H * s.W * 4 * 37 < ((int64_t)1 << 31) && s.D <= (1 << 30);
 }
 
