@@ -48,7 +48,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--quick", action="store_true", help="skip the extra workloads and the CPU baseline")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'c2', 'c4' or 'c5' steps, no JSON extras")
+    ap.add_argument("--only", default="", help="profiling aid: run only 'c2', 'c4', 'c5' or 'calib' (a plain 1 GiB copy), no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path shards by batch item / "
@@ -62,6 +62,15 @@ def main():
     _lib.load()  # fails loudly when the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.only == "calib":
+        # counter calibration: a plain device copy of exactly 1 GiB read + 1 GiB written per launch
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("[bench] calib: copied 1 GiB x %d" % args.steps)
+        return
     BINS = 1024
     extra = {}
 
