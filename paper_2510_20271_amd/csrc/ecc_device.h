@@ -80,12 +80,14 @@ __device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int6
 
 // ---- bins -----------------------------------------------------------------
 // Header at the start of the workspace of ecc_hard, followed by the threshold
-// table (float[bins]) at byte offset kTableOffset.
+// table (float[bins]) at byte offset kTableOffset, the per-item list counters and
+// the per-item lists of critical vertices (single-pass mode).
 struct HardHeader {
   unsigned min_key;  // order-preserving uint encodings of the batch min / max
   unsigned max_key;
   float lo;          // float(lo) used for the bin guess
   float scale;       // bins / (hi - lo), 0 when hi <= lo
+  unsigned overflow; // single-pass mode: a critical-vertex list ran out of room
 };
 constexpr size_t kTableOffset = 256;
 
@@ -116,33 +118,60 @@ template <typename T> __device__ __forceinline__ float as_float(T v) { return (f
 // the binning code with most lanes idle, a wave appends (value, c) to a small
 // LDS queue (lane-compacted with a ballot) and drains it 64 entries at a time
 // with every lane busy.
+template <bool LEVELS>
 struct HistSink {  // drain target: the block's LDS histogram
+  static constexpr bool kTrackRange = false;
   int* lhist;
   const float* table;  // float[bins] thresholds (LDS or global), unused for LEVELS
   int bins;
   float lo, scale;
+  // every lane calls; `active` lanes hold an entry, n = number of entries (wave-uniform)
+  __device__ __forceinline__ void take(float2 e, bool active, int) const {
+    if (!active) return;
+    const float v = e.x;
+    int b;
+    if (LEVELS) b = (v < (float)bins) ? (int)v : bins;
+    else b = bin_from_table(v, table, bins, lo, scale);
+    if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
+  }
 };
 
-template <bool LEVELS>
-__device__ __forceinline__ void sink_add(const HistSink& s, float v, int c) {
-  int b;
-  if (LEVELS) b = (v < (float)s.bins) ? (int)v : s.bins;
-  else b = bin_from_table(v, s.table, s.bins, s.lo, s.scale);
-  if (b < s.bins) atomicAdd(&s.lhist[b], c);
-}
+// Drain target of the single-pass mode: the item's list of critical vertices in
+// the workspace (value, c).  A wave reserves n slots with one atomic; when the
+// list is full the overflow flag is raised and the entries are dropped (the
+// caller then runs the two-pass path instead).
+constexpr unsigned kSubLists = 32;  // lists per item: spreads the slot-reservation atomics
+
+struct ListSink {
+  static constexpr bool kTrackRange = true;
+  float2* list;       // this block's sub-list
+  unsigned* counter;  // its fill count
+  unsigned cap;       // entries per sub-list
+  unsigned* overflow;
+  __device__ __forceinline__ void take(float2 e, bool active, int n) const {
+    const int lane = threadIdx.x & (kWave - 1);
+    unsigned base = 0;
+    if (lane == 0) base = atomicAdd(counter, (unsigned)n);
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (base + (unsigned)n <= cap) {
+      if (active) list[base + lane] = e;
+    } else if (lane == 0) {
+      atomicOr(overflow, 1u);
+    }
+  }
+};
 
 constexpr int kQueueCap = 128;  // entries per wave (float2 each)
 
-template <bool LEVELS>
+template <typename Sink>
 struct WaveQueue {
   float2* buf;  // wave-private LDS, kQueueCap entries
   int count;    // wave-uniform
-  HistSink sink;
+  Sink sink;
 
   __device__ __forceinline__ void drain64() {
     const int lane = threadIdx.x & (kWave - 1);
-    const float2 e = buf[lane];
-    sink_add<LEVELS>(sink, e.x, __float_as_int(e.y));
+    sink.take(buf[lane], true, kWave);
     const int rest = count - kWave;  // < 64
     float2 m = make_float2(0.f, 0.f);
     if (lane < rest) m = buf[lane + kWave];
@@ -160,11 +189,43 @@ struct WaveQueue {
   }
   __device__ __forceinline__ void flush() {
     const int lane = threadIdx.x & (kWave - 1);
-    if (lane < count) {
-      const float2 e = buf[lane];
-      sink_add<LEVELS>(sink, e.x, __float_as_int(e.y));
+    if (count > 0) {  // wave-uniform
+      float2 e = make_float2(0.f, 0.f);
+      if (lane < count) e = buf[lane];
+      sink.take(e, lane < count, count);
     }
     count = 0;
+  }
+};
+
+// Running min / max of the values a wave has seen (single-pass mode); merged
+// into the header with ordered-uint atomics when the wave is done.
+struct WaveRange {
+  float lo = INFINITY, hi = -INFINITY;
+  __device__ __forceinline__ void add(float v) {
+    lo = fminf(lo, v);
+    hi = fmaxf(hi, v);
+  }
+  __device__ __forceinline__ void add_if(float v, bool ok) {
+    lo = fminf(lo, ok ? v : INFINITY);
+    hi = fmaxf(hi, ok ? v : -INFINITY);
+  }
+  __device__ __forceinline__ void commit(HardHeader* h) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      lo = fminf(lo, __shfl_xor(lo, o));
+      hi = fmaxf(hi, __shfl_xor(hi, o));
+    }
+    // Thousands of waves meet here; atomics on one address serialise in the L2, so
+    // only a wave that would improve the value it reads issues one (a stale read can
+    // only cause a needless atomic, never a missed one).
+    if ((threadIdx.x & (kWave - 1)) == 0 && lo <= hi) {
+      const unsigned klo = float_key(lo), khi = float_key(hi);
+      if (klo < __hip_atomic_load(&h->min_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMin(&h->min_key, klo);
+      if (khi > __hip_atomic_load(&h->max_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMax(&h->max_key, khi);
+    }
   }
 };
 

@@ -19,11 +19,14 @@ constexpr int kBlock = 256;
 // ---------------------------------------------------------------------------
 // range pass
 // ---------------------------------------------------------------------------
-__global__ void init_header_kernel(HardHeader* h) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
+__global__ void init_header_kernel(HardHeader* h, unsigned* counters, int batch) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) {
     h->min_key = 0xffffffffu;
     h->max_key = 0u;
+    h->overflow = 0u;
   }
+  if (counters && i < batch) counters[i] = 0u;
 }
 
 __device__ __forceinline__ float wave_min(float v) {
@@ -138,6 +141,34 @@ __global__ __launch_bounds__(kBlock) void sweep_generic_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// single-pass mode: bin the lists of critical vertices once the range is known
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, const float* __restrict__ table,
+                                                         int bins, unsigned long long* __restrict__ hist) {
+  if (la.hdr->overflow) return;  // the two-pass sweep that follows does the work
+  extern __shared__ int lhist[];
+  for (int b = threadIdx.x; b < bins; b += kBlock) lhist[b] = 0;
+  __syncthreads();
+  const float lo = la.hdr->lo, scale = la.hdr->scale;
+  // blocks x, x + kSubLists, ... of item y share sub-list x % kSubLists
+  const unsigned sub = blockIdx.y * kSubLists + blockIdx.x % kSubLists;
+  const unsigned part = blockIdx.x / kSubLists, parts = gridDim.x / kSubLists;
+  const float2* list = la.lists + (size_t)sub * la.cap;
+  const unsigned n = min(la.counters[sub], la.cap);
+  for (unsigned i = part * kBlock + threadIdx.x; i < n; i += parts * kBlock) {
+    const float2 e = list[i];
+    const int b = bin_from_table(e.x, table, bins, lo, scale);
+    if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
+  }
+  __syncthreads();
+  unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
+  for (int b = threadIdx.x; b < bins; b += kBlock) {
+    const int v = lhist[b];
+    if (v != 0) atomicAdd(&out[b], (unsigned long long)(long long)v);
+  }
+}
+
+// ---------------------------------------------------------------------------
 // inclusive prefix sum, one block per batch item, in place (int64)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void scan_kernel(long long* __restrict__ curve, int bins) {
@@ -238,8 +269,19 @@ hipError_t profile_end(float* mean_ms, int* launches) {
 // ---------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------
-size_t hard_workspace_bytes(const Shape&, int bins) {
-  return kTableOffset + (((size_t)bins * sizeof(float) + 255) / 256) * 256;
+// Workspace: header | threshold table | list counters [batch] | lists [batch][cap].
+// The lists (single-pass mode for float grids without a range) hold one entry
+// of 8 bytes per critical vertex; room for one vertex in eight.
+static size_t table_bytes(int bins) { return (((size_t)bins * sizeof(float) + 255) / 256) * 256; }
+static size_t counter_bytes(const Shape& s) { return (((size_t)s.batch * kSubLists * 4 + 255) / 256) * 256; }
+static unsigned list_cap(const Shape& s) {  // entries per sub-list
+  int64_t cap = (s.N / 8 / kSubLists + 63) / 64 * 64;
+  if (cap < 256) cap = 256;
+  if (cap > (int64_t)1 << 30) cap = (int64_t)1 << 30;
+  return (unsigned)cap;
+}
+size_t hard_workspace_bytes(const Shape& s, int bins) {
+  return kTableOffset + table_bytes(bins) + counter_bytes(s) + (size_t)s.batch * kSubLists * list_cap(s) * sizeof(float2);
 }
 
 static int blocks_for(int64_t N) {
@@ -265,33 +307,67 @@ static void launch_sweep_generic(const void* grid, const Shape& s, bool levels, 
 hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
                        double lo, double hi, int64_t* curve, void* ws, hipStream_t st) {
   HardHeader* hdr = static_cast<HardHeader*>(ws);
-  float* table = reinterpret_cast<float*>(static_cast<char*>(ws) + kTableOffset);
+  char* wsb = static_cast<char*>(ws);
+  float* table = reinterpret_cast<float*>(wsb + kTableOffset);
   unsigned long long* hist = reinterpret_cast<unsigned long long*>(curve);
   const bool is_float = (dtype == 2);
   const bool levels = !have_range && !is_float;
   const bool device_range = !have_range && is_float;
   const int64_t total = s.N * s.batch;
+  // ECC_FORCE_GENERIC=1 routes every shape through the plain one-thread-per-vertex sweep,
+  // ECC_TWO_PASS=1 keeps the separate range pass for float grids without a range
+  static const bool force_generic = getenv("ECC_FORCE_GENERIC") != nullptr;
+  static const bool two_pass = getenv("ECC_TWO_PASS") != nullptr;
+  const bool fast2d = !force_generic && sweep2d_supported(s, bins);
+  const bool fast3d = !force_generic && !fast2d && sweep3d_supported(s, bins);
+  const int64_t hist_len = s.batch * bins;
+  int prep_blocks = (int)((hist_len + kBlock - 1) / kBlock);
+  prep_blocks = prep_blocks > 1024 ? 1024 : prep_blocks;
+
+  if (device_range && (fast2d || fast3d) && !two_pass) {
+    // Single pass over the grid: the sweep finds the critical vertices and the
+    // range together; the few critical vertices are binned afterwards.  If a list
+    // overflows (more than one vertex in eight critical), the histogram-mode sweep
+    // that follows runs instead (it is a no-op otherwise).
+    ListArgs la;
+    la.hdr = hdr;
+    la.counters = reinterpret_cast<unsigned*>(wsb + kTableOffset + table_bytes(bins));
+    la.lists = reinterpret_cast<float2*>(wsb + kTableOffset + table_bytes(bins) + counter_bytes(s));
+    la.cap = list_cap(s);
+    const float* gf = static_cast<const float*>(grid);
+    hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)((s.batch * kSubLists + 255) / 256)), dim3(256),
+                       0, st, hdr, la.counters, (int)(s.batch * kSubLists));
+    profile_mark(st, false);
+    if (fast2d) launch_sweep2d_list(gf, s, la, st);
+    else launch_sweep3d_list(gf, s, la, st);
+    profile_mark(st, true);
+    hipLaunchKernelGGL(prepare_kernel, dim3(prep_blocks), dim3(kBlock), 0, st, hdr, table, bins, 1, lo, hi,
+                       hist, hist_len);
+    int64_t parts = 2048 / ((int64_t)kSubLists * s.batch);
+    parts = parts < 1 ? 1 : (parts > 32 ? 32 : parts);
+    hipLaunchKernelGGL(binlist_kernel, dim3(kSubLists * (unsigned)parts, (unsigned)s.batch), dim3(kBlock),
+                       (size_t)bins * sizeof(int), st, la, table, bins, hist);
+    if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow);
+    else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow);
+    hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,
+                       reinterpret_cast<long long*>(curve), bins);
+    return hipGetLastError();
+  }
+
   if (device_range) {
-    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, st, hdr);
+    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, st, hdr, (unsigned*)nullptr, 0);
     int nb = (int)((total / 4 + kBlock - 1) / kBlock);
     nb = nb < 1 ? 1 : (nb > 2048 ? 2048 : nb);
     hipLaunchKernelGGL(minmax_f32_kernel, dim3(nb), dim3(kBlock), 0, st,
                        static_cast<const float*>(grid), total, hdr);
   }
-  {
-    const int64_t hist_len = s.batch * bins;
-    int nb = (int)((hist_len + kBlock - 1) / kBlock);
-    nb = nb > 1024 ? 1024 : nb;
-    hipLaunchKernelGGL(prepare_kernel, dim3(nb), dim3(kBlock), 0, st, hdr, table, bins,
-                       device_range ? 1 : 0, lo, hi, hist, hist_len);
-  }
-  // ECC_FORCE_GENERIC=1 routes every shape through the plain one-thread-per-vertex sweep
-  static const bool force_generic = getenv("ECC_FORCE_GENERIC") != nullptr;
+  hipLaunchKernelGGL(prepare_kernel, dim3(prep_blocks), dim3(kBlock), 0, st, hdr, table, bins,
+                     device_range ? 1 : 0, lo, hi, hist, hist_len);
   profile_mark(st, false);
-  if (!force_generic && sweep2d_supported(s, bins)) {
-    launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st);
-  } else if (!force_generic && sweep3d_supported(s, bins)) {
-    launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st);
+  if (fast2d) {
+    launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr);
+  } else if (fast3d) {
+    launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr);
   } else
   switch (dtype) {
     case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;

@@ -156,10 +156,10 @@ template <typename T> struct RowRegs<T, true> {
 // of the previous chunk's words (one warm-up step on row y0-1 provides them
 // for the first chunk; above the grid they are all ones, i.e. "never before
 // p" once complemented).
-template <typename T, bool LEVELS, bool EDGE>
+template <typename T, typename Sink, bool EDGE>
 __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t item_elems, int H, int W,
-                                            int c0, int y0, int y1, WaveQueue<LEVELS>& queue,
-                                            float* ring /* [kChunkRows][64][kNC] */) {
+                                            int c0, int y0, int y1, WaveQueue<Sink>& queue,
+                                            float* ring /* [kChunkRows][64][kNC] */, WaveRange& range) {
   const int lane = threadIdx.x & (kWave - 1);
   bool ok[kNC];         // column inside the grid
   unsigned voff[kNC];   // byte offset of the column inside a row (clamped into the row)
@@ -211,6 +211,13 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     *reinterpret_cast<float4*>(ring + (slot * kWave + lane) * kNC) =
         make_float4(cur[0], cur[1], cur[2], cur[3]);
     ++slot;
+    if (Sink::kTrackRange) {
+#pragma unroll
+      for (int e = 0; e < kNC; ++e) {
+        if (EDGE) range.add_if(cur[e], ok[e]);
+        else range.add(cur[e]);
+      }
+    }
     float dE, dNE, dNW;
     lane_edge_differences(cur[0], cur[kNC - 1], nxt[0], nxt[kNC - 1], dE, dNE, dNW);
 #pragma unroll
@@ -311,11 +318,35 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 
 // Work unit of a wave: (segment of rows) x (strip of columns) of one item;
 // blockIdx.y is the item, the four waves of a block take adjacent strips.
+template <typename T, typename Sink>
+__device__ __forceinline__ void sweep2d_wave(const T* __restrict__ g, int H, int W, int64_t N, int nstrip,
+                                             int nseg, int rows_per_seg, WaveQueue<Sink>& queue, float* ring,
+                                             WaveRange& range) {
+  const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform
+  if (unit < nstrip * nseg) {
+    const int seg = unit / nstrip, strip = unit - seg * nstrip;
+    const int c0 = strip * kStripOut - kNC;
+    const int y0 = seg * rows_per_seg;
+    const int y1 = min(y0 + rows_per_seg, H);
+    // 4-element loads need every column in the grid and 4-element alignment of the rows
+    const bool edge = (c0 < 0) || (c0 + kNC * kWave > W) || (W % kNC != 0) ||
+                      ((reinterpret_cast<uintptr_t>(g) & (kNC * sizeof(T) - 1)) != 0);
+    if (edge)
+      sweep_strip<T, Sink, true>(g, N, H, W, c0, y0, y1, queue, ring, range);
+    else
+      sweep_strip<T, Sink, false>(g, N, H, W, c0, y0, y1, queue, ring, range);
+  }
+}
+
+// Histogram mode: critical vertices are binned into the block's LDS histogram,
+// which is merged into the global one at the end.  run_if (may be null): the
+// kernel does nothing unless *run_if != 0 (fallback of the single-pass mode).
 template <typename T, bool LEVELS, bool TLDS>
 __global__ __launch_bounds__(256) void sweep2d_kernel(
     const T* __restrict__ grid, int H, int W, int64_t N, int bins, int nstrip, int nseg, int rows_per_seg,
     const HardHeader* __restrict__ hdr, const float* __restrict__ table,
-    unsigned long long* __restrict__ hist) {
+    unsigned long long* __restrict__ hist, const unsigned* __restrict__ run_if) {
+  if (run_if && *run_if == 0) return;
   extern __shared__ int smem[];
   // [4 waves][kChunkRows][64][kNC] floats of value ring, [4 waves] queues, histogram, table
   const int wv = threadIdx.x >> 6;
@@ -328,31 +359,16 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
     if (TLDS) ltable[b] = table[b];
   }
   __syncthreads();
-  float lo = 0.f, scale = 0.f;
-  if (!LEVELS) { lo = hdr->lo; scale = hdr->scale; }
-  const T* g = grid + (int64_t)blockIdx.y * N;
-  const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform
-  if (unit < nstrip * nseg) {
-    const int seg = unit / nstrip, strip = unit - seg * nstrip;
-    const int c0 = strip * kStripOut - kNC;
-    const int y0 = seg * rows_per_seg;
-    const int y1 = min(y0 + rows_per_seg, H);
-    // 4-element loads need every column in the grid and 4-element alignment of the rows
-    const bool edge = (c0 < 0) || (c0 + kNC * kWave > W) || (W % kNC != 0) ||
-                      ((reinterpret_cast<uintptr_t>(g) & (kNC * sizeof(T) - 1)) != 0);
-    WaveQueue<LEVELS> queue;
-    queue.buf = qbuf;
-    queue.count = 0;
-    queue.sink.lhist = lhist;
-    queue.sink.table = TLDS ? ltable : table;
-    queue.sink.bins = bins;
-    queue.sink.lo = lo;
-    queue.sink.scale = scale;
-    if (edge)
-      sweep_strip<T, LEVELS, true>(g, N, H, W, c0, y0, y1, queue, ring);
-    else
-      sweep_strip<T, LEVELS, false>(g, N, H, W, c0, y0, y1, queue, ring);
-  }
+  WaveQueue<HistSink<LEVELS>> queue;
+  queue.buf = qbuf;
+  queue.count = 0;
+  queue.sink.lhist = lhist;
+  queue.sink.table = TLDS ? ltable : table;
+  queue.sink.bins = bins;
+  queue.sink.lo = LEVELS ? 0.f : hdr->lo;
+  queue.sink.scale = LEVELS ? 0.f : hdr->scale;
+  WaveRange range;
+  sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range);
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
   for (int b = threadIdx.x; b < bins; b += 256) {
@@ -361,14 +377,42 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
   }
 }
 
+// Single-pass mode: critical vertices (value, c) go to the item's list in the
+// workspace and the wave's min / max to the header; the bins are assigned later,
+// once the batch-global range is known.
 template <typename T>
-static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
-                       const float* table, unsigned long long* hist, hipStream_t st) {
+__global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__ grid, int H, int W,
+                                                           int64_t N, int nstrip, int nseg,
+                                                           int rows_per_seg, ListArgs la) {
+  extern __shared__ int smem[];
+  const int wv = threadIdx.x >> 6;
+  float* ring = reinterpret_cast<float*>(smem) + wv * (kChunkRows * kWave * kNC);
+  float2* qbuf = reinterpret_cast<float2*>(smem + 4 * kChunkRows * kWave * kNC) + wv * kQueueCap;
+  WaveQueue<ListSink> queue;
+  queue.buf = qbuf;
+  queue.count = 0;
+  const unsigned sub = blockIdx.y * kSubLists + blockIdx.x % kSubLists;
+  queue.sink.list = la.lists + (size_t)sub * la.cap;
+  queue.sink.counter = la.counters + sub;
+  queue.sink.cap = la.cap;
+  queue.sink.overflow = &la.hdr->overflow;
+  WaveRange range;
+  sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range);
+  range.commit(la.hdr);
+}
+
+struct Plan2d {
+  int nstrip, nseg, rows_per_seg;
+  dim3 grid;
+};
+template <typename T>
+static Plan2d plan2d(const Shape& s) {
+  Plan2d p;
   const int H = (int)s.H, W = (int)s.W;
-  const int nstrip = (W + kStripOut - 1) / kStripOut;
+  p.nstrip = (W + kStripOut - 1) / kStripOut;
   // enough wave units to fill 256 CUs several times over, segments of >= 32 rows
   const int64_t target = 16384;
-  int64_t nseg = (target + (int64_t)nstrip * s.batch - 1) / ((int64_t)nstrip * s.batch);
+  int64_t nseg = (target + (int64_t)p.nstrip * s.batch - 1) / ((int64_t)p.nstrip * s.batch);
   const int64_t max_seg = (H + 31) / 32;
   if (nseg > max_seg) nseg = max_seg;
   if (nseg < 1) nseg = 1;
@@ -377,21 +421,36 @@ static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, 
   const int64_t row_bytes = (int64_t)W * (int64_t)sizeof(T);
   const int64_t cap = ((((int64_t)1 << 31) / row_bytes - 16) / 32) * 32;
   if (rows > cap) rows = cap;
-  const int rows_per_seg = (int)rows;
-  nseg = (H + rows_per_seg - 1) / rows_per_seg;
-  const int units = nstrip * (int)nseg;
-  dim3 g((unsigned)((units + 3) / 4), (unsigned)s.batch);
-  const size_t ring_bytes = (size_t)4 * kChunkRows * kWave * kNC * sizeof(float) + 4 * kQueueCap * sizeof(float2);
-  const bool tlds = !levels && (size_t)bins * 8 + ring_bytes <= 64 * 1024;
-  const size_t lds = ring_bytes + (size_t)bins * (tlds ? 8 : 4);
+  p.rows_per_seg = (int)rows;
+  p.nseg = (int)((H + p.rows_per_seg - 1) / p.rows_per_seg);
+  const int units = p.nstrip * p.nseg;
+  p.grid = dim3((unsigned)((units + 3) / 4), (unsigned)s.batch);
+  return p;
+}
+constexpr size_t kRingBytes2d =
+    (size_t)4 * kChunkRows * kWave * kNC * sizeof(float) + 4 * kQueueCap * sizeof(float2);
+
+template <typename T>
+static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
+                       const float* table, unsigned long long* hist, hipStream_t st,
+                       const unsigned* run_if) {
+  const Plan2d pl = plan2d<T>(s);
+  const bool tlds = !levels && (size_t)bins * 8 + kRingBytes2d <= 64 * 1024;
+  const size_t lds = kRingBytes2d + (size_t)bins * (tlds ? 8 : 4);
   const T* p = static_cast<const T*>(grid);
-#define ECC_GO(LV, TL)                                                                          \
-  hipLaunchKernelGGL((sweep2d_kernel<T, LV, TL>), g, dim3(256), lds, st, p, H, W, s.N, bins, nstrip, \
-                     (int)nseg, rows_per_seg, hdr, table, hist)
+#define ECC_GO(LV, TL)                                                                              \
+  hipLaunchKernelGGL((sweep2d_kernel<T, LV, TL>), pl.grid, dim3(256), lds, st, p, (int)s.H, (int)s.W, \
+                     s.N, bins, pl.nstrip, pl.nseg, pl.rows_per_seg, hdr, table, hist, run_if)
   if (levels) ECC_GO(true, false);
   else if (tlds) ECC_GO(false, true);
   else ECC_GO(false, false);
 #undef ECC_GO
+}
+
+void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st) {
+  const Plan2d pl = plan2d<float>(s);
+  hipLaunchKernelGGL((sweep2d_list_kernel<float>), pl.grid, dim3(256), kRingBytes2d, st, grid, (int)s.H,
+                     (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la);
 }
 
 bool sweep2d_supported(const Shape& s, int bins) {
@@ -401,11 +460,11 @@ bool sweep2d_supported(const Shape& s, int bins) {
 
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st) {
+                    hipStream_t st, const unsigned* run_if) {
   switch (dtype) {
-    case 0: launch2d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;
-    case 1: launch2d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st); break;
-    default: launch2d_t<float>(grid, s, levels, bins, hdr, table, hist, st); break;
+    case 0: launch2d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
+    case 1: launch2d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
+    default: launch2d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
   }
 }
 

@@ -186,10 +186,10 @@ __device__ __forceinline__ void arc_starts(const unsigned (&m)[8], unsigned g, u
 // One tube: columns xs .. xs+63 (outputs xs+1 .. xs+62), output rows
 // yb .. yb+R-1, output planes z0 .. z1-1.  SAFE: some lane or row of the tube
 // lies outside the grid (those read as +inf).
-template <typename T, int R, bool LEVELS, bool SAFE, bool SKIP_TOP, bool SKIP_BOTTOM>
+template <typename T, int R, typename Sink, bool SAFE, bool SKIP_TOP, bool SKIP_BOTTOM>
 __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item_elems, int D, int H,
                                            int W, int xs, int yb, int z0, int z1,
-                                           WaveQueue<LEVELS>& queue, unsigned* xch) {
+                                           WaveQueue<Sink>& queue, unsigned* xch, WaveRange& range) {
   constexpr bool skip_top = SKIP_TOP, skip_bottom = SKIP_BOTTOM;
   const int lane = threadIdx.x & (kWave - 1);
   const int x = xs + lane;
@@ -266,18 +266,30 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
     // this chunk, bit i holds plane z+n-1-i, so bit n of a next-plane word still
     // holds the relation of the plane below the chunk's first plane.
     int k = 0;
+    auto track = [&](const float (&p)[R + 2]) {
+      if (Sink::kTrackRange) {
+#pragma unroll
+        for (int j = 1; j <= R; ++j) {
+          if (SAFE) range.add_if(p[j], inb && rok[j]);
+          else range.add(p[j]);
+        }
+      }
+    };
     for (; k + 2 <= n; k += 2) {
       fix(pb, rawx);  // plane above pa
       load_plane(rawx);
+      track(pa);
       push_plane<R>(w, pa, skip_top);
       push_up<R>(w, pa, pb, skip_top, skip_bottom);
       fix(pa, rawy);  // plane above pb
       load_plane(rawy);
+      track(pb);
       push_plane<R>(w, pb, skip_top);
       push_up<R>(w, pb, pa, skip_top, skip_bottom);
     }
     if (k < n) {  // odd tail: only in the last chunk of the segment
       fix(pb, rawx);
+      track(pa);
       push_plane<R>(w, pa, skip_top);
       push_up<R>(w, pa, pb, skip_top, skip_bottom);
     }
@@ -391,26 +403,12 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 
 // Work unit of a wave: (z segment, row group, column strip) of one item;
 // blockIdx.y is the item; the four waves of a block take consecutive row groups
-// of one strip, so their halo rows meet in the CU's vector cache.
-template <typename T, int R, bool LEVELS, bool TLDS>
-__global__ __launch_bounds__(256) void sweep3d_kernel(
-    const T* __restrict__ grid, int D, int H, int W, int64_t N, int bins, int nstrip, int ngroup,
-    int nseg, int planes_per_seg, const HardHeader* __restrict__ hdr,
-    const float* __restrict__ table, unsigned long long* __restrict__ hist) {
-  extern __shared__ int smem[];
-  // [2][4 waves][9][64] exchange words, [4 waves] queues, histogram, table
-  unsigned* xch = reinterpret_cast<unsigned*>(smem);
-  float2* qbuf = reinterpret_cast<float2*>(smem + 2 * 4 * s3::kXchWords * kWave) + (threadIdx.x >> 6) * kQueueCap;
-  int* lhist = smem + 2 * 4 * s3::kXchWords * kWave + 4 * kQueueCap * 2;
-  float* ltable = reinterpret_cast<float*>(lhist + bins);
-  for (int b = threadIdx.x; b < bins; b += 256) {
-    lhist[b] = 0;
-    if (TLDS) ltable[b] = table[b];
-  }
-  __syncthreads();
-  float lo = 0.f, scale = 0.f;
-  if (!LEVELS) { lo = hdr->lo; scale = hdr->scale; }
-  const T* g = grid + (int64_t)blockIdx.y * N;
+// of one strip, so their halo rows meet in the CU's vector cache and their halo
+// words are swapped through LDS.
+template <typename T, int R, typename Sink>
+__device__ __forceinline__ void sweep3d_wave(const T* __restrict__ g, int D, int H, int W, int64_t N,
+                                             int nstrip, int ngroup, int nseg, int planes_per_seg,
+                                             WaveQueue<Sink>& queue, unsigned* xch, WaveRange& range) {
   // unit = ((seg * nstrip) + strip) * ngroup4 + group, group fastest
   const int ngroup4 = (ngroup + 3) & ~3;
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform
@@ -427,29 +425,55 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
     const bool skip_top = (unit & 3) != 0;
     const bool skip_bottom = (unit & 3) != 3 && group + 1 < ngroup;
     const bool safe = (xs < 0) || (xs + kWave > W) || (yb == 0) || (yb + R + 1 > H);
-    WaveQueue<LEVELS> queue;
-    queue.buf = qbuf;
-    queue.count = 0;
-    queue.sink.lhist = lhist;
-    queue.sink.table = TLDS ? ltable : table;
-    queue.sink.bins = bins;
-    queue.sink.lo = lo;
-    queue.sink.scale = scale;
     // tubes touching the grid boundary compute their own halo words (one variant fewer)
     if (safe)
-      s3::sweep_tube<T, R, LEVELS, true, false, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
+      s3::sweep_tube<T, R, Sink, true, false, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
     else if (skip_top && skip_bottom)
-      s3::sweep_tube<T, R, LEVELS, false, true, true>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
+      s3::sweep_tube<T, R, Sink, false, true, true>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
     else if (skip_top)
-      s3::sweep_tube<T, R, LEVELS, false, true, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
+      s3::sweep_tube<T, R, Sink, false, true, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
     else if (skip_bottom)
-      s3::sweep_tube<T, R, LEVELS, false, false, true>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
+      s3::sweep_tube<T, R, Sink, false, false, true>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
     else
-      s3::sweep_tube<T, R, LEVELS, false, false, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch);
+      s3::sweep_tube<T, R, Sink, false, false, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
   } else {
     // a wave without a row group still meets the block's one barrier per chunk
     for (int z = z0; z < z1; z += s3::kChunk) __syncthreads();
   }
+}
+
+constexpr int kXchInts = 2 * 4 * s3::kXchWords * kWave;  // exchange words of a block, in ints
+
+// Histogram mode; run_if (may be null): do nothing unless *run_if != 0.
+template <typename T, int R, bool LEVELS, bool TLDS>
+__global__ __launch_bounds__(256) void sweep3d_kernel(
+    const T* __restrict__ grid, int D, int H, int W, int64_t N, int bins, int nstrip, int ngroup,
+    int nseg, int planes_per_seg, const HardHeader* __restrict__ hdr,
+    const float* __restrict__ table, unsigned long long* __restrict__ hist,
+    const unsigned* __restrict__ run_if) {
+  if (run_if && *run_if == 0) return;
+  extern __shared__ int smem[];
+  // [2][4 waves][9][64] exchange words, [4 waves] queues, histogram, table
+  unsigned* xch = reinterpret_cast<unsigned*>(smem);
+  float2* qbuf = reinterpret_cast<float2*>(smem + kXchInts) + (threadIdx.x >> 6) * kQueueCap;
+  int* lhist = smem + kXchInts + 4 * kQueueCap * 2;
+  float* ltable = reinterpret_cast<float*>(lhist + bins);
+  for (int b = threadIdx.x; b < bins; b += 256) {
+    lhist[b] = 0;
+    if (TLDS) ltable[b] = table[b];
+  }
+  __syncthreads();
+  WaveQueue<HistSink<LEVELS>> queue;
+  queue.buf = qbuf;
+  queue.count = 0;
+  queue.sink.lhist = lhist;
+  queue.sink.table = TLDS ? ltable : table;
+  queue.sink.bins = bins;
+  queue.sink.lo = LEVELS ? 0.f : hdr->lo;
+  queue.sink.scale = LEVELS ? 0.f : hdr->scale;
+  WaveRange range;
+  sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
+                     queue, xch, range);
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
   for (int b = threadIdx.x; b < bins; b += 256) {
@@ -458,17 +482,43 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
   }
 }
 
+// Single-pass mode: critical vertices to the item's list, min / max to the header.
+template <typename T, int R>
+__global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__ grid, int D, int H, int W,
+                                                           int64_t N, int nstrip, int ngroup, int nseg,
+                                                           int planes_per_seg, ListArgs la) {
+  extern __shared__ int smem[];
+  unsigned* xch = reinterpret_cast<unsigned*>(smem);
+  float2* qbuf = reinterpret_cast<float2*>(smem + kXchInts) + (threadIdx.x >> 6) * kQueueCap;
+  WaveQueue<ListSink> queue;
+  queue.buf = qbuf;
+  queue.count = 0;
+  const unsigned sub = blockIdx.y * kSubLists + blockIdx.x % kSubLists;
+  queue.sink.list = la.lists + (size_t)sub * la.cap;
+  queue.sink.counter = la.counters + sub;
+  queue.sink.cap = la.cap;
+  queue.sink.overflow = &la.hdr->overflow;
+  WaveRange range;
+  sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
+                     queue, xch, range);
+  range.commit(la.hdr);
+}
+
 constexpr int kRows3d = 4;
 
+struct Plan3d {
+  int nstrip, ngroup, nseg, planes_per_seg;
+  dim3 grid;
+};
 template <typename T>
-static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
-                       const float* table, unsigned long long* hist, hipStream_t st) {
+static Plan3d plan3d(const Shape& s) {
   constexpr int R = kRows3d;
+  Plan3d p;
   const int D = (int)s.D, H = (int)s.H, W = (int)s.W;
-  const int nstrip = (W + s3::kOut - 1) / s3::kOut;
-  const int ngroup = (H + R - 1) / R;
-  const int ngroup4 = (ngroup + 3) & ~3;
-  const int64_t per_seg = (int64_t)nstrip * ngroup * s.batch;
+  p.nstrip = (W + s3::kOut - 1) / s3::kOut;
+  p.ngroup = (H + R - 1) / R;
+  const int ngroup4 = (p.ngroup + 3) & ~3;
+  const int64_t per_seg = (int64_t)p.nstrip * p.ngroup * s.batch;
   int64_t nseg = (8192 + per_seg - 1) / per_seg;
   const int64_t max_seg = (D + s3::kChunk - 1) / s3::kChunk;
   if (nseg > max_seg) nseg = max_seg;
@@ -478,21 +528,38 @@ static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, 
   const int64_t plane_bytes = (int64_t)H * W * (int64_t)sizeof(T);
   const int64_t cap = ((((int64_t)1 << 31) / plane_bytes - 6) / s3::kChunk) * s3::kChunk;
   if (planes > cap) planes = cap;
-  const int planes_per_seg = (int)planes;
-  nseg = (D + planes_per_seg - 1) / planes_per_seg;
-  const int64_t units = nseg * nstrip * ngroup4;
-  dim3 g((unsigned)(units / 4), (unsigned)s.batch);
-  const size_t qbytes = (size_t)4 * kQueueCap * sizeof(float2) + (size_t)2 * 4 * s3::kXchWords * kWave * 4;
-  const bool tlds = !levels && (size_t)bins * 8 + qbytes <= 60 * 1024;
-  const size_t lds = qbytes + (size_t)bins * (tlds ? 8 : 4);
+  p.planes_per_seg = (int)planes;
+  p.nseg = (int)((D + p.planes_per_seg - 1) / p.planes_per_seg);
+  const int64_t units = (int64_t)p.nseg * p.nstrip * ngroup4;
+  p.grid = dim3((unsigned)(units / 4), (unsigned)s.batch);
+  return p;
+}
+constexpr size_t kFixedLds3d = (size_t)4 * kQueueCap * sizeof(float2) + (size_t)kXchInts * 4;
+
+template <typename T>
+static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
+                       const float* table, unsigned long long* hist, hipStream_t st,
+                       const unsigned* run_if) {
+  constexpr int R = kRows3d;
+  const Plan3d pl = plan3d<T>(s);
+  const bool tlds = !levels && (size_t)bins * 8 + kFixedLds3d <= 60 * 1024;
+  const size_t lds = kFixedLds3d + (size_t)bins * (tlds ? 8 : 4);
   const T* p = static_cast<const T*>(grid);
-#define ECC_GO(LV, TL)                                                                              \
-  hipLaunchKernelGGL((sweep3d_kernel<T, R, LV, TL>), g, dim3(256), lds, st, p, D, H, W, s.N, bins, \
-                     nstrip, ngroup, (int)nseg, planes_per_seg, hdr, table, hist)
+#define ECC_GO(LV, TL)                                                                                  \
+  hipLaunchKernelGGL((sweep3d_kernel<T, R, LV, TL>), pl.grid, dim3(256), lds, st, p, (int)s.D, (int)s.H, \
+                     (int)s.W, s.N, bins, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg, hdr, table,  \
+                     hist, run_if)
   if (levels) ECC_GO(true, false);
   else if (tlds) ECC_GO(false, true);
   else ECC_GO(false, false);
 #undef ECC_GO
+}
+
+void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st) {
+  const Plan3d pl = plan3d<float>(s);
+  hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d>), pl.grid, dim3(256), kFixedLds3d, st, grid,
+                     (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg,
+                     la);
 }
 
 bool sweep3d_supported(const Shape& s, int bins) {
@@ -503,11 +570,11 @@ bool sweep3d_supported(const Shape& s, int bins) {
 
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st) {
+                    hipStream_t st, const unsigned* run_if) {
   switch (dtype) {
-    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;
-    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st); break;
-    default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st); break;
+    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
+    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
+    default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
   }
 }
 
