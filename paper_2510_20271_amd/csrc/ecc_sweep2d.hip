@@ -290,6 +290,10 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     const unsigned E_left = word_from_left(E[kNC - 1]);
     const unsigned pNEE_left = word_from_left(pNE[kNC - 1] | E[kNC - 1]);
     const unsigned pNW_right = word_from_right(pNW[0]);
+    // A chunk uses the top kChunkRows (8) bits of a word, so the four columns of a
+    // lane are packed into one word (column e in byte 3-e) and walked in one loop.
+    static_assert(kChunkRows * kNC <= 32, "four columns of a chunk must fit one word");
+    unsigned pE = 0, pNn = 0, pW = 0, pS = 0, nz = 0;
 #pragma unroll
     for (int e = 0; e < kNC; ++e) {
       const unsigned El = e > 0 ? E[e - 1] : E_left;                              // [p before its -x neighbour]
@@ -301,16 +305,24 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
       const unsigned sS = pNEEl & ~pN[e];
       const unsigned x1 = sE ^ sN, c1 = sE & sN, x2 = sW ^ sS, c2 = sW & sS;
       const unsigned one = (x1 ^ x2) & ~(c1 | c2);
-      unsigned nz = (out_lane && ok[e]) ? (~one & rows) : 0u;
-      while (ballot(nz != 0)) {
-        const bool active = nz != 0;
-        const int b = active ? 31 - __clz(nz) : 0;
-        nz &= ~(1u << b);
-        const int c = 1 - (int)((sE >> b) & 1u) - (int)((sN >> b) & 1u) - (int)((sW >> b) & 1u) -
-                      (int)((sS >> b) & 1u);
-        const float v = ring[((31 - b) * kWave + lane) * kNC + e];
-        queue.push(active, v, c);
-      }
+      const unsigned crit = ok[e] ? (~one & rows) : 0u;
+      const unsigned top = 0xff000000u;
+      pE |= (sE & top) >> (8 * e);
+      pNn |= (sN & top) >> (8 * e);
+      pW |= (sW & top) >> (8 * e);
+      pS |= (sS & top) >> (8 * e);
+      nz |= (crit & top) >> (8 * e);
+    }
+    if (!out_lane) nz = 0u;
+    while (ballot(nz != 0)) {
+      const bool active = nz != 0;
+      const int b = active ? 31 - __clz(nz) : 0;
+      nz &= ~(1u << b);
+      const int c = 1 - (int)((pE >> b) & 1u) - (int)((pNn >> b) & 1u) - (int)((pW >> b) & 1u) -
+                    (int)((pS >> b) & 1u);
+      const int pos = 31 - b;  // column pos / 8, row pos % 8 of the chunk
+      const float v = ring[((pos & 7) * kWave + lane) * kNC + (pos >> 3)];
+      queue.push(active, v, c);
     }
   }
   queue.flush();
