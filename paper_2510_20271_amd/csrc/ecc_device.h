@@ -118,16 +118,25 @@ template <typename T> __device__ __forceinline__ float as_float(T v) { return (f
 // the binning code with most lanes idle, a wave appends (value, c) to a small
 // LDS queue (lane-compacted with a ballot) and drains it 64 entries at a time
 // with every lane busy.
+// A sink names its entry type (what the queue stores per critical vertex), makes
+// an entry from (value, c, column, row) and consumes the first n entries of the
+// queue buffer with the whole wave (n is wave-uniform, n <= 64).
 template <bool LEVELS>
 struct HistSink {  // drain target: the block's LDS histogram
+  typedef float2 Entry;
   static constexpr bool kTrackRange = false;
+  static constexpr bool kZeroFill = false;
   int* lhist;
   const float* table;  // float[bins] thresholds (LDS or global), unused for LEVELS
   int bins;
   float lo, scale;
-  // every lane calls; `active` lanes hold an entry, n = number of entries (wave-uniform)
-  __device__ __forceinline__ void take(float2 e, bool active, int) const {
-    if (!active) return;
+  static __device__ __forceinline__ Entry make(float v, int c, int, int) {
+    return make_float2(v, __int_as_float(c));
+  }
+  __device__ __forceinline__ void consume(const Entry* buf, int n) {
+    const int lane = threadIdx.x & (kWave - 1);
+    if (lane >= n) return;
+    const Entry e = buf[lane];
     const float v = e.x;
     int b;
     if (LEVELS) b = (v < (float)bins) ? (int)v : bins;
@@ -136,64 +145,64 @@ struct HistSink {  // drain target: the block's LDS histogram
   }
 };
 
-// Drain target of the single-pass mode: the item's list of critical vertices in
-// the workspace (value, c).  A wave reserves n slots with one atomic; when the
-// list is full the overflow flag is raised and the entries are dropped (the
-// caller then runs the two-pass path instead).
+// Drain target of the single-pass mode: a list of critical vertices (value, c)
+// in the workspace.  A wave reserves n slots with one atomic; when the list is
+// full the overflow flag is raised and the entries are dropped (the caller then
+// runs the two-pass path instead).
 constexpr unsigned kSubLists = 32;  // lists per item: spreads the slot-reservation atomics
 
 struct ListSink {
+  typedef float2 Entry;
   static constexpr bool kTrackRange = true;
+  static constexpr bool kZeroFill = false;
   float2* list;       // this block's sub-list
   unsigned* counter;  // its fill count
   unsigned cap;       // entries per sub-list
   unsigned* overflow;
-  __device__ __forceinline__ void take(float2 e, bool active, int n) const {
+  static __device__ __forceinline__ Entry make(float v, int c, int, int) {
+    return make_float2(v, __int_as_float(c));
+  }
+  __device__ __forceinline__ void consume(const Entry* buf, int n) {
     const int lane = threadIdx.x & (kWave - 1);
     unsigned base = 0;
     if (lane == 0) base = atomicAdd(counter, (unsigned)n);
     base = __builtin_amdgcn_readfirstlane(base);
     if (base + (unsigned)n <= cap) {
-      if (active) list[base + lane] = e;
+      if (lane < n) list[base + lane] = buf[lane];
     } else if (lane == 0) {
       atomicOr(overflow, 1u);
     }
   }
 };
 
-constexpr int kQueueCap = 128;  // entries per wave (float2 each)
+constexpr int kQueueCap = 128;  // entries per wave
 
 template <typename Sink>
 struct WaveQueue {
-  float2* buf;  // wave-private LDS, kQueueCap entries
-  int count;    // wave-uniform
+  typedef typename Sink::Entry Entry;
+  Entry* buf;  // wave-private LDS, kQueueCap entries
+  int count;   // wave-uniform
   Sink sink;
 
   __device__ __forceinline__ void drain64() {
     const int lane = threadIdx.x & (kWave - 1);
-    sink.take(buf[lane], true, kWave);
+    sink.consume(buf, kWave);
     const int rest = count - kWave;  // < 64
-    float2 m = make_float2(0.f, 0.f);
-    if (lane < rest) m = buf[lane + kWave];
+    Entry m = buf[lane < rest ? lane + kWave : lane];
     if (lane < rest) buf[lane] = m;
     count = rest;
   }
-  // every lane calls; `active` lanes append (v, c)
-  __device__ __forceinline__ void push(bool active, float v, int c) {
+  // every lane calls; `active` lanes append the critical vertex (v, c) at (col, row)
+  __device__ __forceinline__ void push(bool active, float v, int c, int col, int row) {
     const unsigned long long m = __builtin_amdgcn_ballot_w64(active);
     const int idx = count + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
                                                            __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
-    if (active) buf[idx] = make_float2(v, __int_as_float(c));
+    if (active) buf[idx] = sink.make(v, c, col, row);
     count += __builtin_popcountll(m);
     if (count >= kWave) drain64();
   }
   __device__ __forceinline__ void flush() {
-    const int lane = threadIdx.x & (kWave - 1);
-    if (count > 0) {  // wave-uniform
-      float2 e = make_float2(0.f, 0.f);
-      if (lane < count) e = buf[lane];
-      sink.take(e, lane < count, count);
-    }
+    if (count > 0) sink.consume(buf, count);  // wave-uniform
     count = 0;
   }
 };

@@ -56,4 +56,13 @@ hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, fl
                            const float* tau, int T, float lambda, const float* g, float* grad_X,
                            float* dtau, float* du, void* ws, hipStream_t st);
 
+// fused 2D soft path (strip sweep + sigmoid sinks)
+bool soft2d_supported(const Shape& s, int T);
+size_t soft2d_workspace_bytes(const Shape& s, int T);
+void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
+                       int T, float lambda, float* chi, void* ws, hipStream_t st);
+void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
+                       int T, float lambda, const float* gup, float* grad_X, float* dtau, float* du,
+                       void* ws, hipStream_t st);
+
 }  // namespace ecc

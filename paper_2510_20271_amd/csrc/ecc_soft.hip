@@ -19,6 +19,8 @@
 #include "ecc_device.h"
 #include "ecc_internal.h"
 
+#include <cstdlib>
+
 namespace ecc {
 
 constexpr int kSoftBlock = 256;
@@ -259,7 +261,15 @@ __global__ void soft_bwd_reduce_kernel(const float* __restrict__ partial, int nt
 static int64_t tiles_of(const Shape& s) { return (s.N + kTile - 1) / kTile; }
 
 size_t soft_workspace_bytes(const Shape& s, int T) {
-  return (size_t)256 + (size_t)s.batch * (size_t)tiles_of(s) * (size_t)T * 4 * sizeof(float);
+  const size_t a = (size_t)256 + (size_t)s.batch * (size_t)tiles_of(s) * (size_t)T * 4 * sizeof(float);
+  const size_t b = soft2d_workspace_bytes(s, T);
+  return a > b ? a : b;
+}
+
+// ECC_SOFT_TILES=1 keeps the tile kernels of this file for every shape
+static bool use_soft2d(const Shape& s, int T) {
+  static const bool tiles_only = getenv("ECC_SOFT_TILES") != nullptr;
+  return !tiles_only && soft2d_supported(s, T);
 }
 
 static float kneg_of(float lambda) { return (float)(-(double)lambda * 1.4426950408889634); }
@@ -267,6 +277,10 @@ static float kneg_of(float lambda) { return (float)(-(double)lambda * 1.44269504
 hipError_t launch_soft_fwd(const float* grid, const Shape& s, const float* u, float alpha,
                            const float* tau, int T, float lambda, float* chi, void* ws,
                            hipStream_t st) {
+  if (use_soft2d(s, T)) {
+    launch_soft2d_fwd(grid, s, u, alpha, tau, T, lambda, chi, ws, st);
+    return hipGetLastError();
+  }
   float* partial = static_cast<float*>(ws);
   const int ntiles = (int)tiles_of(s);
   dim3 g((unsigned)ntiles, (unsigned)s.batch);
@@ -285,6 +299,10 @@ hipError_t launch_soft_fwd(const float* grid, const Shape& s, const float* u, fl
 hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, float alpha,
                            const float* tau, int T, float lambda, const float* gup, float* grad_X,
                            float* dtau, float* du, void* ws, hipStream_t st) {
+  if (use_soft2d(s, T)) {
+    launch_soft2d_bwd(grid, s, u, alpha, tau, T, lambda, gup, grad_X, dtau, du, ws, st);
+    return hipGetLastError();
+  }
   float* partial = (dtau || du) ? static_cast<float*>(ws) : nullptr;
   const int ntiles = (int)tiles_of(s);
   dim3 g((unsigned)ntiles, (unsigned)s.batch);

@@ -392,7 +392,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
         const int zr = z + (n - 1 - b) - zs;  // plane relative to the resource
         float val = 0.f;
         if (active) val = (float)Load<T>::get(rsrc, voff + (unsigned)zr * plane_bytes + roff[j], 0);
-        queue.push(active, val, P - Q);
+        queue.push(active, val, P - Q, 0, 0);
       }
     }
   }
