@@ -9,8 +9,8 @@
 //   - threshold-major: lane l owns thresholds tau_l, tau_{l+64}, ... (up to 4,
 //     so T <= 256) and runs over the queue entries (LDS broadcast reads): the
 //     sums over p of Eq. 6 / Eq. 9 / Eq. 10 need no cross-lane reduction;
-//   - vertex-major (backward): lane l owns entry l and runs over all thresholds:
-//     the contraction of Eq. 8 with the upstream gradient, written to grad_X.
+//   - backward: the same pass also forms, per entry, the contraction of Eq. 8 with
+//     the upstream gradient as a fixed butterfly sum over the lanes (grad_X).
 // grad_X is zero away from critical vertices; the sweep writes those zeros row
 // by row for the vertices it owns, before any entry of those rows is drained.
 // Each wave writes its partial sums to the workspace; a second kernel adds them
@@ -42,6 +42,7 @@ struct SoftCommon {
   double ux, uy, alpha;
   double tj[kSoftTL];  // this lane's thresholds
   int T;
+  int nt;  // threshold slots in use: ceil(T / 64)
   float kneg;
   __device__ __forceinline__ Entry make(float v, int c, int col, int row) const {
     Entry e;
@@ -57,6 +58,7 @@ struct SoftCommon {
     uy = (double)u[1];
     alpha = (double)alpha_;
     T = T_;
+    nt = (T_ + kWave - 1) / kWave;
     kneg = kneg_;
     const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
@@ -76,9 +78,11 @@ struct SoftFwdSink : SoftCommon {
       const float c = buf[e].c;
 #pragma unroll
       for (int t = 0; t < kSoftTL; ++t) {
-        const float z = (float)(tj[t] - y);
-        const float ex = soft_exp_neg(z, kneg);
-        acc[t] += c * __builtin_amdgcn_rcpf(1.0f + ex);
+        if (t < nt) {  // wave-uniform
+          const float z = (float)(tj[t] - y);
+          const float ex = soft_exp_neg(z, kneg);
+          acc[t] += c * __builtin_amdgcn_rcpf(1.0f + ex);
+        }
       }
     }
   }
@@ -87,10 +91,8 @@ struct SoftFwdSink : SoftCommon {
 struct SoftBwdSink : SoftCommon {
   static constexpr bool kZeroFill = true;
   float a0[kSoftTL], ax[kSoftTL], ay[kSoftTL];
-  const float* tau;  // all thresholds, for the vertex-major loop
-  const float* gup;  // upstream gradient of this item [T] or null (all ones)
-  float* gx;         // grad_X of this item or null
-  bool sums;         // accumulate the sums of Eq. 9 / Eq. 10
+  float gj[kSoftTL];  // upstream gradient at this lane's thresholds (0 beyond T)
+  float* gx;          // grad_X of this item or null
   int W;
   int col0, row0;    // origin of the wave's unit: coordinates are summed relative to it
   float lambda;
@@ -108,35 +110,35 @@ struct SoftBwdSink : SoftCommon {
     }
   }
 
+  // One pass over entries x thresholds serves all three derivatives: lane l holds
+  // sigma'(z) / lambda for its thresholds; the sums over p stay in the lane, the
+  // contraction with the upstream gradient (Eq. 8) is a fixed butterfly over lanes.
   __device__ __forceinline__ void consume(const Entry* buf, int n) {
     const int lane = threadIdx.x & (kWave - 1);
-    if (sums) {
-      for (int e = 0; e < n; ++e) {
-        const double y = buf[e].y;
-        const float c = buf[e].c;
-        const float rx = (float)(buf[e].col - col0), ry = (float)(buf[e].row - row0);
+    for (int e = 0; e < n; ++e) {
+      const double y = buf[e].y;
+      const float c = buf[e].c;
+      const float rx = (float)(buf[e].col - col0), ry = (float)(buf[e].row - row0);
+      float gd = 0.0f;
 #pragma unroll
-        for (int t = 0; t < kSoftTL; ++t) {
+      for (int t = 0; t < kSoftTL; ++t) {
+        if (t < nt) {  // wave-uniform
           const float z = (float)(tj[t] - y);
           const float ex = soft_exp_neg(z, kneg);
           const float s = __builtin_amdgcn_rcpf(1.0f + ex);
-          const float cd = c * (ex * s * s);  // c sigma (1 - sigma)
+          const float d = ex * s * s;  // sigma (1 - sigma)
+          const float cd = c * d;
           a0[t] += cd;
           ax[t] += cd * rx;
           ay[t] += cd * ry;
+          gd += gj[t] * d;
         }
       }
-    }
-    if (gx && lane < n) {  // Eq. 8 contracted with the upstream gradient
-      const Entry en = buf[lane];
-      float acc = 0.0f;
-      for (int j = 0; j < T; ++j) {
-        const float z = (float)((double)tau[j] - en.y);
-        const float ex = soft_exp_neg(z, kneg);
-        const float s = __builtin_amdgcn_rcpf(1.0f + ex);
-        acc += (gup ? gup[j] : 1.0f) * (ex * s * s);
+      if (gx) {  // wave-uniform
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) gd += __shfl_xor(gd, o);
+        if (lane == 0) gx[(int64_t)buf[e].row * W + buf[e].col] = -lambda * c * gd;
       }
-      gx[(int64_t)en.row * W + en.col] = -lambda * en.c * acc;
     }
   }
 };
@@ -197,10 +199,15 @@ __global__ __launch_bounds__(256) void soft2d_bwd_kernel(const float* __restrict
   s.init(u, alpha, tau, T, kneg);
 #pragma unroll
   for (int t = 0; t < kSoftTL; ++t) s.a0[t] = s.ax[t] = s.ay[t] = 0.f;
-  s.tau = tau;
-  s.gup = gup ? gup + (int64_t)blockIdx.y * T : nullptr;
+  {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int t = 0; t < kSoftTL; ++t) {
+      const int j = lane + kWave * t;
+      s.gj[t] = j < T ? (gup ? gup[(int64_t)blockIdx.y * T + j] : 1.0f) : 0.0f;
+    }
+  }
   s.gx = grad_X ? grad_X + (int64_t)blockIdx.y * N : nullptr;
-  s.sums = partial != nullptr;
   s.W = W;
   s.lambda = lambda;
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), units = nstrip * nseg;
@@ -223,40 +230,56 @@ __global__ __launch_bounds__(256) void soft2d_bwd_kernel(const float* __restrict
   }
 }
 
-__global__ void soft2d_fwd_reduce_kernel(const float* __restrict__ partial, int units, int T,
-                                         int64_t total /* batch*T */, float* __restrict__ chi) {
-  const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (k >= total) return;
-  const int64_t item = k / T;
-  const int j = (int)(k - item * T);
-  const float* p = partial + item * units * (int64_t)T + j;
+// Reduction over units: block (x = group of 64 thresholds, y = item); the four
+// waves take units w, w+4, ... in order, then wave 0 adds the four sums in order.
+__global__ __launch_bounds__(256) void soft2d_fwd_reduce_kernel(const float* __restrict__ partial,
+                                                                int units, int T,
+                                                                float* __restrict__ chi) {
+  __shared__ double red[4][kWave];
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+  const int j = blockIdx.x * kWave + lane;
+  const float* p = partial + (int64_t)blockIdx.y * units * T + j;
   double s = 0.0;
-  for (int q = 0; q < units; ++q) s += (double)p[(int64_t)q * T];
-  chi[k] = (float)s;
+  if (j < T)
+    for (int q = wv; q < units; q += 4) s += (double)p[(int64_t)q * T];
+  red[wv][lane] = s;
+  __syncthreads();
+  if (wv == 0 && j < T) chi[(int64_t)blockIdx.y * T + j] = (float)(((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane]);
 }
 
 // dchi_dtau = lambda sum A0;  dchi_du = -alpha lambda sum (origin * A0 + A_xy)
-__global__ void soft2d_bwd_reduce_kernel(const float* __restrict__ partial, int units, int nstrip,
-                                         int rows_per_seg, int T, int64_t total, float alpha, float lambda,
-                                         float* __restrict__ dtau, float* __restrict__ du) {
-  const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (k >= total) return;
-  const int64_t item = k / T;
-  const int j = (int)(k - item * T);
-  const float* p = partial + (item * units * (int64_t)T + j) * 4;
+__global__ __launch_bounds__(256) void soft2d_bwd_reduce_kernel(const float* __restrict__ partial,
+                                                                int units, int nstrip, int rows_per_seg,
+                                                                int T, float alpha, float lambda,
+                                                                float* __restrict__ dtau,
+                                                                float* __restrict__ du) {
+  __shared__ double red[3][4][kWave];
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+  const int j = blockIdx.x * kWave + lane;
+  const float* p = partial + ((int64_t)blockIdx.y * units * T + j) * 4;
   double s0 = 0.0, sx = 0.0, sy = 0.0;
-  for (int q = 0; q < units; ++q) {
-    const float* e = p + (int64_t)q * T * 4;
-    const double ox = (double)((q % nstrip) * kStripOut - kNC), oy = (double)((q / nstrip) * rows_per_seg);
-    const double a0 = (double)e[0];
-    s0 += a0;
-    sx += ox * a0 + (double)e[1];
-    sy += oy * a0 + (double)e[2];
-  }
-  if (dtau) dtau[k] = (float)((double)lambda * s0);
-  if (du) {
-    du[k * 2 + 0] = (float)(-(double)alpha * (double)lambda * sx);
-    du[k * 2 + 1] = (float)(-(double)alpha * (double)lambda * sy);
+  if (j < T)
+    for (int q = wv; q < units; q += 4) {
+      const float4 e = *reinterpret_cast<const float4*>(p + (int64_t)q * T * 4);
+      const double ox = (double)((q % nstrip) * kStripOut - kNC), oy = (double)((q / nstrip) * rows_per_seg);
+      const double a0 = (double)e.x;
+      s0 += a0;
+      sx += ox * a0 + (double)e.y;
+      sy += oy * a0 + (double)e.z;
+    }
+  red[0][wv][lane] = s0;
+  red[1][wv][lane] = sx;
+  red[2][wv][lane] = sy;
+  __syncthreads();
+  if (wv == 0 && j < T) {
+    const int64_t k = (int64_t)blockIdx.y * T + j;
+    double r[3];
+    for (int c = 0; c < 3; ++c) r[c] = ((red[c][0][lane] + red[c][1][lane]) + red[c][2][lane]) + red[c][3][lane];
+    if (dtau) dtau[k] = (float)((double)lambda * r[0]);
+    if (du) {
+      du[k * 2 + 0] = (float)(-(double)alpha * (double)lambda * r[1]);
+      du[k * 2 + 1] = (float)(-(double)alpha * (double)lambda * r[2]);
+    }
   }
 }
 
@@ -280,9 +303,8 @@ void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float 
   float* partial = static_cast<float*>(ws);
   hipLaunchKernelGGL(soft2d_fwd_kernel, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
                      pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), partial);
-  const int64_t total = s.batch * T;
-  hipLaunchKernelGGL(soft2d_fwd_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                     partial, pl.nstrip * pl.nseg, T, total, chi);
+  hipLaunchKernelGGL(soft2d_fwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
+                     dim3(256), 0, st, partial, pl.nstrip * pl.nseg, T, chi);
 }
 
 void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
@@ -294,10 +316,9 @@ void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float 
                      pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), lambda, gup,
                      grad_X, partial);
   if (partial) {
-    const int64_t total = s.batch * T;
-    hipLaunchKernelGGL(soft2d_bwd_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       partial, pl.nstrip * pl.nseg, pl.nstrip, pl.rows_per_seg, T, total, alpha, lambda,
-                       dtau, du);
+    hipLaunchKernelGGL(soft2d_bwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
+                       dim3(256), 0, st, partial, pl.nstrip * pl.nseg, pl.nstrip, pl.rows_per_seg, T, alpha,
+                       lambda, dtau, du);
   }
 }
 

@@ -363,16 +363,18 @@ static Plan2d plan2d(const Shape& s) {
   Plan2d p;
   const int H = (int)s.H, W = (int)s.W;
   p.nstrip = (W + kStripOut - 1) / kStripOut;
-  // enough wave units to fill 256 CUs several times over, segments of >= 32 rows
+  // enough wave units to fill 256 CUs several times over, segments of >= 16 rows
   const int64_t target = 16384;
   int64_t nseg = (target + (int64_t)p.nstrip * s.batch - 1) / ((int64_t)p.nstrip * s.batch);
-  const int64_t max_seg = (H + 31) / 32;
+  const int64_t max_seg = (H + 15) / 16;
   if (nseg > max_seg) nseg = max_seg;
   if (nseg < 1) nseg = 1;
-  // whole chunks of 32 rows per segment; segment + prefetch must stay below 2^31 bytes
-  int64_t rows = ((H + nseg - 1) / nseg + 31) / 32 * 32;
+  // whole chunks per segment; segment + prefetch must stay below 2^31 bytes
+  int64_t rows = (H + nseg - 1) / nseg;
+  const int64_t gran = rows >= 64 ? 32 : kChunkRows;  // long segments amortise their warm-up row
+  rows = (rows + gran - 1) / gran * gran;
   const int64_t row_bytes = (int64_t)W * (int64_t)sizeof(T);
-  const int64_t cap = ((((int64_t)1 << 31) / row_bytes - 16) / 32) * 32;
+  const int64_t cap = ((((int64_t)1 << 31) / row_bytes - 16) / kChunkRows) * kChunkRows;
   if (rows > cap) rows = cap;
   p.rows_per_seg = (int)rows;
   p.nseg = (int)((H + p.rows_per_seg - 1) / p.rows_per_seg);
