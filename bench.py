@@ -1,14 +1,14 @@
 #!/usr/bin/env python3
 """Benchmark of the ECC hot path on one MI355X.
 
-A step is one ecc_hard call (range pass, thresholds, coefficient + histogram
-sweep, merge, scan) over workload C2: a batch of 16 2D 4096x4096 float32
+A step is one ecc_hard call (batch-global range, thresholds, coefficient sweep,
+histogram, merge, scan) over workload C2: a batch of 16 2D 4096x4096 float32
 smoothed Gaussian random fields, 1024 equal-width bins over the batch-global
 [min, max] computed on the device.  Inputs are resident in HBM before the
 timed region.  The same run also times, as extra fields of the one JSON line,
-the 3D 512^3 float32 volume (C4), the hard path with the range supplied, and
-soft forward + backward over the 32 x 512^2 batch (C5), and the CPU oracle on
-the host cores (a baseline, not the target).
+the 3D 512^3 float32 volume (C4), the hard path with the range supplied, the
+two integer workloads (C1, C3), soft forward + backward over the 32 x 512^2
+batch (C5), and the CPU oracle on the host cores (a baseline, not the target).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--quick]
 """
@@ -103,7 +103,7 @@ def main():
             traffic = json.load(open(tpath)).get("c2_sweep_bytes_per_launch")
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                    "kernel": "sweep (coefficient + LDS histogram)", "kernel_ms": round(sweep_ms, 4),
+                    "kernel": "sweep2d_list_kernel (coefficient sweep + range + critical-vertex lists)", "kernel_ms": round(sweep_ms, 4),
                     "launches_timed": nl, "algorithmic_bytes_per_launch": alg_bytes}
         log(f"[bench] C2: {ms:.3f} ms/step, {value:.1f} Gvoxel/s, sweep kernel {sweep_ms:.3f} ms")
         if args.only == "c2":
@@ -161,6 +161,29 @@ def main():
         del g4, X4
         torch.cuda.empty_cache()
 
+    # ---------------- C1 / C3: integer levels, one bin per level ----------------
+    if args.only == "" and not args.quick:
+        for name, X, nd, bins in (("c1", synth.config_c1()[None], 2, 256), ("c3", synth.config_c3()[None], 3, 4096)):
+            if X.dtype == np.uint16:
+                gi = torch.from_numpy(X.view(np.int16)).cuda()
+            else:
+                gi = torch.from_numpy(X).cuda()
+            wsi = torch.empty(api.ecc_workspace_bytes(X.shape[1:], 1, bins), dtype=torch.uint8, device="cuda")
+            cvi = torch.empty((1, bins), dtype=torch.int64, device="cuda")
+            fn = lambda: api.ecc_hard(gi, nd, bins, curve=cvi, workspace=wsi)
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            api.ecc_profile_begin(args.steps)
+            msi = time_steps(fn, args.steps, 0)
+            swi, _ = api.ecc_profile_end()
+            extra[name] = {"workload": {"c1": "C1: 2D 256^2 uint8 i.i.d., 256 levels (launch-latency bound, 3 launches)",
+                                        "c3": "C3: 3D 256^3 uint16 i.i.d., 4096 levels"}[name],
+                           "us_per_step": round(msi * 1e3, 2), "sweep_kernel_us": round(swi * 1e3, 2),
+                           "gvoxel_per_s": round(X.size / msi / 1e6, 2)}
+            log(f"[bench] {name}: {msi * 1e3:.1f} us/step, sweep {swi * 1e3:.1f} us")
+            del gi
+
     # ---------------- C5: soft forward + backward -------------------------------
     if args.only in ("", "c5") and (not args.quick or args.only == "c5"):
         X5 = synth.config_c5()
@@ -205,7 +228,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "C2: hard ECC, batch 16 of 2D 4096x4096 float32 smoothed Gaussian random fields "
                                "(sigma=4 px), 1024 equal-width bins over the batch-global [min,max] found on the "
-                               "device (two read passes)", "bins": BINS, "batch": 16},
+                               "device (single read pass: the sweep tracks the range and lists the critical "
+                               "vertices, which are binned afterwards)", "bins": BINS, "batch": 16},
         "roofline": roofline,
     }
     if not args.quick:
