@@ -108,6 +108,48 @@ def test_repeated_calls_are_identical_and_workspace_reusable():
         np.testing.assert_array_equal(host(api.ecc_hard(g, 3, 128, workspace=ws)), a)
 
 
+def _overflow_flag(ws):
+    # fifth 32-bit word of the workspace header: set by the single-pass sweep when a
+    # critical-vertex list ran out of room (the histogram-mode sweep then redid the work)
+    return int(ws[16:20].cpu().numpy().view(np.uint32)[0])
+
+
+@pytest.mark.parametrize("shape", [(256, 256), (300, 1000), (33, 70, 130), (64, 64, 64)])
+def test_single_pass_overflow_fallback(shape):
+    bins = 100
+    rng = np.random.default_rng(21)
+    rough = rng.standard_normal((2,) + shape).astype(np.float32)   # ~58 % of the vertices critical
+    smooth = np.stack([synth.grf(shape, 3.0, 500 + i) for i in range(2)])  # ~1 %
+    ws = torch.empty(api.ecc_workspace_bytes(shape, 2, bins), dtype=torch.uint8, device="cuda")
+    for X, want_flag in ((rough, 1), (smooth, 0), (rough, 1)):
+        got = host(api.ecc_hard(dev(X), len(shape), bins, workspace=ws))
+        assert _overflow_flag(ws) == want_flag
+        t = O.thresholds_equal_width(X.min(), X.max(), bins)
+        np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, t))
+
+
+@pytest.mark.parametrize("shape", [(70, 300), (9, 40, 130)])
+def test_float_extremes_denormals_and_neighbouring_floats(shape):
+    # the fast sweeps decide "q before p" from the sign of a float difference: that is
+    # exact only with gradual underflow, and must survive overflow of the difference
+    tiny = np.float32(1e-45)  # smallest denormal
+    pool = np.array([0.0, -0.0, tiny, -tiny, 3 * tiny, np.finfo(np.float32).tiny,
+                     np.finfo(np.float32).tiny - tiny, 1.0, np.nextafter(np.float32(1), np.float32(2)),
+                     np.nextafter(np.float32(1), np.float32(0)), -1.0, np.finfo(np.float32).max,
+                     -np.finfo(np.float32).max, 1e38, -1e38], dtype=np.float32)
+    rng = np.random.default_rng(33)
+    X = pool[rng.integers(0, len(pool), size=(2,) + shape)]
+    got = host(api.ecc_coeff(dev(X), len(shape)))
+    for i in range(2):
+        np.testing.assert_array_equal(got[i], OC.coeff(X[i]))
+    for rng_arg in (None, (-2.0, 2.0), (-1e-44, 1e-44)):
+        bins = 64
+        got = host(api.ecc_hard(dev(X), len(shape), bins, range=rng_arg))
+        lo, hi = (X.min(), X.max()) if rng_arg is None else rng_arg
+        t = O.thresholds_equal_width(lo, hi, bins)
+        np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, t), err_msg=str(rng_arg))
+
+
 # ---- the workloads the benchmark times, at full size -------------------------
 
 
