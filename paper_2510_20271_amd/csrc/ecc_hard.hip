@@ -344,7 +344,7 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     hipLaunchKernelGGL(prepare_kernel, dim3(prep_blocks), dim3(kBlock), 0, st, hdr, table, bins, 1, lo, hi,
                        hist, hist_len);
     int64_t parts = 2048 / ((int64_t)kSubLists * s.batch);
-    parts = parts < 1 ? 1 : (parts > 32 ? 32 : parts);
+    parts = parts < 1 ? 1 : (parts > 8 ? 8 : parts);
     hipLaunchKernelGGL(binlist_kernel, dim3(kSubLists * (unsigned)parts, (unsigned)s.batch), dim3(kBlock),
                        (size_t)bins * sizeof(int), st, la, table, bins, hist);
     if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow);

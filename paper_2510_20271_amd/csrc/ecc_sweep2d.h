@@ -203,6 +203,27 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     }
   }
 
+  // Range (single-pass mode).  The smallest vertex of the grid is critical
+  // (c = 1) and so is the largest one unless it lies on the grid's boundary (an
+  // interior vertex with all eight neighbours before it has c = 1 as well), so
+  // the range is taken over the critical vertices and the boundary vertices:
+  // EDGE strips look at all their values, interior strips at the grid's first
+  // and last row here and at the critical vertices where they are pushed.
+  if (Sink::kTrackRange && !EDGE) {
+    if (y0 == 0) {
+      Row t;
+      t.load(rsrc, voff, voff4, 0);
+#pragma unroll
+      for (int e = 0; e < kNC; ++e) range.add(t.value(e, ok));
+    }
+    if (y1 >= H) {
+      Row t;
+      t.load(rsrc, voff, voff4, (unsigned)(H - 1 - ya) * row_bytes);
+#pragma unroll
+      for (int e = 0; e < kNC; ++e) range.add(t.value(e, ok));
+    }
+  }
+
   unsigned wE[kNC], wN[kNC], wNE[kNC], wNW[kNC];
 #pragma unroll
   for (int e = 0; e < kNC; ++e) wE[e] = wN[e] = wNE[e] = wNW[e] = 0;
@@ -212,12 +233,9 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     *reinterpret_cast<float4*>(ring + (slot * kWave + lane) * kNC) =
         make_float4(cur[0], cur[1], cur[2], cur[3]);
     ++slot;
-    if (Sink::kTrackRange) {
+    if (Sink::kTrackRange && EDGE) {
 #pragma unroll
-      for (int e = 0; e < kNC; ++e) {
-        if (EDGE) range.add_if(cur[e], ok[e]);
-        else range.add(cur[e]);
-      }
+      for (int e = 0; e < kNC; ++e) range.add_if(cur[e], ok[e]);
     }
     float dE, dNE, dNW;
     lane_edge_differences(cur[0], cur[kNC - 1], nxt[0], nxt[kNC - 1], dE, dNE, dNW);
@@ -326,6 +344,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
                     (int)((pS >> b) & 1u);
       const int pos = 31 - b;  // column pos / 8, row pos % 8 of the chunk
       const float v = ring[((pos & 7) * kWave + lane) * kNC + (pos >> 3)];
+      if (Sink::kTrackRange && !EDGE) range.add_if(v, active);
       queue.push(active, v, c, c0 + kNC * lane + (pos >> 3), r + (pos & 7));
     }
   }

@@ -197,14 +197,11 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
   const bool out_lane = lane >= 1 && lane <= kOut && x >= 0 && x < W;
   const unsigned voff = (SAFE ? (inb ? (unsigned)x : 0u) : (unsigned)lane) * (unsigned)sizeof(T);
 
-  // resource starts at plane zs = max(z0-1, 0), row 0, column xs (0 for SAFE tubes)
-  const int zs = max(z0 - 1, 0);
+  // The buffer resource is rebuilt for every plane (base: row 0 of the plane,
+  // column xs; column 0 for SAFE tubes), so only one plane has to stay below
+  // 2^31 bytes.  Planes past the end of the item are not read (zero records).
   const int64_t plane = (int64_t)H * W;
-  const int64_t first = (int64_t)zs * plane + (SAFE ? 0 : xs);
-  const int64_t left = (item_elems - first) * (int64_t)sizeof(T);
-  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<T*>(g + first), 0, (int)(left > 0x7fffffff ? 0x7fffffff : left), 0x00020000);
-  const unsigned plane_bytes = (unsigned)(plane * (int64_t)sizeof(T));
+  const T* const item_end = g + item_elems;
   unsigned roff[R + 2];  // byte offset of tube row j inside a plane (clamped into the grid)
   bool rok[R + 2];       // row j is inside the grid
 #pragma unroll
@@ -213,11 +210,14 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
     rok[j] = y >= 0 && y < H;
     roff[j] = (unsigned)min(max(y, 0), H - 1) * (unsigned)W * (unsigned)sizeof(T);
   }
-  unsigned poff = 0;  // byte offset of the next plane to load
+  const T* pnext = g + (int64_t)max(z0 - 1, 0) * plane + (SAFE ? 0 : xs);  // next plane to load
   auto load_plane = [&](T (&raw)[R + 2]) {
+    const int64_t left = (item_end - pnext) * (int64_t)sizeof(T);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<T*>(pnext), 0, (int)(left > 0x7fffffff ? 0x7fffffff : (left > 0 ? left : 0)), 0x00020000);
 #pragma unroll
-    for (int j = 0; j <= R + 1; ++j) raw[j] = Load<T>::get(rsrc, voff, poff + roff[j]);
-    poff += plane_bytes;
+    for (int j = 0; j <= R + 1; ++j) raw[j] = Load<T>::get(rsrc, voff, roff[j]);
+    pnext += plane;
   };
   auto fix = [&](float (&dst)[R + 2], const T (&raw)[R + 2]) {
 #pragma unroll
@@ -334,6 +334,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
     }
     // plane z+i sits at bit n-1-i of every word; the plane below the chunk at bit n of U
     const unsigned planes = (n >= 32) ? 0xffffffffu : ((1u << n) - 1u);
+    const T* const chunk0 = g + (int64_t)z * plane;  // first plane of the chunk (32-bit offsets from here)
 
 #pragma unroll
     for (int j = 1; j <= R; ++j) {
@@ -389,9 +390,8 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
                       4 * (int)((sl.p2 >> b) & 1u) + 8 * (int)((sl.p3 >> b) & 1u);
         const int Q = (int)((sl.q0 >> b) & 1u) + 2 * (int)((sl.q1 >> b) & 1u) +
                       4 * (int)((sl.q2 >> b) & 1u);
-        const int zr = z + (n - 1 - b) - zs;  // plane relative to the resource
-        float val = 0.f;
-        if (active) val = (float)Load<T>::get(rsrc, voff + (unsigned)zr * plane_bytes + roff[j], 0);
+        float val = 0.f;  // the critical vertex's value: re-read, most likely an L2 hit
+        if (active) val = (float)chunk0[(unsigned)(n - 1 - b) * (unsigned)plane + (unsigned)((yb - 1 + j) * W + x)];
         queue.push(active, val, P - Q, 0, 0);
       }
     }
@@ -523,11 +523,8 @@ static Plan3d plan3d(const Shape& s) {
   const int64_t max_seg = (D + s3::kChunk - 1) / s3::kChunk;
   if (nseg > max_seg) nseg = max_seg;
   if (nseg < 1) nseg = 1;
-  // whole chunks per segment; segment + planes in flight must stay below 2^31 bytes
-  int64_t planes = ((D + nseg - 1) / nseg + s3::kChunk - 1) / s3::kChunk * s3::kChunk;
-  const int64_t plane_bytes = (int64_t)H * W * (int64_t)sizeof(T);
-  const int64_t cap = ((((int64_t)1 << 31) / plane_bytes - 6) / s3::kChunk) * s3::kChunk;
-  if (planes > cap) planes = cap;
+  // whole chunks per segment
+  const int64_t planes = ((D + nseg - 1) / nseg + s3::kChunk - 1) / s3::kChunk * s3::kChunk;
   p.planes_per_seg = (int)planes;
   p.nseg = (int)((D + p.planes_per_seg - 1) / p.planes_per_seg);
   const int64_t units = (int64_t)p.nseg * p.nstrip * ngroup4;
@@ -563,9 +560,10 @@ void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, 
 }
 
 bool sweep3d_supported(const Shape& s, int bins) {
-  // a plane must fit 37 times in 2^31 bytes (31-plane chunk + planes in flight), worst element size 4
+  // 32-bit element offsets inside a chunk of up to 31 planes (and so one plane stays far
+  // below the 2^31 bytes a buffer resource can span)
   return bins <= 10240 && s.ndim == 3 && s.D >= 2 && s.W >= 8 && s.W <= (1 << 22) && s.H <= (1 << 22) &&
-         s.H * s.W * 4 * 37 < ((int64_t)1 << 31) && s.D <= (1 << 30);
+         s.H * s.W * 32 < ((int64_t)1 << 32) && s.D <= (1 << 30);
 }
 
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,

@@ -150,6 +150,25 @@ def test_float_extremes_denormals_and_neighbouring_floats(shape):
         np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, t), err_msg=str(rng_arg))
 
 
+def test_3d_planes_beyond_the_32_bit_segment_window():
+    # nine planes of 243 MB: byte offsets inside the one z segment pass 2^31, so the
+    # sweep has to rebase its buffer resource as it marches
+    D, H, W = 9, 7800, 7800
+    rng = np.random.default_rng(8)
+    y = np.sin(np.arange(H, dtype=np.float32) * 0.05)[:, None]
+    x = np.cos(np.arange(W, dtype=np.float32) * 0.03)[None, :]
+    X = np.empty((1, D, H, W), np.float32)
+    for z in range(D):
+        X[0, z] = y * x * np.float32(np.cos(0.7 * z)) + np.float32(0.004) * rng.random((H, W), dtype=np.float32)
+    bins = 300
+    lo, hi = float(X.min()), float(X.max())
+    want = OC.ecc_hard_batch(X, O.thresholds_equal_width(lo, hi, bins))
+    g = dev(X)
+    np.testing.assert_array_equal(host(api.ecc_hard(g, 3, bins)), want)                    # single pass (lists)
+    np.testing.assert_array_equal(host(api.ecc_hard(g, 3, bins, range=(lo, hi))), want)    # histogram mode
+    assert want[0, -1] == 1
+
+
 # ---- the workloads the benchmark times, at full size -------------------------
 
 
