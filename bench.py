@@ -42,12 +42,53 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e3  # ms per step
 
 
+# "New" kernel times of the paper's Tables 1 and 2 (ms, one RTX A6000; dtype, bins and timing
+# method not stated there): context beside the sizes below, not a target.
+PAPER_MS = {(128, 128): 0.0165, (256, 256): 0.0174, (512, 512): 0.021, (1024, 1024): 0.032,
+            (2048, 2048): 0.11, (4096, 4096): 0.408, (8192, 8192): 1.6, (128, 128, 128): 0.1,
+            (256, 256, 256): 0.71, (512, 512, 512): 5.61, (1024, 1024, 1024): 48.47}
+
+
+def run_sweep(args, np, torch, api, synth):
+    """One float32 smoothed random field of each size of the paper's Tables 1-2, 1024 bins over
+    the range found on the device (the whole hot path per call).  The 1024^3 volume is the
+    periodic 512^3 field tiled 2x2x2 (the generator smooths with wrap-around, so the tiling is
+    seamless); exact duplicates across tiles are ties like any other."""
+    rows = []
+    for shape in PAPER_MS:
+        nd = len(shape)
+        if shape == (1024, 1024, 1024):
+            X = np.tile(synth.grf((512, 512, 512), 3.0, 4242), (2, 2, 2))
+        else:
+            X = synth.grf(shape, 4.0 if nd == 2 else 3.0, 4242)
+        g = torch.from_numpy(X[None]).cuda()
+        ws = torch.empty(api.ecc_workspace_bytes(shape, 1, 1024), dtype=torch.uint8, device="cuda")
+        cv = torch.empty((1, 1024), dtype=torch.int64, device="cuda")
+        fn = lambda: api.ecc_hard(g, nd, 1024, curve=cv, workspace=ws)
+        ms = time_steps(fn, args.steps, args.warmup)
+        assert int(cv[0, -1]) == 1  # the full grid is contractible
+        n = int(np.prod(shape))
+        rows.append({"shape": "x".join(map(str, shape)), "ms": round(ms, 4), "gvoxel_per_s": round(n / ms / 1e6, 1),
+                     "paper_ms_rtx_a6000": PAPER_MS[shape]})
+        log(f"[bench] sweep {rows[-1]['shape']:>14}: {ms:8.4f} ms  {rows[-1]['gvoxel_per_s']:8.1f} Gvoxel/s"
+            f"   (paper, RTX A6000: {PAPER_MS[shape]} ms)")
+        del g, ws, cv, X
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "hard_ecc_size_sweep", "unit": "ms", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": "one float32 smoothed random field per size of the paper's "
+                                             "Tables 1-2, 1024 bins, range found on the device"},
+                      "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--quick", action="store_true", help="skip the extra workloads and the CPU baseline")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time one grid of every size of the paper's Tables 1-2 instead (own JSON line)")
     ap.add_argument("--only", default="", help="profiling aid: run only 'c2', 'c4', 'c5' or 'calib' (a plain 1 GiB copy), no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -73,6 +114,9 @@ def main():
         return
     BINS = 1024
     extra = {}
+    if args.sweep:
+        run_sweep(args, np, torch, api, synth)
+        return
 
     # ---------------- C2: the headline workload --------------------------------
     if args.only in ("", "c2"):

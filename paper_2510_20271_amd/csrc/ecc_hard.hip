@@ -150,15 +150,16 @@ __global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, const floa
   for (int b = threadIdx.x; b < bins; b += kBlock) lhist[b] = 0;
   __syncthreads();
   const float lo = la.hdr->lo, scale = la.hdr->scale;
-  // blocks x, x + kSubLists, ... of item y share sub-list x % kSubLists
-  const unsigned sub = blockIdx.y * kSubLists + blockIdx.x % kSubLists;
-  const unsigned part = blockIdx.x / kSubLists, parts = gridDim.x / kSubLists;
-  const float2* list = la.lists + (size_t)sub * la.cap;
-  const unsigned n = min(la.counters[sub], la.cap);
-  for (unsigned i = part * kBlock + threadIdx.x; i < n; i += parts * kBlock) {
-    const float2 e = list[i];
-    const int b = bin_from_table(e.x, table, bins, lo, scale);
-    if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
+  // block x of item y takes the sub-lists x, x + gridDim.x, ...
+  for (unsigned sl = blockIdx.x; sl < la.nsub; sl += gridDim.x) {
+    const unsigned sub = blockIdx.y * la.nsub + sl;
+    const float2* list = la.lists + (size_t)sub * la.cap;
+    const unsigned n = min(la.counters[sub], la.cap);
+    for (unsigned i = threadIdx.x; i < n; i += kBlock) {
+      const float2 e = list[i];
+      const int b = bin_from_table(e.x, table, bins, lo, scale);
+      if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
+    }
   }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
@@ -273,15 +274,22 @@ hipError_t profile_end(float* mean_ms, int* launches) {
 // The lists (single-pass mode for float grids without a range) hold one entry
 // of 8 bytes per critical vertex; room for one vertex in eight.
 static size_t table_bytes(int bins) { return (((size_t)bins * sizeof(float) + 255) / 256) * 256; }
-static size_t counter_bytes(const Shape& s) { return (((size_t)s.batch * kSubLists * 4 + 255) / 256) * 256; }
+// Lists of an item: room for one vertex in eight, split into a power-of-two
+// number of sub-lists of at least kMinSubListCap entries each.
+static unsigned list_nsub(const Shape& s) {
+  unsigned n = kMinSubLists;
+  while (n < kMaxSubLists && s.N / 8 / (2 * n) >= (int64_t)kMinSubListCap) n *= 2;
+  return n;
+}
 static unsigned list_cap(const Shape& s) {  // entries per sub-list
-  int64_t cap = (s.N / 8 / kSubLists + 63) / 64 * 64;
-  if (cap < 256) cap = 256;
+  int64_t cap = (s.N / 8 / list_nsub(s) + 63) / 64 * 64;
+  if (cap < (int64_t)kMinSubListCap) cap = kMinSubListCap;
   if (cap > (int64_t)1 << 30) cap = (int64_t)1 << 30;
   return (unsigned)cap;
 }
+static size_t counter_bytes(const Shape& s) { return (((size_t)s.batch * list_nsub(s) * 4 + 255) / 256) * 256; }
 size_t hard_workspace_bytes(const Shape& s, int bins) {
-  return kTableOffset + table_bytes(bins) + counter_bytes(s) + (size_t)s.batch * kSubLists * list_cap(s) * sizeof(float2);
+  return kTableOffset + table_bytes(bins) + counter_bytes(s) + (size_t)s.batch * list_nsub(s) * list_cap(s) * sizeof(float2);
 }
 
 static int blocks_for(int64_t N) {
@@ -333,19 +341,30 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     la.hdr = hdr;
     la.counters = reinterpret_cast<unsigned*>(wsb + kTableOffset + table_bytes(bins));
     la.lists = reinterpret_cast<float2*>(wsb + kTableOffset + table_bytes(bins) + counter_bytes(s));
+    // no more sub-lists than blocks that append to them (a block uses one sub-list);
+    // the room of the unused ones goes to the others
+    const unsigned blocks = fast2d ? sweep2d_list_blocks(s) : sweep3d_list_blocks(s);
+    la.nsub = list_nsub(s);
     la.cap = list_cap(s);
+    while (la.nsub > kMinSubLists && la.nsub > blocks) {
+      la.nsub /= 2;
+      la.cap *= 2;
+    }
     const float* gf = static_cast<const float*>(grid);
-    hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)((s.batch * kSubLists + 255) / 256)), dim3(256),
-                       0, st, hdr, la.counters, (int)(s.batch * kSubLists));
+    hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)((s.batch * la.nsub + 255) / 256)), dim3(256),
+                       0, st, hdr, la.counters, (int)(s.batch * la.nsub));
     profile_mark(st, false);
     if (fast2d) launch_sweep2d_list(gf, s, la, st);
     else launch_sweep3d_list(gf, s, la, st);
     profile_mark(st, true);
     hipLaunchKernelGGL(prepare_kernel, dim3(prep_blocks), dim3(kBlock), 0, st, hdr, table, bins, 1, lo, hi,
                        hist, hist_len);
-    int64_t parts = 2048 / ((int64_t)kSubLists * s.batch);
-    parts = parts < 1 ? 1 : (parts > 8 ? 8 : parts);
-    hipLaunchKernelGGL(binlist_kernel, dim3(kSubLists * (unsigned)parts, (unsigned)s.batch), dim3(kBlock),
+    // few blocks per item merge into the global histogram (same-address atomics), but
+    // enough of them in all to keep the list reads in flight
+    int64_t nblk = 1024 / s.batch;
+    nblk = nblk < 32 ? 32 : (nblk > 256 ? 256 : nblk);
+    if (nblk > (int64_t)la.nsub) nblk = la.nsub;
+    hipLaunchKernelGGL(binlist_kernel, dim3((unsigned)nblk, (unsigned)s.batch), dim3(kBlock),
                        (size_t)bins * sizeof(int), st, la, table, bins, hist);
     if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow);
     else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow);

@@ -25,9 +25,10 @@ hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_o
 struct HardHeader;
 // single-pass mode: per-item lists of critical vertices (value, c) in the workspace
 struct ListArgs {
-  float2* lists;       // [batch][kSubLists][cap]
-  unsigned* counters;  // [batch][kSubLists]
+  float2* lists;       // [batch][nsub][cap]
+  unsigned* counters;  // [batch][nsub]
   unsigned cap;        // entries per sub-list
+  unsigned nsub;       // sub-lists per item, a power of two
   HardHeader* hdr;
 };
 bool sweep2d_supported(const Shape& s, int bins);
@@ -35,12 +36,14 @@ void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, in
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st, const unsigned* run_if);
 void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st);
+unsigned sweep2d_list_blocks(const Shape& s);  // blocks per item of that launch
 
 bool sweep3d_supported(const Shape& s, int bins);
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st, const unsigned* run_if);
 void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st);
+unsigned sweep3d_list_blocks(const Shape& s);
 
 // ---- sweep-kernel timing (measurement aid) ----------------------------------
 hipError_t profile_begin(int max_launches);

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__
   WaveQueue<ListSink> queue;
   queue.buf = qbuf;
   queue.count = 0;
-  const unsigned sub = blockIdx.y * kSubLists + blockIdx.x % kSubLists;
+  const unsigned sub = blockIdx.y * la.nsub + (blockIdx.x & (la.nsub - 1u));
   queue.sink.list = la.lists + (size_t)sub * la.cap;
   queue.sink.counter = la.counters + sub;
   queue.sink.cap = la.cap;
@@ -90,6 +90,8 @@ void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, 
   hipLaunchKernelGGL((sweep2d_list_kernel<float>), pl.grid, dim3(256), kRingBytes2d, st, grid, (int)s.H,
                      (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la);
 }
+
+unsigned sweep2d_list_blocks(const Shape& s) { return plan2d<float>(s).grid.x; }
 
 bool sweep2d_supported(const Shape& s, int bins) {
   // value ring (32 KiB) + queues (4 KiB) + histogram must fit the 64 KiB of LDS a block may ask for

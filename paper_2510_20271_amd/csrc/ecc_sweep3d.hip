@@ -493,7 +493,7 @@ __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__
   WaveQueue<ListSink> queue;
   queue.buf = qbuf;
   queue.count = 0;
-  const unsigned sub = blockIdx.y * kSubLists + blockIdx.x % kSubLists;
+  const unsigned sub = blockIdx.y * la.nsub + (blockIdx.x & (la.nsub - 1u));
   queue.sink.list = la.lists + (size_t)sub * la.cap;
   queue.sink.counter = la.counters + sub;
   queue.sink.cap = la.cap;
@@ -558,6 +558,8 @@ void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, 
                      (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg,
                      la);
 }
+
+unsigned sweep3d_list_blocks(const Shape& s) { return plan3d<float>(s).grid.x; }
 
 bool sweep3d_supported(const Shape& s, int bins) {
   // 32-bit element offsets inside a chunk of up to 31 planes (and so one plane stays far
