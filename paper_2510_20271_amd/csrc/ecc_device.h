@@ -99,6 +99,19 @@ __device__ __forceinline__ float key_float(unsigned k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
+// Threshold b of B equal-width bins over [lo, hi]: t_b = float32(lo + (b+1)(hi-lo)/B)
+// in float64 with every operation rounded on its own (no contraction), the last
+// one float32(hi); and the factor of the bin guess, B / (hi - lo) (0 when hi <= lo).
+__device__ __forceinline__ float threshold_at(int b, int bins, double lo, double hi) {
+  const double w = __dsub_rn(hi, lo);
+  const double t = __dadd_rn(lo, __ddiv_rn(__dmul_rn((double)(b + 1), w), (double)bins));
+  return (b == bins - 1) ? __double2float_rn(hi) : __double2float_rn(t);
+}
+__device__ __forceinline__ float bin_scale(int bins, double lo, double hi) {
+  const double w = __dsub_rn(hi, lo);
+  return (w > 0.0) ? __double2float_rn(__ddiv_rn((double)bins, w)) : 0.0f;
+}
+
 // bin(x) = min{ b : x <= t_b } on the float32 table; `bins` when x is above
 // every threshold.  The guess comes from float arithmetic, the answer from
 // comparisons with the table only, so it is the same on every machine.

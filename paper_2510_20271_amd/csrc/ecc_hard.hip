@@ -10,6 +10,7 @@
 #include "ecc_device.h"
 #include "ecc_internal.h"
 
+#include <algorithm>
 #include <cstdlib>
 
 namespace ecc {
@@ -19,14 +20,20 @@ constexpr int kBlock = 256;
 // ---------------------------------------------------------------------------
 // range pass
 // ---------------------------------------------------------------------------
-__global__ void init_header_kernel(HardHeader* h, unsigned* counters, int batch) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+// resets the header and the list counters; hist (may be null): zeroed too
+__global__ void init_header_kernel(HardHeader* h, unsigned* counters, int ncounters,
+                                   unsigned long long* hist, int64_t hist_len) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   if (i == 0) {
     h->min_key = 0xffffffffu;
     h->max_key = 0u;
     h->overflow = 0u;
   }
-  if (counters && i < batch) counters[i] = 0u;
+  if (counters)
+    for (int64_t k = i; k < ncounters; k += stride) counters[k] = 0u;
+  if (hist)
+    for (int64_t k = i; k < hist_len; k += stride) hist[k] = 0ull;
 }
 
 __device__ __forceinline__ float wave_min(float v) {
@@ -90,16 +97,11 @@ __global__ void prepare_kernel(HardHeader* h, float* __restrict__ table, int bin
   }
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t b = tid; b < bins; b += stride) {
-    double w = __dsub_rn(hi, lo);
-    double t = __dadd_rn(lo, __ddiv_rn(__dmul_rn((double)(b + 1), w), (double)bins));
-    table[b] = (b == bins - 1) ? __double2float_rn(hi) : __double2float_rn(t);
-  }
+  for (int64_t b = tid; b < bins; b += stride) table[b] = threshold_at((int)b, bins, lo, hi);
   for (int64_t i = tid; i < hist_len; i += stride) hist[i] = 0ull;
   if (tid == 0) {
     h->lo = __double2float_rn(lo);
-    double w = __dsub_rn(hi, lo);
-    h->scale = (w > 0.0) ? __double2float_rn(__ddiv_rn((double)bins, w)) : 0.0f;
+    h->scale = bin_scale(bins, lo, hi);
   }
 }
 
@@ -143,13 +145,30 @@ __global__ __launch_bounds__(kBlock) void sweep_generic_kernel(
 // ---------------------------------------------------------------------------
 // single-pass mode: bin the lists of critical vertices once the range is known
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, const float* __restrict__ table,
-                                                         int bins, unsigned long long* __restrict__ hist) {
-  if (la.hdr->overflow) return;  // the two-pass sweep that follows does the work
+// Every block builds the threshold table from the range the sweep found (LDS);
+// block (0, 0) also leaves it, with the factor of the bin guess, in the
+// workspace for the histogram-mode sweep that runs if a list overflowed.
+__global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, float* __restrict__ table, int bins,
+                                                         unsigned long long* __restrict__ hist) {
   extern __shared__ int lhist[];
-  for (int b = threadIdx.x; b < bins; b += kBlock) lhist[b] = 0;
+  float* ltable = reinterpret_cast<float*>(lhist + bins);
+  const double lo_d = (double)key_float(la.hdr->min_key), hi_d = (double)key_float(la.hdr->max_key);
+  const float lo = __double2float_rn(lo_d), scale = bin_scale(bins, lo_d, hi_d);
+  const bool first = blockIdx.x == 0 && blockIdx.y == 0;
+  const bool overflow = la.hdr->overflow != 0u;  // the two-pass sweep that follows does the work
+  if (overflow && !first) return;
+  for (int b = threadIdx.x; b < bins; b += kBlock) {
+    const float t = threshold_at(b, bins, lo_d, hi_d);
+    ltable[b] = t;
+    lhist[b] = 0;
+    if (first) table[b] = t;
+  }
+  if (first && threadIdx.x == 0) {
+    la.hdr->lo = lo;
+    la.hdr->scale = scale;
+  }
+  if (overflow) return;
   __syncthreads();
-  const float lo = la.hdr->lo, scale = la.hdr->scale;
   // block x of item y takes the sub-lists x, x + gridDim.x, ...
   for (unsigned sl = blockIdx.x; sl < la.nsub; sl += gridDim.x) {
     const unsigned sub = blockIdx.y * la.nsub + sl;
@@ -157,7 +176,7 @@ __global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, const floa
     const unsigned n = min(la.counters[sub], la.cap);
     for (unsigned i = threadIdx.x; i < n; i += kBlock) {
       const float2 e = list[i];
-      const int b = bin_from_table(e.x, table, bins, lo, scale);
+      const int b = bin_from_table(e.x, ltable, bins, lo, scale);
       if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
     }
   }
@@ -351,21 +370,21 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
       la.cap *= 2;
     }
     const float* gf = static_cast<const float*>(grid);
-    hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)((s.batch * la.nsub + 255) / 256)), dim3(256),
-                       0, st, hdr, la.counters, (int)(s.batch * la.nsub));
+    int64_t ib = (std::max<int64_t>(s.batch * la.nsub, hist_len) + 255) / 256;
+    ib = ib > 1024 ? 1024 : ib;
+    hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)ib), dim3(256), 0, st, hdr, la.counters,
+                       (int)(s.batch * la.nsub), hist, hist_len);
     profile_mark(st, false);
     if (fast2d) launch_sweep2d_list(gf, s, la, st);
     else launch_sweep3d_list(gf, s, la, st);
     profile_mark(st, true);
-    hipLaunchKernelGGL(prepare_kernel, dim3(prep_blocks), dim3(kBlock), 0, st, hdr, table, bins, 1, lo, hi,
-                       hist, hist_len);
     // few blocks per item merge into the global histogram (same-address atomics), but
     // enough of them in all to keep the list reads in flight
     int64_t nblk = 1024 / s.batch;
     nblk = nblk < 32 ? 32 : (nblk > 256 ? 256 : nblk);
     if (nblk > (int64_t)la.nsub) nblk = la.nsub;
     hipLaunchKernelGGL(binlist_kernel, dim3((unsigned)nblk, (unsigned)s.batch), dim3(kBlock),
-                       (size_t)bins * sizeof(int), st, la, table, bins, hist);
+                       (size_t)bins * 2 * sizeof(int), st, la, table, bins, hist);
     if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow);
     else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow);
     hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,
@@ -374,7 +393,8 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
   }
 
   if (device_range) {
-    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, st, hdr, (unsigned*)nullptr, 0);
+    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, st, hdr, (unsigned*)nullptr, 0,
+                       (unsigned long long*)nullptr, (int64_t)0);
     int nb = (int)((total / 4 + kBlock - 1) / kBlock);
     nb = nb < 1 ? 1 : (nb > 2048 ? 2048 : nb);
     hipLaunchKernelGGL(minmax_f32_kernel, dim3(nb), dim3(kBlock), 0, st,
