@@ -1,0 +1,80 @@
+"""Differentiable ECC layer over the C ABI (the paper's "differentiable PyTorch layer").
+
+``SoftECCFunction`` is a ``torch.autograd.Function``: forward is ``ecc_soft_fwd`` (Eq. 6),
+backward is ``ecc_soft_bwd`` (Eq. 8-10, appendix on analytical derivatives).  The kernels
+return d chi / d tau and d chi / d u uncontracted ([batch, T] and [batch, T, ndim]); the two
+small contractions with the upstream gradient that autograd needs are the only arithmetic
+done here.  ``SoftECCLayer`` holds the learnable thresholds and a direction kept on the unit
+sphere by reparametrisation (an angle in 2D, two angles in 3D), as the main text suggests.
+
+Inputs must live on the GPU; there is no CPU path.
+"""
+from __future__ import annotations
+
+import math
+
+import torch
+
+from . import api
+
+
+class SoftECCFunction(torch.autograd.Function):
+    """chi[b, j] = sum_p c(p) sigmoid(lambda (tau_j - X_b(p) - alpha <u, p>)), p = (x, y[, z])."""
+
+    @staticmethod
+    def forward(ctx, grid, u, tau, alpha: float, lam: float):
+        ndim = grid.dim() - 1
+        grid_c = grid.detach().contiguous().float()
+        u_c = u.detach().contiguous().float()
+        tau_c = tau.detach().contiguous().float()
+        ctx.save_for_backward(grid_c, u_c, tau_c)
+        ctx.alpha, ctx.lam, ctx.ndim = float(alpha), float(lam), ndim
+        return api.ecc_soft_fwd(grid_c, ndim, u_c, alpha, tau_c, lam)
+
+    @staticmethod
+    def backward(ctx, grad_chi):
+        grid, u, tau = ctx.saved_tensors
+        g = grad_chi.contiguous().float()
+        grad_X, dtau, du = api.ecc_soft_bwd(grid, ctx.ndim, u, ctx.alpha, tau, ctx.lam, grad_chi=g)
+        grad_grid = grad_X if ctx.needs_input_grad[0] else None
+        grad_u = torch.einsum("bj,bjd->d", g, du) if ctx.needs_input_grad[1] else None
+        grad_tau = (g * dtau).sum(0) if ctx.needs_input_grad[2] else None
+        return grad_grid, grad_u, grad_tau, None, None
+
+
+def soft_ecc(grid, u, tau, alpha: float, lam: float):
+    """Functional form: grid [batch, (D,) H, W] float32 on the GPU, u [ndim], tau [T]."""
+    return SoftECCFunction.apply(grid, u, tau, alpha, lam)
+
+
+class SoftECCLayer(torch.nn.Module):
+    """Soft directional ECC with learnable thresholds and direction.
+
+    tau:   T thresholds, initialised evenly over [tau_min, tau_max].
+    theta: the direction's angle(s): u = (cos t, sin t) in 2D; in 3D u = (sin p cos t,
+           sin p sin t, cos p) with theta = (t, p).  ||u|| = 1 by construction.
+    alpha (weight of the tilt) and lam (sharpness of the sigmoid) are fixed.
+    """
+
+    def __init__(self, ndim: int, T: int, tau_min: float, tau_max: float, alpha: float = 0.01,
+                 lam: float = 20.0, theta=None, learn_tau: bool = True, learn_theta: bool = True):
+        super().__init__()
+        if ndim not in (2, 3):
+            raise ValueError("ndim must be 2 or 3")
+        self.ndim, self.alpha, self.lam = ndim, float(alpha), float(lam)
+        tau = torch.linspace(float(tau_min), float(tau_max), T, dtype=torch.float32)
+        if theta is None:
+            theta = [0.3] if ndim == 2 else [0.3, 0.5 * math.pi]
+        theta = torch.as_tensor(theta, dtype=torch.float32).reshape(ndim - 1)
+        self.tau = torch.nn.Parameter(tau, requires_grad=learn_tau)
+        self.theta = torch.nn.Parameter(theta, requires_grad=learn_theta)
+
+    def direction(self) -> torch.Tensor:
+        t = self.theta
+        if self.ndim == 2:
+            return torch.stack([torch.cos(t[0]), torch.sin(t[0])])
+        return torch.stack([torch.sin(t[1]) * torch.cos(t[0]), torch.sin(t[1]) * torch.sin(t[0]),
+                            torch.cos(t[1])])
+
+    def forward(self, grid: torch.Tensor) -> torch.Tensor:
+        return soft_ecc(grid, self.direction(), self.tau, self.alpha, self.lam)
