@@ -74,7 +74,7 @@ def test_direction_gradient_through_the_angle_matches_finite_differences():
         fd = (float(loss_at(0.5 + h)[1]) - float(loss_at(0.5 - h)[1])) / (2 * h)
     assert abs(g - fd) <= 0.05 * max(abs(fd), 1e-6), (g, fd)
     n = m.direction()
-    assert abs(float((n * n).sum()) - 1.0) < 1e-6  # the direction stays on the unit circle
+    assert abs(float((n * n).sum().detach()) - 1.0) < 1e-6  # the direction stays on the unit circle
 
 
 def test_layer_learns_its_thresholds_back():
