@@ -162,11 +162,11 @@ struct HistSink {  // drain target: the block's LDS histogram
 // in the workspace.  A wave reserves n slots with one atomic; when the list is
 // full the overflow flag is raised and the entries are dropped (the caller then
 // runs the two-pass path instead).
-// An item's list is split into sub-lists (32 to 1024 of them, a block appends to
+// An item's list is split into sub-lists (up to 1024 of them, a block appends to
 // sub-list blockIdx.x mod that number): atomics on one address serialise in the
 // L2, and there is one per 64 critical vertices plus one per wave.
-constexpr unsigned kMinSubLists = 32, kMaxSubLists = 1024;
-constexpr unsigned kMinSubListCap = 256;  // entries
+constexpr unsigned kMaxSubLists = 1024;
+constexpr unsigned kMinSubListCap = 256;  // entries (unless the whole item has fewer)
 
 struct ListSink {
   typedef float2 Entry;

@@ -293,16 +293,21 @@ hipError_t profile_end(float* mean_ms, int* launches) {
 // The lists (single-pass mode for float grids without a range) hold one entry
 // of 8 bytes per critical vertex; room for one vertex in eight.
 static size_t table_bytes(int bins) { return (((size_t)bins * sizeof(float) + 255) / 256) * 256; }
-// Lists of an item: room for one vertex in eight, split into a power-of-two
-// number of sub-lists of at least kMinSubListCap entries each.
+// Lists of an item: room for one vertex in eight (for every vertex when the item
+// has fewer than 8192), split into a power-of-two number of sub-lists of at
+// least kMinSubListCap entries each (a single shorter one for tiny items).
+static int64_t list_entries(const Shape& s) {
+  const int64_t all = (s.N + 63) / 64 * 64;
+  const int64_t eighth = s.N / 8;
+  return eighth >= 8192 ? eighth : (all < 8192 ? all : 8192);
+}
 static unsigned list_nsub(const Shape& s) {
-  unsigned n = kMinSubLists;
-  while (n < kMaxSubLists && s.N / 8 / (2 * n) >= (int64_t)kMinSubListCap) n *= 2;
+  unsigned n = 1;
+  while (n < kMaxSubLists && list_entries(s) / (2 * n) >= (int64_t)kMinSubListCap) n *= 2;
   return n;
 }
 static unsigned list_cap(const Shape& s) {  // entries per sub-list
-  int64_t cap = (s.N / 8 / list_nsub(s) + 63) / 64 * 64;
-  if (cap < (int64_t)kMinSubListCap) cap = kMinSubListCap;
+  int64_t cap = (list_entries(s) / list_nsub(s) + 63) / 64 * 64;
   if (cap > (int64_t)1 << 30) cap = (int64_t)1 << 30;
   return (unsigned)cap;
 }
@@ -365,7 +370,7 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     const unsigned blocks = fast2d ? sweep2d_list_blocks(s) : sweep3d_list_blocks(s);
     la.nsub = list_nsub(s);
     la.cap = list_cap(s);
-    while (la.nsub > kMinSubLists && la.nsub > blocks) {
+    while (la.nsub > 1 && la.nsub > blocks) {
       la.nsub /= 2;
       la.cap *= 2;
     }

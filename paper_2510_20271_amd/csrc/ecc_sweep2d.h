@@ -387,7 +387,10 @@ static Plan2d plan2d(const Shape& s) {
   // segments by 5 %: the ragged last round costs more than the extra warm-up rows)
   const int64_t target = 32768;
   int64_t nseg = (target + (int64_t)p.nstrip * s.batch - 1) / ((int64_t)p.nstrip * s.batch);
-  const int64_t max_seg = (H + 15) / 16;
+  // at least 16 rows per segment (24 when that still leaves two rounds of waves: a
+  // segment reads five rows more than it puts out)
+  const int64_t tubes = (int64_t)p.nstrip * s.batch;
+  const int64_t max_seg = tubes * ((H + 23) / 24) >= 8192 ? (H + 23) / 24 : (H + 15) / 16;
   if (nseg > max_seg) nseg = max_seg;
   if (nseg < 1) nseg = 1;
   // whole chunks per segment; segment + prefetch must stay below 2^31 bytes

@@ -169,6 +169,26 @@ def test_3d_planes_beyond_the_32_bit_segment_window():
     assert want[0, -1] == 1
 
 
+@pytest.mark.parametrize("shape", [(3, 5), (4, 8), (2, 3, 9)])
+def test_largest_batch(shape):
+    # 65535 items (the batch rides on the grid's y dimension), tiny grids: one curve each
+    rng = np.random.default_rng(19)
+    X = rng.integers(0, 7, size=(65535,) + shape, dtype=np.uint8)
+    got = host(api.ecc_hard(dev(X), len(shape), 7))
+    np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_levels(7)))
+    Xf = (X.astype(np.float32) - 3) / 2
+    gotf = host(api.ecc_hard(dev(Xf), len(shape), 5))  # batch-global range
+    np.testing.assert_array_equal(gotf, OC.ecc_hard_batch(Xf, O.thresholds_equal_width(Xf.min(), Xf.max(), 5)))
+
+
+def test_one_bin_and_most_bins():
+    X = synth.grf((70, 90), 2.0, 31)[None]
+    for bins in (1, 16384):
+        got = host(api.ecc_hard(dev(X), 2, bins))
+        np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(X.min(), X.max(), bins)))
+        assert got[0, -1] == 1
+
+
 # ---- the workloads the benchmark times, at full size -------------------------
 
 
