@@ -12,10 +12,12 @@ from tests.gpu_util import dev, host
 
 pytestmark = pytest.mark.gpu
 
+# (with the thresholds known up front, inputs of up to 2^16 vertices take the one-thread-per-
+# vertex sweep, larger ones the strip / tube sweeps: both sides of that line are covered)
 SHAPES_2D = [(1, 1), (1, 7), (7, 1), (2, 2), (3, 3), (5, 64), (64, 5), (17, 65), (63, 129), (130, 257),
-             (256, 256), (300, 1000)]
+             (256, 256), (257, 259), (9, 7300), (300, 1000)]
 SHAPES_3D = [(1, 1, 1), (2, 2, 2), (1, 5, 9), (5, 1, 9), (5, 9, 1), (3, 4, 5), (9, 17, 33), (8, 64, 64),
-             (20, 31, 65), (33, 70, 130), (4, 9, 300)]
+             (20, 31, 65), (33, 70, 130), (4, 9, 300), (2, 129, 257), (67, 9, 131), (31, 300, 9)]
 
 
 def _rand(shape, dtype, seed, levels=6):
