@@ -187,6 +187,41 @@ def ecc_hard_batch(Xb: np.ndarray, t: np.ndarray) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
+# directional hard ECC: the curve of the tilted field (Background: the Euler
+# characteristic transform sweeps a shape along directions; Eq. 6 tilts the
+# filtration by alpha <u, p>)
+# ----------------------------------------------------------------------------
+
+
+def tilt_field(X: np.ndarray, u, alpha) -> np.ndarray:
+    """Y(p) = X(p) + alpha <u, p> in float32, p = (x, y[, z]) 0-based with x the
+    fastest axis.  The float32 operations and their order are part of the
+    definition (the order on vertices depends on every rounding):
+        a_d = fl(alpha * u_d);  t = fl(fl(a_x x) + fl(a_y y));  [t = fl(t + fl(a_z z));]
+        Y = fl(X + t).
+    """
+    X = np.asarray(X, dtype=np.float32)
+    u = np.asarray(u, dtype=np.float32)
+    a = (np.float32(alpha) * u).astype(np.float32)
+    nd = X.ndim
+    shape = X.shape
+    xs = np.arange(shape[-1], dtype=np.float32)
+    ys = np.arange(shape[-2], dtype=np.float32)
+    t = (a[0] * xs)[None, :] + (a[1] * ys)[:, None]          # float32 throughout
+    if nd == 3:
+        zs = np.arange(shape[0], dtype=np.float32)
+        t = t[None, :, :] + (a[2] * zs)[:, None, None]
+    assert t.dtype == np.float32
+    return (X + t).astype(np.float32)
+
+
+def ecc_hard_dir(Xb: np.ndarray, U, alpha, t: np.ndarray) -> np.ndarray:
+    """Directional curves [ndir, batch, bins]: hard ECC of the tilted fields."""
+    U = np.asarray(U, dtype=np.float32).reshape(-1, Xb.ndim - 1)
+    return np.stack([np.stack([ecc_hard(tilt_field(x, u, alpha), t) for x in Xb]) for u in U])
+
+
+# ----------------------------------------------------------------------------
 # soft single-direction ECC (Eq. 6) and its derivatives (Eq. 8-10)
 # ----------------------------------------------------------------------------
 

@@ -277,3 +277,54 @@ def test_mid_size_dtypes_and_batch():
     for i in range(2):
         np.testing.assert_array_equal(got[i], O.ecc_cellmax(Xf[i], t))
         np.testing.assert_array_equal(got[i], O.ecc_hard(Xf[i], t))
+
+
+# ---- directional curves (tilted filtration) ----------------------------------
+
+
+def test_tilt_zero_alpha_is_the_plain_curve_and_rounding_is_float32():
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((6, 7)).astype(np.float32)
+    assert np.array_equal(O.tilt_field(X, [0.6, 0.8], 0.0), X)
+    Y = O.tilt_field(X, [0.6, 0.8], 0.25)
+    assert Y.dtype == np.float32
+    # one vertex by hand, every operation rounded to float32
+    a = np.float32(0.25) * np.array([0.6, 0.8], np.float32)
+    want = np.float32(X[4, 5] + np.float32(np.float32(a[0] * np.float32(5)) + np.float32(a[1] * np.float32(4))))
+    assert Y[4, 5] == want
+    Z = rng.standard_normal((3, 4, 5)).astype(np.float32)
+    W = O.tilt_field(Z, [0.1, 0.2, 0.3], 2.0)
+    a = np.float32(2.0) * np.array([0.1, 0.2, 0.3], np.float32)
+    t = np.float32(np.float32(np.float32(a[0] * np.float32(4)) + np.float32(a[1] * np.float32(3))) + np.float32(a[2] * np.float32(2)))
+    assert W[2, 3, 4] == np.float32(Z[2, 3, 4] + t)
+
+
+def test_directional_curve_of_a_flat_grid_is_a_ramp():
+    # X = 0: the tilted field is strictly monotone along every axis, so one vertex
+    # (the corner the direction points away from) carries c = 1 and the curve is 1
+    # from the smallest value on -- for any direction without a zero component
+    for shape, u in (((5, 6), [0.6, -0.8]), ((3, 4, 5), [-0.3, 0.5, 0.8])):
+        X = np.zeros(shape, np.float32)
+        Y = O.tilt_field(X, u, 1.0)
+        c = O.coeff(Y)
+        assert c.sum() == 1 and np.count_nonzero(c) == 1 and c.ravel()[np.argmin(Y)] == 1
+        t = O.thresholds_equal_width(Y.min(), Y.max(), 9)
+        assert np.array_equal(O.ecc_hard_dir(X[None], [u], 1.0, t)[0, 0], np.ones(9, np.int64))
+
+
+def test_directional_curves_match_the_brute_force_count_on_the_tilted_field():
+    rng = np.random.default_rng(11)
+    for shape in ((5, 7), (3, 4, 5)):
+        nd = len(shape)
+        Xb = rng.integers(0, 4, size=(2,) + shape).astype(np.float32)
+        U = rng.standard_normal((3, nd)).astype(np.float32)
+        lo = min(O.tilt_field(x, u, 0.5).min() for x in Xb for u in U)
+        hi = max(O.tilt_field(x, u, 0.5).max() for x in Xb for u in U)
+        t = O.thresholds_equal_width(lo, hi, 13)
+        got = O.ecc_hard_dir(Xb, U, 0.5, t)
+        assert got.shape == (3, 2, 13)
+        for k, u in enumerate(U):
+            for i, x in enumerate(Xb):
+                Y = O.tilt_field(x, u, 0.5)
+                assert np.array_equal(got[k, i], O.ecc_bruteforce(Y, t))
+                assert np.array_equal(got[k, i], O.ecc_cellmax(Y, t))
