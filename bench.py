@@ -89,7 +89,7 @@ def main():
     ap.add_argument("--quick", action="store_true", help="skip the extra workloads and the CPU baseline")
     ap.add_argument("--sweep", action="store_true",
                     help="time one grid of every size of the paper's Tables 1-2 instead (own JSON line)")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'c2', 'c2r' (range supplied), 'c4', 'c5' or 'calib' (a plain 1 GiB copy), no JSON")
+    ap.add_argument("--only", default="", help="profiling aid: run only 'c2', 'c2r' (range supplied), 'c4', 'c5', 'dir' or 'calib' (a plain 1 GiB copy), no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path shards by batch item / "
@@ -233,6 +233,34 @@ def main():
                            "gvoxel_per_s": round(X.size / msi / 1e6, 2)}
             log(f"[bench] {name}: {msi * 1e3:.1f} us/step, sweep {swi * 1e3:.1f} us")
             del gi
+
+    # ---------------- directional curves: 16 directions of one 4096^2 field --------
+    if args.only in ("", "dir") and (not args.quick or args.only == "dir"):
+        Xd = synth.grf((4096, 4096), 4.0, 2002)[None]
+        th = np.linspace(0.0, np.pi, 16, endpoint=False)
+        Ud = np.stack([np.cos(th), np.sin(th)], 1).astype(np.float32)
+        gd, ud = torch.from_numpy(Xd).cuda(), torch.from_numpy(Ud).cuda()
+        wsd = torch.empty(api.ecc_workspace_bytes_dir(Xd.shape[1:], 1, 16, BINS), dtype=torch.uint8, device="cuda")
+        cvd = torch.empty((16, 1, BINS), dtype=torch.int64, device="cuda")
+        fnd = lambda: api.ecc_hard_dir(gd, 2, ud, 1e-4, BINS, curve=cvd, workspace=wsd)
+        for _ in range(args.warmup):
+            fnd()
+        torch.cuda.synchronize()
+        api.ecc_profile_begin(args.steps)
+        msd = time_steps(fnd, args.steps, 0)
+        swd, _ = api.ecc_profile_end()
+        extra["directional"] = {"workload": "16 directions x one 2D 4096^2 float32 GRF (alpha = 1e-4 per pixel), 1024 "
+                                            "bins over the range of all tilted fields, found on the device",
+                                "ms_per_step": round(msd, 4), "sweep_kernel_ms": round(swd, 4),
+                                "gvoxel_per_s": round(16 * Xd.size / msd / 1e6, 1),
+                                "note": "the field (64 MiB) is read once per direction; re-reads are served by "
+                                        "the L2 / Infinity Cache, so vertices/s may pass the HBM roofline of a "
+                                        "single read"}
+        log(f"[bench] directional: {msd:.3f} ms/step (16 x 4096^2), sweep kernel {swd:.3f} ms")
+        del gd, Xd
+        torch.cuda.empty_cache()
+        if args.only == "dir":
+            return
 
     # ---------------- C5: soft forward + backward -------------------------------
     if args.only in ("", "c5") and (not args.quick or args.only == "c5"):

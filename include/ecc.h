@@ -136,6 +136,28 @@ int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Directional hard curves (Background: the Euler characteristic transform looks at
+ * a shape along directions; Eq. 6 tilts the filtration by alpha <u, p>).  For
+ * every direction u_k the field
+ *     Y_k(p) = X(p) + t_k(p),   p = (x, y[, z]) 0-based, x the fastest axis,
+ *     t_k = fl(fl(fl(a_x x) + fl(a_y y)) + fl(a_z z))   (last term in 3D only),
+ *     a_d = fl(alpha u_kd),
+ * is formed in float32 -- every operation rounded to float32 in exactly this
+ * order, the order on the vertices depends on it -- and its hard ECC taken
+ * as in ecc_hard (Eq. 3): the coefficient c(p) is the one of the tilted field.
+ *   grid   device float32 [batch][D][H][W]
+ *   u      device float32 [ndir][ndim]   (used as given; the caller normalises)
+ *   range  host [lo, hi] or NULL: the min / max over all directions and items
+ *   curve  device int64 out [ndir][batch][bins]
+ *   ndir * batch <= 65535; workspace of ecc_workspace_bytes_dir() bytes.
+ * Other arguments, ownership, errors: as ecc_hard.
+ */
+size_t ecc_workspace_bytes_dir(int ndim, const int64_t* dims, int64_t batch, int ndir, int bins);
+int ecc_hard_dir(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u, int ndir,
+                 float alpha, int bins, const double* range, int64_t* curve, void* workspace,
+                 size_t workspace_bytes, void* hip_stream);
+
+/*
  * Measurement aid (not part of the method; Experiments section reports
  * "kernel execution times"): between ecc_profile_begin() and
  * ecc_profile_end() every ecc_hard call records a pair of HIP events around

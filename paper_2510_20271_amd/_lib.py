@@ -28,6 +28,11 @@ SIGNATURES = {
     "ecc_soft_bwd": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp,
                                     ctypes.c_float, c_vp, ctypes.c_int, ctypes.c_float, c_vp, c_vp,
                                     c_vp, c_vp, c_vp, ctypes.c_size_t, c_vp]),
+    "ecc_workspace_bytes_dir": (ctypes.c_size_t, [ctypes.c_int, ctypes.POINTER(c_i64), c_i64, ctypes.c_int,
+                                                  ctypes.c_int]),
+    "ecc_hard_dir": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp, ctypes.c_int,
+                                    ctypes.c_float, ctypes.c_int, ctypes.POINTER(ctypes.c_double), c_vp, c_vp,
+                                    ctypes.c_size_t, c_vp]),
     "ecc_profile_begin": (ctypes.c_int, [ctypes.c_int]),
     "ecc_profile_end": (ctypes.c_int, [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]),
 }

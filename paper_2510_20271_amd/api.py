@@ -78,6 +78,35 @@ def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, w
     return curve
 
 
+def ecc_workspace_bytes_dir(item_shape, batch: int, ndir: int, bins: int) -> int:
+    return int(_lib.load().ecc_workspace_bytes_dir(len(item_shape), _dims(item_shape), batch, ndir, bins))
+
+
+def ecc_hard_dir(grid: torch.Tensor, ndim: int, u: torch.Tensor, alpha: float, bins: int, range=None,
+                 curve=None, workspace=None):
+    """Directional curves: grid [batch, (D,) H, W] float32, u [ndir, ndim] float32, both on the
+    device.  Returns the int64 curves [ndir, batch, bins] of the tilted fields."""
+    _need_device(grid, u, curve, workspace)
+    if grid.dim() != ndim + 1 or u.dim() != 2 or u.shape[1] != ndim:
+        raise ValueError("grid must be [batch, *item_shape] and u [ndir, ndim]")
+    if grid.dtype != torch.float32 or u.dtype != torch.float32:
+        raise ValueError("grid and u must be float32")
+    batch, item = grid.shape[0], tuple(grid.shape[1:])
+    ndir = u.shape[0]
+    if curve is None:
+        curve = torch.empty((ndir, batch, bins), dtype=torch.int64, device=grid.device)
+    if workspace is None:
+        need = ecc_workspace_bytes_dir(item, batch, ndir, bins)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=grid.device)
+    rng = None
+    if range is not None:
+        rng = (ctypes.c_double * 2)(float(range[0]), float(range[1]))
+    _check(_lib.load().ecc_hard_dir(_ptr(grid), ndim, _dims(item), batch, _ptr(u.contiguous()), ndir,
+                                    float(alpha), bins, rng, _ptr(curve), _ptr(workspace), workspace.numel(),
+                                    _stream()))
+    return curve
+
+
 def ecc_coeff(grid: torch.Tensor, ndim: int, c_out=None):
     _need_device(grid, c_out)
     batch, item = grid.shape[0], tuple(grid.shape[1:])

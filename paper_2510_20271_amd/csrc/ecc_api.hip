@@ -132,6 +132,54 @@ int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, int
                        "ecc_hard");
 }
 
+size_t ecc_workspace_bytes_dir(int ndim, const int64_t* dims, int64_t batch, int ndir, int bins) {
+  ecc::Shape s;
+  if (make_shape(ndim, dims, batch, &s) != ECC_OK) return 0;
+  if (bins < 1 || ndir < 1 || (int64_t)ndir * batch > kMaxBatch) {
+    fail(ECC_ERR_INVALID_ARG, "bins and ndir must be >= 1 and ndir * batch <= %lld", (long long)kMaxBatch);
+    return 0;
+  }
+  s.batch = (int64_t)ndir * batch;
+  return ecc::hard_dir_workspace_bytes(s, bins);
+}
+
+int ecc_hard_dir(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u, int ndir,
+                 float alpha, int bins, const double* range, int64_t* curve, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  ecc::Shape s;
+  int rc = make_shape(ndim, dims, batch, &s);
+  if (rc != ECC_OK) return rc;
+  if (!grid) return fail(ECC_ERR_INVALID_ARG, "grid is NULL");
+  if (!u) return fail(ECC_ERR_INVALID_ARG, "u is NULL");
+  if (!curve) return fail(ECC_ERR_INVALID_ARG, "curve is NULL");
+  if (ndir < 1) return fail(ECC_ERR_INVALID_ARG, "ndir must be >= 1, got %d", ndir);
+  if ((int64_t)ndir * batch > kMaxBatch)
+    return fail(ECC_ERR_UNSUPPORTED, "ndir * batch = %lld exceeds %lld", (long long)ndir * (long long)batch,
+                (long long)kMaxBatch);
+  if (!std::isfinite(alpha)) return fail(ECC_ERR_INVALID_ARG, "alpha must be finite");
+  if (bins < 1) return fail(ECC_ERR_INVALID_ARG, "bins must be >= 1, got %d", bins);
+  if (bins > ECC_MAX_BINS)
+    return fail(ECC_ERR_UNSUPPORTED, "bins %d exceeds ECC_MAX_BINS %d", bins, ECC_MAX_BINS);
+  double lo = 0.0, hi = 0.0;
+  if (range) {
+    lo = range[0];
+    hi = range[1];
+    if (!std::isfinite(lo) || !std::isfinite(hi) || lo > hi)
+      return fail(ECC_ERR_INVALID_ARG, "range must be finite with lo <= hi");
+  }
+  if (reinterpret_cast<uintptr_t>(grid) % 4 || reinterpret_cast<uintptr_t>(u) % 4)
+    return fail(ECC_ERR_INVALID_ARG, "grid / u is not 4-byte aligned");
+  if (reinterpret_cast<uintptr_t>(curve) % 8)
+    return fail(ECC_ERR_INVALID_ARG, "curve is not 8-byte aligned");
+  ecc::Shape sv = s;
+  sv.batch = (int64_t)ndir * batch;
+  if ((rc = check_workspace(workspace, workspace_bytes, ecc::hard_dir_workspace_bytes(sv, bins))) != ECC_OK)
+    return rc;
+  return device_status(ecc::launch_hard_dir(grid, sv, u, alpha, (int)batch, bins, range != nullptr, lo, hi,
+                                            curve, workspace, static_cast<hipStream_t>(hip_stream)),
+                       "ecc_hard_dir");
+}
+
 int ecc_coeff(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype,
               int8_t* c_out, void* hip_stream) {
   ecc::Shape s;

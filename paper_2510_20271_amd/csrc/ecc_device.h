@@ -126,6 +126,45 @@ __device__ __forceinline__ int bin_from_table(float x, const float* __restrict__
 
 template <typename T> __device__ __forceinline__ float as_float(T v) { return (float)v; }
 
+// ---- tilted filtration (directional curves) ------------------------------------
+// The sweeps can add a linear function of the vertex's coordinates to the field as
+// they load it: Y(p) = X(p) + t(p), t = fl(fl(fl(a_x x) + fl(a_y y)) + fl(a_z z))
+// (the last term in 3D only), a_d = fl(alpha u_d), every operation a float32 one
+// in this order.  A launch then runs over directions x batch items: blockIdx.y =
+// direction * batch + item.
+// float32 product / sum rounded on their own: never contracted into an fma with a
+// neighbouring operation (the tilt's rounding sequence is part of its definition)
+__device__ __forceinline__ float mul_rn(float a, float b) {
+#pragma clang fp contract(off)
+  return a * b;
+}
+__device__ __forceinline__ float add_rn(float a, float b) {
+#pragma clang fp contract(off)
+  return a + b;
+}
+
+struct NoTilt {
+  static constexpr bool kOn = false;
+  float ax, ay, az;
+};
+struct Tilt {
+  static constexpr bool kOn = true;
+  float ax, ay, az;
+};
+struct DirArgs {
+  const float* u;  // device [ndir][ndim]
+  float alpha;
+  int batch;       // items per direction
+  int ndim;
+};
+__device__ __forceinline__ Tilt load_tilt(const DirArgs& d, int dir) {
+  Tilt t;
+  t.ax = mul_rn(d.alpha, d.u[dir * d.ndim]);
+  t.ay = mul_rn(d.alpha, d.u[dir * d.ndim + 1]);
+  t.az = d.ndim == 3 ? mul_rn(d.alpha, d.u[dir * d.ndim + 2]) : 0.0f;
+  return t;
+}
+
 // ---- critical-vertex queue of a wave ----------------------------------------
 // Critical vertices (c != 0) turn up a few lanes at a time.  Instead of running
 // the binning code with most lanes idle, a wave appends (value, c) to a small

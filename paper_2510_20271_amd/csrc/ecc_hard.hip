@@ -337,7 +337,7 @@ static void launch_sweep_generic(const void* grid, const Shape& s, bool levels, 
 }
 
 hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
-                       double lo, double hi, int64_t* curve, void* ws, hipStream_t st) {
+                       double lo, double hi, int64_t* curve, void* ws, hipStream_t st, const DirArgs* dir) {
   HardHeader* hdr = static_cast<HardHeader*>(ws);
   char* wsb = static_cast<char*>(ws);
   float* table = reinterpret_cast<float*>(wsb + kTableOffset);
@@ -354,13 +354,14 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
   // the one-thread-per-vertex sweep: a strip / tube wave marching alone is bound by its own
   // instruction latency (256^2 uint8: 11.7 against 19.5 us).
   const bool tiny = !device_range && total <= (1 << 16);
-  const bool fast2d = !force_generic && !tiny && sweep2d_supported(s, bins);
-  const bool fast3d = !force_generic && !tiny && !fast2d && sweep3d_supported(s, bins);
+  // (a directional call comes here only for shapes the strip / tube sweeps take)
+  const bool fast2d = (dir || (!force_generic && !tiny)) && sweep2d_supported(s, bins);
+  const bool fast3d = (dir || (!force_generic && !tiny)) && !fast2d && sweep3d_supported(s, bins);
   const int64_t hist_len = s.batch * bins;
   int prep_blocks = (int)((hist_len + kBlock - 1) / kBlock);
   prep_blocks = prep_blocks > 1024 ? 1024 : prep_blocks;
 
-  if (device_range && (fast2d || fast3d) && !two_pass) {
+  if (device_range && (fast2d || fast3d) && (!two_pass || dir)) {
     // Single pass over the grid: the sweep finds the critical vertices and the
     // range together; the few critical vertices are binned afterwards.  If a list
     // overflows (more than one vertex in eight critical), the histogram-mode sweep
@@ -384,8 +385,8 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)ib), dim3(256), 0, st, hdr, la.counters,
                        (int)(s.batch * la.nsub), hist, hist_len);
     profile_mark(st, false);
-    if (fast2d) launch_sweep2d_list(gf, s, la, st);
-    else launch_sweep3d_list(gf, s, la, st);
+    if (fast2d) launch_sweep2d_list(gf, s, la, st, dir);
+    else launch_sweep3d_list(gf, s, la, st, dir);
     profile_mark(st, true);
     // few blocks per item merge into the global histogram (same-address atomics), but
     // enough of them in all to keep the list reads in flight
@@ -394,8 +395,8 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     if (nblk > (int64_t)la.nsub) nblk = la.nsub;
     hipLaunchKernelGGL(binlist_kernel, dim3((unsigned)nblk, (unsigned)s.batch), dim3(kBlock),
                        (size_t)bins * 2 * sizeof(int), st, la, table, bins, hist);
-    if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow);
-    else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow);
+    if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir);
+    else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir);
     hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,
                        reinterpret_cast<long long*>(curve), bins);
     return hipGetLastError();
@@ -413,9 +414,9 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
                      device_range ? 1 : 0, lo, hi, hist, hist_len);
   profile_mark(st, false);
   if (fast2d) {
-    launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr);
+    launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir);
   } else if (fast3d) {
-    launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr);
+    launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir);
   } else
   switch (dtype) {
     case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;
@@ -426,6 +427,56 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
   hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,
                      reinterpret_cast<long long*>(curve), bins);
   return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// directional curves: hard ECC of the tilted fields X + alpha <u_k, p>
+// ---------------------------------------------------------------------------
+// Shapes the strip / tube sweeps do not take: the tilted fields are written out
+// (one per direction and item) and go through the plain path.
+__global__ __launch_bounds__(kBlock) void tilt_kernel(const float* __restrict__ grid, int64_t D, int64_t H,
+                                                      int64_t W, int64_t N, DirArgs dir,
+                                                      float* __restrict__ out) {
+  const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
+  const Tilt t = load_tilt(dir, d);
+  const float* g = grid + (int64_t)item * N;
+  float* o = out + (int64_t)blockIdx.y * N;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < N; i += stride) {
+    const int64_t x = i % W, r = i / W, y = r % H, z = r / H;
+    float tt = add_rn(mul_rn(t.ax, (float)x), mul_rn(t.ay, (float)y));
+    if (dir.ndim == 3) tt = add_rn(tt, mul_rn(t.az, (float)z));
+    o[i] = add_rn(g[i], tt);
+  }
+}
+
+static bool dir_fused(const Shape& sv, int bins, bool have_range) {
+  const bool tiny = have_range && sv.N * sv.batch <= (1 << 16);
+  return !tiny && (sweep2d_supported(sv, bins) || sweep3d_supported(sv, bins));
+}
+
+// sv: the shape with batch = directions x items
+size_t hard_dir_workspace_bytes(const Shape& sv, int bins) {
+  size_t n = hard_workspace_bytes(sv, bins);
+  if (!dir_fused(sv, bins, true) || !dir_fused(sv, bins, false))
+    n += (((size_t)sv.N * sv.batch * sizeof(float) + 255) / 256) * 256;
+  return n;
+}
+
+hipError_t launch_hard_dir(const float* grid, const Shape& sv, const float* u, float alpha, int batch,
+                           int bins, bool have_range, double lo, double hi, int64_t* curve, void* ws,
+                           hipStream_t st) {
+  DirArgs dir;
+  dir.u = u;
+  dir.alpha = alpha;
+  dir.batch = batch;
+  dir.ndim = sv.ndim;
+  if (dir_fused(sv, bins, have_range))
+    return launch_hard(grid, sv, 2, bins, have_range, lo, hi, curve, ws, st, &dir);
+  float* tilted = reinterpret_cast<float*>(static_cast<char*>(ws) + hard_workspace_bytes(sv, bins));
+  hipLaunchKernelGGL(tilt_kernel, dim3(blocks_for(sv.N), (unsigned)sv.batch), dim3(kBlock), 0, st, grid, sv.D,
+                     sv.H, sv.W, sv.N, dir, tilted);
+  return launch_hard(tilted, sv, 2, bins, have_range, lo, hi, curve, ws, st, nullptr);
 }
 
 hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st) {

@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256) void soft2d_fwd_kernel(const float* __restrict
 #pragma unroll
   for (int t = 0; t < kSoftTL; ++t) queue.sink.acc[t] = 0.f;
   WaveRange range;
-  sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range);
+  sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range, NoTilt());
   const int unit = blockIdx.x * 4 + (threadIdx.x >> 6), units = nstrip * nseg;
   if (unit < units) {
     float* out = partial + ((int64_t)blockIdx.y * units + unit) * T;
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256) void soft2d_bwd_kernel(const float* __restrict
   s.col0 = (unit % nstrip) * kStripOut - kNC;
   s.row0 = (unit / nstrip) * rows_per_seg;
   WaveRange range;
-  sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range);
+  sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range, NoTilt());
   if (partial && unit < units) {
     float* out = partial + ((int64_t)blockIdx.y * units + unit) * (int64_t)T * 4;
     const int lane = threadIdx.x & (kWave - 1);

@@ -157,10 +157,14 @@ template <typename T> struct RowRegs<T, true> {
 // of the previous chunk's words (one warm-up step on row y0-1 provides them
 // for the first chunk; above the grid they are all ones, i.e. "never before
 // p" once complemented).
-template <typename T, typename Sink, bool EDGE>
+//
+// Tilt: the field swept is Y(p) = X(p) + t(p) with t = fl(fl(a_x x) + fl(a_y y)),
+// every operation a float32 one in this order (directional curves; NoTilt: Y = X).
+template <typename T, typename Sink, bool EDGE, typename Tilt>
 __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t item_elems, int H, int W,
                                             int c0, int y0, int y1, WaveQueue<Sink>& queue,
-                                            float* ring /* [kChunkRows][64][kNC] */, WaveRange& range) {
+                                            float* ring /* [kChunkRows][64][kNC] */, WaveRange& range,
+                                            const Tilt& tilt) {
   const int lane = threadIdx.x & (kWave - 1);
   bool ok[kNC];         // column inside the grid
   unsigned voff[kNC];   // byte offset of the column inside a row (clamped into the row)
@@ -183,8 +187,19 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
   unsigned soff = 0;  // byte offset of the next row to load
 
   typedef RowRegs<T, EDGE> Row;
+  // value of column e of a loaded row, which is row y of the grid
+  float lx[kNC];  // the column's share of the tilt (zero made +0: equal values must differ by +0)
+#pragma unroll
+  for (int e = 0; e < kNC; ++e)
+    lx[e] = Tilt::kOn ? add_rn(mul_rn(tilt.ax, (float)(c0 + kNC * lane + e)), 0.0f) : 0.0f;
+  auto value_at = [&](const Row& r, int e, int y) -> float {
+    const float f = r.value(e, ok);
+    if (!Tilt::kOn) return f;
+    return add_rn(f, add_rn(lx[e], mul_rn(tilt.ay, (float)y)));
+  };
   Row pf[kPF];
   float cur[kNC], nxt[kNC];
+  int yn = ya + 2;  // row of the grid that becomes nxt at the next step
   {
     Row a, b;
     a.load(rsrc, voff, voff4, soff);
@@ -198,8 +213,8 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     }
 #pragma unroll
     for (int e = 0; e < kNC; ++e) {
-      cur[e] = a.value(e, ok);
-      nxt[e] = b.value(e, ok);
+      cur[e] = value_at(a, e, ya);
+      nxt[e] = value_at(b, e, ya + 1);
     }
   }
 
@@ -214,13 +229,13 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
       Row t;
       t.load(rsrc, voff, voff4, 0);
 #pragma unroll
-      for (int e = 0; e < kNC; ++e) range.add(t.value(e, ok));
+      for (int e = 0; e < kNC; ++e) range.add(value_at(t, e, 0));
     }
     if (y1 >= H) {
       Row t;
       t.load(rsrc, voff, voff4, (unsigned)(H - 1 - ya) * row_bytes);
 #pragma unroll
-      for (int e = 0; e < kNC; ++e) range.add(t.value(e, ok));
+      for (int e = 0; e < kNC; ++e) range.add(value_at(t, e, H - 1));
     }
   }
 
@@ -249,8 +264,9 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 #pragma unroll
     for (int e = 0; e < kNC; ++e) {
       cur[e] = nxt[e];
-      nxt[e] = pf[0].value(e, ok);
+      nxt[e] = value_at(pf[0], e, yn);
     }
+    ++yn;
 #pragma unroll
     for (int q = 0; q + 1 < kPF; ++q) pf[q] = pf[q + 1];
     pf[kPF - 1].load(rsrc, voff, voff4, soff);
@@ -353,10 +369,10 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 
 // Work unit of a wave: (segment of rows) x (strip of columns) of one item;
 // blockIdx.y is the item, the four waves of a block take adjacent strips.
-template <typename T, typename Sink>
+template <typename T, typename Sink, typename Tilt>
 __device__ __forceinline__ void sweep2d_wave(const T* __restrict__ g, int H, int W, int64_t N, int nstrip,
                                              int nseg, int rows_per_seg, WaveQueue<Sink>& queue, float* ring,
-                                             WaveRange& range) {
+                                             WaveRange& range, const Tilt& tilt) {
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform
   if (unit < nstrip * nseg) {
     const int seg = unit / nstrip, strip = unit - seg * nstrip;
@@ -367,9 +383,9 @@ __device__ __forceinline__ void sweep2d_wave(const T* __restrict__ g, int H, int
     const bool edge = (c0 < 0) || (c0 + kNC * kWave > W) || (W % kNC != 0) ||
                       ((reinterpret_cast<uintptr_t>(g) & (kNC * sizeof(T) - 1)) != 0);
     if (edge)
-      sweep_strip<T, Sink, true>(g, N, H, W, c0, y0, y1, queue, ring, range);
+      sweep_strip<T, Sink, true>(g, N, H, W, c0, y0, y1, queue, ring, range, tilt);
     else
-      sweep_strip<T, Sink, false>(g, N, H, W, c0, y0, y1, queue, ring, range);
+      sweep_strip<T, Sink, false>(g, N, H, W, c0, y0, y1, queue, ring, range, tilt);
   }
 }
 

@@ -1,16 +1,19 @@
 // Hard ECC, 2D: kernels and launchers around the strip sweep of ecc_sweep2d.h.
 #include "ecc_sweep2d.h"
 
+#include <type_traits>
+
 namespace ecc {
 
 // Histogram mode: critical vertices are binned into the block's LDS histogram,
 // which is merged into the global one at the end.  run_if (may be null): the
 // kernel does nothing unless *run_if != 0 (fallback of the single-pass mode).
-template <typename T, bool LEVELS, bool TLDS>
+// TILT: a directional launch (blockIdx.y = direction * batch + item, tilted field).
+template <typename T, bool LEVELS, bool TLDS, bool TILT>
 __global__ __launch_bounds__(256) void sweep2d_kernel(
     const T* __restrict__ grid, int H, int W, int64_t N, int bins, int nstrip, int nseg, int rows_per_seg,
     const HardHeader* __restrict__ hdr, const float* __restrict__ table,
-    unsigned long long* __restrict__ hist, const unsigned* __restrict__ run_if) {
+    unsigned long long* __restrict__ hist, const unsigned* __restrict__ run_if, DirArgs dir) {
   if (run_if && *run_if == 0) return;
   extern __shared__ int smem[];
   // [4 waves][kChunkRows][64][kNC] floats of value ring, [4 waves] queues, histogram, table
@@ -33,7 +36,14 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
   queue.sink.lo = LEVELS ? 0.f : hdr->lo;
   queue.sink.scale = LEVELS ? 0.f : hdr->scale;
   WaveRange range;
-  sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range);
+  if constexpr (TILT) {
+    const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
+    sweep2d_wave<T>(grid + (int64_t)item * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                    load_tilt(dir, d));
+  } else {
+    sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                    NoTilt());
+  }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
   for (int b = threadIdx.x; b < bins; b += 256) {
@@ -45,10 +55,10 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
 // Single-pass mode: critical vertices (value, c) go to the item's list in the
 // workspace and the wave's min / max to the header; the bins are assigned later,
 // once the batch-global range is known.
-template <typename T>
+template <typename T, bool TILT>
 __global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__ grid, int H, int W,
                                                            int64_t N, int nstrip, int nseg,
-                                                           int rows_per_seg, ListArgs la) {
+                                                           int rows_per_seg, ListArgs la, DirArgs dir) {
   extern __shared__ int smem[];
   const int wv = threadIdx.x >> 6;
   float* ring = reinterpret_cast<float*>(smem) + wv * (kChunkRows * kWave * kNC);
@@ -62,7 +72,14 @@ __global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__
   queue.sink.cap = la.cap;
   queue.sink.overflow = &la.hdr->overflow;
   WaveRange range;
-  sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range);
+  if constexpr (TILT) {
+    const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
+    sweep2d_wave<T>(grid + (int64_t)item * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                    load_tilt(dir, d));
+  } else {
+    sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                    NoTilt());
+  }
   range.commit(la.hdr);
 }
 
@@ -71,24 +88,39 @@ constexpr size_t kRingBytes2d = ring_bytes2d<float2>();
 template <typename T>
 static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
                        const float* table, unsigned long long* hist, hipStream_t st,
-                       const unsigned* run_if) {
+                       const unsigned* run_if, const DirArgs* dir) {
   const Plan2d pl = plan2d<T>(s);
   const bool tlds = !levels && (size_t)bins * 8 + kRingBytes2d <= 64 * 1024;
   const size_t lds = kRingBytes2d + (size_t)bins * (tlds ? 8 : 4);
   const T* p = static_cast<const T*>(grid);
-#define ECC_GO(LV, TL)                                                                              \
-  hipLaunchKernelGGL((sweep2d_kernel<T, LV, TL>), pl.grid, dim3(256), lds, st, p, (int)s.H, (int)s.W, \
-                     s.N, bins, pl.nstrip, pl.nseg, pl.rows_per_seg, hdr, table, hist, run_if)
-  if (levels) ECC_GO(true, false);
-  else if (tlds) ECC_GO(false, true);
-  else ECC_GO(false, false);
+  const DirArgs none = {nullptr, 0.f, 1, 2};
+#define ECC_GO(LV, TL, TI)                                                                                \
+  hipLaunchKernelGGL((sweep2d_kernel<T, LV, TL, TI>), pl.grid, dim3(256), lds, st, p, (int)s.H, (int)s.W, \
+                     s.N, bins, pl.nstrip, pl.nseg, pl.rows_per_seg, hdr, table, hist, run_if,           \
+                     dir ? *dir : none)
+  if constexpr (std::is_same<T, float>::value) {
+    if (dir) {  // directional call: float grids, thresholds from a range
+      if (tlds) ECC_GO(false, true, true);
+      else ECC_GO(false, false, true);
+      return;
+    }
+  }
+  if (levels) ECC_GO(true, false, false);
+  else if (tlds) ECC_GO(false, true, false);
+  else ECC_GO(false, false, false);
 #undef ECC_GO
 }
 
-void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st) {
+void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
+                         const DirArgs* dir) {
   const Plan2d pl = plan2d<float>(s);
-  hipLaunchKernelGGL((sweep2d_list_kernel<float>), pl.grid, dim3(256), kRingBytes2d, st, grid, (int)s.H,
-                     (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la);
+  if (dir)
+    hipLaunchKernelGGL((sweep2d_list_kernel<float, true>), pl.grid, dim3(256), kRingBytes2d, st, grid,
+                       (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la, *dir);
+  else
+    hipLaunchKernelGGL((sweep2d_list_kernel<float, false>), pl.grid, dim3(256), kRingBytes2d, st, grid,
+                       (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la,
+                       DirArgs{nullptr, 0.f, 1, 2});
 }
 
 unsigned sweep2d_list_blocks(const Shape& s) { return plan2d<float>(s).grid.x; }
@@ -100,11 +132,11 @@ bool sweep2d_supported(const Shape& s, int bins) {
 
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st, const unsigned* run_if) {
+                    hipStream_t st, const unsigned* run_if, const DirArgs* dir) {
   switch (dtype) {
-    case 0: launch2d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
-    case 1: launch2d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
-    default: launch2d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
+    case 0: launch2d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr); break;
+    case 1: launch2d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr); break;
+    default: launch2d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir); break;
   }
 }
 

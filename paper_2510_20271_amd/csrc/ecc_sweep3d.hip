@@ -35,6 +35,8 @@
 #include "ecc_device.h"
 #include "ecc_internal.h"
 
+#include <type_traits>
+
 namespace ecc {
 
 namespace s3 {
@@ -186,10 +188,12 @@ __device__ __forceinline__ void arc_starts(const unsigned (&m)[8], unsigned g, u
 // One tube: columns xs .. xs+63 (outputs xs+1 .. xs+62), output rows
 // yb .. yb+R-1, output planes z0 .. z1-1.  SAFE: some lane or row of the tube
 // lies outside the grid (those read as +inf).
-template <typename T, int R, typename Sink, bool SAFE, bool SKIP_TOP, bool SKIP_BOTTOM>
+// TiltT: the field swept is X + t(p) (directional curves), NoTilt: X itself.
+template <typename T, int R, typename Sink, bool SAFE, bool SKIP_TOP, bool SKIP_BOTTOM, typename TiltT>
 __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item_elems, int D, int H,
                                            int W, int xs, int yb, int z0, int z1,
-                                           WaveQueue<Sink>& queue, unsigned* xch, WaveRange& range) {
+                                           WaveQueue<Sink>& queue, unsigned* xch, WaveRange& range,
+                                           const TiltT& tilt) {
   constexpr bool skip_top = SKIP_TOP, skip_bottom = SKIP_BOTTOM;
   const int lane = threadIdx.x & (kWave - 1);
   const int x = xs + lane;
@@ -219,11 +223,22 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
     for (int j = 0; j <= R + 1; ++j) raw[j] = Load<T>::get(rsrc, voff, roff[j]);
     pnext += plane;
   };
+  // tilt of the vertex (x, row j of the tube, plane z): t = fl(fl(fl(a_x x) + fl(a_y y)) + fl(a_z z));
+  // txy[j] is the in-plane part (zero made +0, so that equal values differ by +0)
+  float txy[R + 2];
+#pragma unroll
+  for (int j = 0; j <= R + 1; ++j)
+    txy[j] = TiltT::kOn ? add_rn(add_rn(mul_rn(tilt.ax, (float)x), mul_rn(tilt.ay, (float)(yb - 1 + j))), 0.0f)
+                        : 0.0f;
+  int zfix = max(z0 - 1, 0);  // plane the next call of fix converts
   auto fix = [&](float (&dst)[R + 2], const T (&raw)[R + 2]) {
+    const float tz = TiltT::kOn ? mul_rn(tilt.az, (float)zfix) : 0.0f;
+    ++zfix;
 #pragma unroll
     for (int j = 0; j <= R + 1; ++j) {
       float f = (float)raw[j];
-      if (sizeof(T) == 4) f += 0.0f;  // -0 -> +0 so that equal values differ by +0
+      if (TiltT::kOn) f = add_rn(f, add_rn(txy[j], tz));
+      else if (sizeof(T) == 4) f += 0.0f;  // -0 -> +0 so that equal values differ by +0
       if (SAFE) f = (inb && rok[j]) ? f : INFINITY;
       dst[j] = f;
     }
@@ -392,6 +407,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
                       4 * (int)((sl.q2 >> b) & 1u);
         float val = 0.f;  // the critical vertex's value: re-read, most likely an L2 hit
         if (active) val = (float)chunk0[(unsigned)(n - 1 - b) * (unsigned)plane + (unsigned)((yb - 1 + j) * W + x)];
+        if (TiltT::kOn) val = add_rn(val, add_rn(txy[j], mul_rn(tilt.az, (float)(z + (n - 1 - b)))));
         queue.push(active, val, P - Q, 0, 0);
       }
     }
@@ -405,10 +421,11 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 // blockIdx.y is the item; the four waves of a block take consecutive row groups
 // of one strip, so their halo rows meet in the CU's vector cache and their halo
 // words are swapped through LDS.
-template <typename T, int R, typename Sink>
+template <typename T, int R, typename Sink, typename TiltT>
 __device__ __forceinline__ void sweep3d_wave(const T* __restrict__ g, int D, int H, int W, int64_t N,
                                              int nstrip, int ngroup, int nseg, int planes_per_seg,
-                                             WaveQueue<Sink>& queue, unsigned* xch, WaveRange& range) {
+                                             WaveQueue<Sink>& queue, unsigned* xch, WaveRange& range,
+                                             const TiltT& tilt) {
   // unit = ((seg * nstrip) + strip) * ngroup4 + group, group fastest
   const int ngroup4 = (ngroup + 3) & ~3;
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform
@@ -427,15 +444,15 @@ __device__ __forceinline__ void sweep3d_wave(const T* __restrict__ g, int D, int
     const bool safe = (xs < 0) || (xs + kWave > W) || (yb == 0) || (yb + R + 1 > H);
     // tubes touching the grid boundary compute their own halo words (one variant fewer)
     if (safe)
-      s3::sweep_tube<T, R, Sink, true, false, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
+      s3::sweep_tube<T, R, Sink, true, false, false, TiltT>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range, tilt);
     else if (skip_top && skip_bottom)
-      s3::sweep_tube<T, R, Sink, false, true, true>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
+      s3::sweep_tube<T, R, Sink, false, true, true, TiltT>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range, tilt);
     else if (skip_top)
-      s3::sweep_tube<T, R, Sink, false, true, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
+      s3::sweep_tube<T, R, Sink, false, true, false, TiltT>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range, tilt);
     else if (skip_bottom)
-      s3::sweep_tube<T, R, Sink, false, false, true>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
+      s3::sweep_tube<T, R, Sink, false, false, true, TiltT>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range, tilt);
     else
-      s3::sweep_tube<T, R, Sink, false, false, false>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range);
+      s3::sweep_tube<T, R, Sink, false, false, false, TiltT>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range, tilt);
   } else {
     // a wave without a row group still meets the block's one barrier per chunk
     for (int z = z0; z < z1; z += s3::kChunk) __syncthreads();
@@ -445,12 +462,12 @@ __device__ __forceinline__ void sweep3d_wave(const T* __restrict__ g, int D, int
 constexpr int kXchInts = 2 * 4 * s3::kXchWords * kWave;  // exchange words of a block, in ints
 
 // Histogram mode; run_if (may be null): do nothing unless *run_if != 0.
-template <typename T, int R, bool LEVELS, bool TLDS>
+template <typename T, int R, bool LEVELS, bool TLDS, bool TILT>
 __global__ __launch_bounds__(256) void sweep3d_kernel(
     const T* __restrict__ grid, int D, int H, int W, int64_t N, int bins, int nstrip, int ngroup,
     int nseg, int planes_per_seg, const HardHeader* __restrict__ hdr,
     const float* __restrict__ table, unsigned long long* __restrict__ hist,
-    const unsigned* __restrict__ run_if) {
+    const unsigned* __restrict__ run_if, DirArgs dir) {
   if (run_if && *run_if == 0) return;
   extern __shared__ int smem[];
   // [2][4 waves][9][64] exchange words, [4 waves] queues, histogram, table
@@ -472,8 +489,14 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
   queue.sink.lo = LEVELS ? 0.f : hdr->lo;
   queue.sink.scale = LEVELS ? 0.f : hdr->scale;
   WaveRange range;
-  sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
-                     queue, xch, range);
+  if constexpr (TILT) {
+    const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
+    sweep3d_wave<T, R>(grid + (int64_t)item * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg, queue, xch,
+                       range, load_tilt(dir, d));
+  } else {
+    sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
+                       queue, xch, range, NoTilt());
+  }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
   for (int b = threadIdx.x; b < bins; b += 256) {
@@ -483,10 +506,10 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
 }
 
 // Single-pass mode: critical vertices to the item's list, min / max to the header.
-template <typename T, int R>
+template <typename T, int R, bool TILT>
 __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__ grid, int D, int H, int W,
                                                            int64_t N, int nstrip, int ngroup, int nseg,
-                                                           int planes_per_seg, ListArgs la) {
+                                                           int planes_per_seg, ListArgs la, DirArgs dir) {
   extern __shared__ int smem[];
   unsigned* xch = reinterpret_cast<unsigned*>(smem);
   float2* qbuf = reinterpret_cast<float2*>(smem + kXchInts) + (threadIdx.x >> 6) * kQueueCap;
@@ -499,8 +522,14 @@ __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__
   queue.sink.cap = la.cap;
   queue.sink.overflow = &la.hdr->overflow;
   WaveRange range;
-  sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
-                     queue, xch, range);
+  if constexpr (TILT) {
+    const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
+    sweep3d_wave<T, R>(grid + (int64_t)item * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg, queue, xch,
+                       range, load_tilt(dir, d));
+  } else {
+    sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
+                       queue, xch, range, NoTilt());
+  }
   range.commit(la.hdr);
 }
 
@@ -539,27 +568,41 @@ constexpr size_t kFixedLds3d = (size_t)4 * kQueueCap * sizeof(float2) + (size_t)
 template <typename T>
 static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
                        const float* table, unsigned long long* hist, hipStream_t st,
-                       const unsigned* run_if) {
+                       const unsigned* run_if, const DirArgs* dir) {
   constexpr int R = kRows3d;
   const Plan3d pl = plan3d<T>(s);
   const bool tlds = !levels && (size_t)bins * 8 + kFixedLds3d <= 60 * 1024;
   const size_t lds = kFixedLds3d + (size_t)bins * (tlds ? 8 : 4);
   const T* p = static_cast<const T*>(grid);
-#define ECC_GO(LV, TL)                                                                                  \
-  hipLaunchKernelGGL((sweep3d_kernel<T, R, LV, TL>), pl.grid, dim3(256), lds, st, p, (int)s.D, (int)s.H, \
-                     (int)s.W, s.N, bins, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg, hdr, table,  \
-                     hist, run_if)
-  if (levels) ECC_GO(true, false);
-  else if (tlds) ECC_GO(false, true);
-  else ECC_GO(false, false);
+  const DirArgs none = {nullptr, 0.f, 1, 3};
+#define ECC_GO(LV, TL, TI)                                                                                  \
+  hipLaunchKernelGGL((sweep3d_kernel<T, R, LV, TL, TI>), pl.grid, dim3(256), lds, st, p, (int)s.D, (int)s.H, \
+                     (int)s.W, s.N, bins, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg, hdr, table,      \
+                     hist, run_if, dir ? *dir : none)
+  if constexpr (std::is_same<T, float>::value) {
+    if (dir) {  // directional call: float grids, thresholds from a range
+      if (tlds) ECC_GO(false, true, true);
+      else ECC_GO(false, false, true);
+      return;
+    }
+  }
+  if (levels) ECC_GO(true, false, false);
+  else if (tlds) ECC_GO(false, true, false);
+  else ECC_GO(false, false, false);
 #undef ECC_GO
 }
 
-void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st) {
+void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
+                         const DirArgs* dir) {
   const Plan3d pl = plan3d<float>(s);
-  hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d>), pl.grid, dim3(256), kFixedLds3d, st, grid,
-                     (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg,
-                     la);
+  if (dir)
+    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, true>), pl.grid, dim3(256), kFixedLds3d, st, grid,
+                       (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg,
+                       la, *dir);
+  else
+    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, false>), pl.grid, dim3(256), kFixedLds3d, st, grid,
+                       (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg,
+                       la, DirArgs{nullptr, 0.f, 1, 3});
 }
 
 unsigned sweep3d_list_blocks(const Shape& s) { return plan3d<float>(s).grid.x; }
@@ -573,11 +616,11 @@ bool sweep3d_supported(const Shape& s, int bins) {
 
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st, const unsigned* run_if) {
+                    hipStream_t st, const unsigned* run_if, const DirArgs* dir) {
   switch (dtype) {
-    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
-    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
-    default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if); break;
+    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr); break;
+    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr); break;
+    default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir); break;
   }
 }
 

@@ -113,6 +113,44 @@ def test_soft_rejects_bad_arguments(kw, status, word):
     assert rc == status, lib.ecc_last_error()
 
 
+@pytest.mark.parametrize("kw,status,word", [
+    (dict(ndim=1), INVALID, "ndim"),
+    (dict(grid=None), INVALID, "grid"),
+    (dict(u=None), INVALID, "u is"),
+    (dict(curve=None), INVALID, "curve"),
+    (dict(ndir=0), INVALID, "ndir"),
+    (dict(ndir=300, batch=300), UNSUPPORTED, "ndir * batch"),
+    (dict(alpha=float("inf")), INVALID, "alpha"),
+    (dict(bins=0), INVALID, "bins"),
+    (dict(bins=1 << 20), UNSUPPORTED, "bins"),
+    (dict(range=(3.0, 1.0)), INVALID, "range"),
+    (dict(ws_bytes=8), WORKSPACE, "workspace"),
+    (dict(u=ctypes.c_void_p(0x1002)), INVALID, "aligned"),
+])
+def test_hard_dir_rejects_bad_arguments(kw, status, word):
+    lib = _lib.load()
+    a = dict(grid=FAKE, ndim=2, dims=(4, 4), batch=1, u=FAKE, ndir=2, alpha=0.5, bins=8, range=None, curve=FAKE,
+             ws=FAKE, ws_bytes=1 << 20)
+    a.update(kw)
+    rng = None if a["range"] is None else (ctypes.c_double * 2)(*a["range"])
+    rc = lib.ecc_hard_dir(a["grid"], a["ndim"], _dims(*a["dims"]), a["batch"], a["u"], a["ndir"], a["alpha"],
+                          a["bins"], rng, a["curve"], a["ws"], a["ws_bytes"], None)
+    assert rc == status, lib.ecc_last_error()
+    assert word in lib.ecc_last_error().decode()
+
+
+def test_hard_dir_workspace_bytes_host_only():
+    lib = _lib.load()
+    one = lib.ecc_workspace_bytes_dir(2, _dims(300, 1000), 2, 1, 64)
+    four = lib.ecc_workspace_bytes_dir(2, _dims(300, 1000), 2, 4, 64)
+    assert 0 < one < four
+    assert lib.ecc_workspace_bytes_dir(2, _dims(300, 1000), 2, 0, 64) == 0
+    assert lib.ecc_workspace_bytes_dir(2, _dims(300, 1000), 300, 300, 64) == 0
+    # shapes the strip sweep does not take also need room for the tilted fields
+    tiny = lib.ecc_workspace_bytes_dir(2, _dims(50, 5), 1, 3, 64)
+    assert tiny >= 3 * 50 * 5 * 4
+
+
 def test_coeff_rejects_bad_arguments():
     lib = _lib.load()
     assert lib.ecc_coeff(None, 2, _dims(4, 4), 1, 0, FAKE, None) == INVALID
