@@ -185,6 +185,11 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
       const_cast<T*>(g + first), 0, (int)(left > 0x7fffffff ? 0x7fffffff : left), 0x00020000);
   const unsigned row_bytes = (unsigned)W * (unsigned)sizeof(T);
   unsigned soff = 0;  // byte offset of the next row to load
+  // The last row this segment needs is y1 (the row below its last output row), or
+  // the grid's last row; the rows the pipeline would fetch beyond it are not read
+  // from memory again: the offset stays on that row (a cache hit).
+  const unsigned soff_last = (unsigned)(min(y1, H - 1) - ya) * row_bytes;
+  auto next_row = [&]() { soff = min(soff + row_bytes, soff_last); };
 
   typedef RowRegs<T, EDGE> Row;
   // value of column e of a loaded row, which is row y of the grid
@@ -203,13 +208,13 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
   {
     Row a, b;
     a.load(rsrc, voff, voff4, soff);
-    soff += row_bytes;
+    next_row();
     b.load(rsrc, voff, voff4, soff);
-    soff += row_bytes;
+    next_row();
 #pragma unroll
     for (int k = 0; k < kPF; ++k) {
       pf[k].load(rsrc, voff, voff4, soff);
-      soff += row_bytes;
+      next_row();
     }
 #pragma unroll
     for (int e = 0; e < kNC; ++e) {
@@ -270,7 +275,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 #pragma unroll
     for (int q = 0; q + 1 < kPF; ++q) pf[q] = pf[q + 1];
     pf[kPF - 1].load(rsrc, voff, voff4, soff);
-    soff += row_bytes;
+    next_row();
   };
 
   unsigned oN[kNC], oNE[kNC], oNW[kNC];  // bit 0: the row above the first output row

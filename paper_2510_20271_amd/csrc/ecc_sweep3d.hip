@@ -215,13 +215,16 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
     roff[j] = (unsigned)min(max(y, 0), H - 1) * (unsigned)W * (unsigned)sizeof(T);
   }
   const T* pnext = g + (int64_t)max(z0 - 1, 0) * plane + (SAFE ? 0 : xs);  // next plane to load
+  // the last plane this segment needs: z1 (above its last output plane) or the grid's last one;
+  // what the pipeline would fetch beyond it is that plane again (a cache hit, no memory traffic)
+  const T* const plast = g + (int64_t)min(z1, D - 1) * plane + (SAFE ? 0 : xs);
   auto load_plane = [&](T (&raw)[R + 2]) {
     const int64_t left = (item_end - pnext) * (int64_t)sizeof(T);
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<T*>(pnext), 0, (int)(left > 0x7fffffff ? 0x7fffffff : (left > 0 ? left : 0)), 0x00020000);
 #pragma unroll
     for (int j = 0; j <= R + 1; ++j) raw[j] = Load<T>::get(rsrc, voff, roff[j]);
-    pnext += plane;
+    if (pnext < plast) pnext += plane;
   };
   // tilt of the vertex (x, row j of the tube, plane z): t = fl(fl(fl(a_x x) + fl(a_y y)) + fl(a_z z));
   // txy[j] is the in-plane part (zero made +0, so that equal values differ by +0)
