@@ -95,4 +95,4 @@ def test_layer_learns_its_thresholds_back():
         opt.step()
         first = first if first is not None else float(loss.detach())
     assert float(loss.detach()) < 0.1 * first
-    assert float((model.tau - target.tau).abs().mean()) < 0.015
+    assert float((model.tau - target.tau).abs().mean().detach()) < 0.015
