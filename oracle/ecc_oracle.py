@@ -187,6 +187,82 @@ def ecc_hard_batch(Xb: np.ndarray, t: np.ndarray) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
+# top-cell construction: grid points are the top-dimensional cells (pixels /
+# voxels as squares / cubes); a lower cell is present as soon as one of the top
+# cells around it is.  (The Background section leaves the construction open; the
+# vertex construction above is the one the rest of this file uses.)
+# ----------------------------------------------------------------------------
+
+
+def _any_shifted(m: np.ndarray, axes) -> np.ndarray:
+    """Cells spanned between neighbouring top cells along `axes`: present when ANY
+    of the 2^k top cells around them is (m padded with False outside the grid)."""
+    out = np.pad(m, [(1, 1) if a in axes else (0, 0) for a in range(m.ndim)], constant_values=False)
+    for a in axes:
+        lo = [slice(None)] * m.ndim
+        hi = [slice(None)] * m.ndim
+        lo[a], hi[a] = slice(0, -1), slice(1, None)
+        out = out[tuple(lo)] | out[tuple(hi)]
+    return out
+
+
+def euler_characteristic_topcells(m: np.ndarray) -> int:
+    """chi of the closed union of the unit squares / cubes marked in m: cells of
+    codimension k are indexed by the top cells shifted half a step along k axes."""
+    import itertools
+    d = m.ndim
+    chi = 0
+    for k in range(d + 1):
+        for axes in itertools.combinations(range(d), k):
+            chi += (-1) ** (d - k) * int(_any_shifted(m, axes).sum())
+    return chi
+
+
+def ecc_top_bruteforce(X: np.ndarray, t: np.ndarray) -> np.ndarray:
+    return np.array([euler_characteristic_topcells(X <= tb) for tb in t], dtype=np.int64)
+
+
+def coeff_top(X: np.ndarray) -> np.ndarray:
+    """Per-top-cell coefficient: every cell is charged to the FIRST top cell around
+    it (X, then C-order index).  That is the vertex coefficient of the reversed
+    order with everything outside the grid coming before, times (-1)^d."""
+    X = np.asarray(X)
+    d = X.ndim
+    idx = np.arange(X.size, dtype=np.int64).reshape(X.shape)
+    big = X.astype(np.float64)
+    c = np.zeros(X.shape, dtype=np.int64)
+    import itertools
+    pad_v = np.pad(big, 1, constant_values=np.inf)        # outside: never first
+    pad_i = np.pad(idx, 1, constant_values=-1)
+    centre = tuple(slice(1, -1) for _ in range(d))
+
+    def first_among(offsets):
+        """p is the first of the top cells p + s, s over all sub-offsets of `offsets`."""
+        ok = np.ones(X.shape, bool)
+        for s in itertools.product(*[(0, o) if o else (0,) for o in offsets]):
+            if not any(s):
+                continue
+            sl = tuple(slice(1 + si, 1 + si + n) for si, n in zip(s, X.shape))
+            qv, qi = pad_v[sl], pad_i[sl]
+            p_first = (big < qv) | ((big == qv) & (idx < qi))
+            ok &= p_first
+        return ok
+
+    for o in itertools.product((-1, 0, 1), repeat=d):
+        k = sum(1 for v in o if v)                      # codimension of the cell between p and p + o
+        c += (-1) ** (d - k) * first_among(o)
+    return c
+
+
+def ecc_top(X: np.ndarray, t: np.ndarray) -> np.ndarray:
+    return ecc_from_coeff(X, coeff_top(X), t)
+
+
+def ecc_top_batch(Xb: np.ndarray, t: np.ndarray) -> np.ndarray:
+    return np.stack([ecc_top(x, t) for x in Xb])
+
+
+# ----------------------------------------------------------------------------
 # directional hard ECC: the curve of the tilted field (Background: the Euler
 # characteristic transform sweeps a shape along directions; Eq. 6 tilts the
 # filtration by alpha <u, p>)

@@ -328,3 +328,46 @@ def test_directional_curves_match_the_brute_force_count_on_the_tilted_field():
                 Y = O.tilt_field(x, u, 0.5)
                 assert np.array_equal(got[k, i], O.ecc_bruteforce(Y, t))
                 assert np.array_equal(got[k, i], O.ecc_cellmax(Y, t))
+
+
+# ---- top-cell construction ------------------------------------------------------
+
+
+def test_topcell_closed_forms():
+    one = np.ones((1, 1), bool)
+    assert O.euler_characteristic_topcells(one) == 1                    # a closed square
+    assert O.euler_characteristic_topcells(np.ones((3, 4, 5), bool)) == 1
+    ring = np.ones((3, 3), bool)
+    ring[1, 1] = False
+    assert O.euler_characteristic_topcells(ring) == 0                   # annulus
+    diag = np.eye(2, dtype=bool)
+    assert O.euler_characteristic_topcells(diag) == 1                   # corner contact joins (8-connectivity)
+    assert O.euler_characteristic_mask(diag) == 2                       # ... where the vertex construction has two
+    shell = np.ones((3, 3, 3), bool)
+    shell[1, 1, 1] = False
+    assert O.euler_characteristic_topcells(shell) == 2
+    assert O.euler_characteristic_topcells(np.zeros((4, 4), bool)) == 0
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (1, 5), (4, 1), (3, 3), (5, 6), (2, 2, 2), (1, 3, 4), (3, 4, 5)])
+def test_topcell_coefficients_reproduce_the_brute_force_curve(shape):
+    rng = np.random.default_rng(sum(shape))
+    for levels in (2, 3, 50):
+        for _ in range(10):
+            X = rng.integers(0, levels, size=shape).astype(np.float32)
+            t = O.thresholds_levels(levels)
+            c = O.coeff_top(X)
+            assert c.sum() == 1                                         # the full box is contractible
+            assert np.array_equal(O.ecc_top(X, t), O.ecc_top_bruteforce(X, t))
+
+
+def test_topcell_coefficient_is_the_reversed_vertex_coefficient_in_the_interior():
+    # away from the boundary: c_top(X) = (-1)^d c_vertex(-X) up to the tie-break, so on
+    # grids without ties the two agree exactly there
+    rng = np.random.default_rng(3)
+    for shape in ((7, 8), (5, 6, 7)):
+        X = rng.permutation(int(np.prod(shape))).reshape(shape).astype(np.float32)
+        a = O.coeff_top(X)
+        b = (-1) ** len(shape) * O.coeff(-X)
+        inner = tuple(slice(1, -1) for _ in shape)
+        assert np.array_equal(a[inner], b[inner])
