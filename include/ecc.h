@@ -136,6 +136,22 @@ int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Hard ECC of the top-cell construction (the Background section leaves the
+ * construction of the cubical complex open): the grid points are the
+ * top-dimensional cells -- pixels are closed unit squares, voxels closed unit
+ * cubes -- and a lower cell (edge, vertex, face) is present as soon as one of
+ * the top cells around it is, so squares that touch in a corner are connected
+ * (8- / 26-connectivity of the sublevel set, where ecc_hard has 4- / 6-).  Every
+ * cell is charged to the first top cell around it; that coefficient is (-1)^d
+ * times the vertex coefficient of Eq. 3 for the reversed order with everything
+ * outside the grid coming first, which is how it is computed.  Arguments,
+ * thresholds, bins, output, workspace and errors: exactly as ecc_hard.
+ */
+int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
+                 const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
+                 void* hip_stream);
+
+/*
  * Directional hard curves (Background: the Euler characteristic transform looks at
  * a shape along directions; Eq. 6 tilts the filtration by alpha <u, p>).  For
  * every direction u_k the field

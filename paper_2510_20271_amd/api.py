@@ -60,9 +60,9 @@ def _workspace(item_shape, batch, n, device, workspace):
     return workspace
 
 
-def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, workspace=None):
+def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, workspace=None, top=False):
     """grid: [batch, (D,) H, W] device tensor (uint8 / uint16 / float32).
-    Returns the int64 curve [batch, bins]."""
+    Returns the int64 curve [batch, bins].  top=True: top-cell construction (ecc_hard_top)."""
     _need_device(grid, curve, workspace)
     if grid.dim() != ndim + 1:
         raise ValueError("grid must be [batch, *item_shape]")
@@ -73,9 +73,15 @@ def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, w
     rng = None
     if range is not None:
         rng = (ctypes.c_double * 2)(float(range[0]), float(range[1]))
-    _check(_lib.load().ecc_hard(_ptr(grid), ndim, _dims(item), batch, _DTYPES[grid.dtype], bins, rng,
-                                _ptr(curve), _ptr(workspace), workspace.numel(), _stream()))
+    fn = _lib.load().ecc_hard_top if top else _lib.load().ecc_hard
+    _check(fn(_ptr(grid), ndim, _dims(item), batch, _DTYPES[grid.dtype], bins, rng, _ptr(curve),
+              _ptr(workspace), workspace.numel(), _stream()))
     return curve
+
+
+def ecc_hard_top(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, workspace=None):
+    """Hard ECC of the top-cell construction (grid points are squares / cubes)."""
+    return ecc_hard(grid, ndim, bins, range=range, curve=curve, workspace=workspace, top=True)
 
 
 def ecc_workspace_bytes_dir(item_shape, batch: int, ndir: int, bins: int) -> int:

@@ -101,7 +101,7 @@ size_t ecc_workspace_bytes(int ndim, const int64_t* dims, int64_t batch, int bin
   return a > b ? a : b;
 }
 
-int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
+static int hard_common(bool top, const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
              const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
              void* hip_stream) {
   ecc::Shape s;
@@ -127,9 +127,23 @@ int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, int
     return fail(ECC_ERR_INVALID_ARG, "curve is not 8-byte aligned");
   if ((rc = check_workspace(workspace, workspace_bytes, ecc::hard_workspace_bytes(s, bins))) != ECC_OK)
     return rc;
-  return device_status(ecc::launch_hard(grid, s, dtype, bins, range != nullptr, lo, hi, curve,
-                                        workspace, static_cast<hipStream_t>(hip_stream)),
-                       "ecc_hard");
+  return device_status(ecc::launch_hard(grid, s, dtype, bins, range != nullptr, lo, hi, curve, workspace,
+                                        static_cast<hipStream_t>(hip_stream), nullptr, top),
+                       top ? "ecc_hard_top" : "ecc_hard");
+}
+
+int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
+             const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
+             void* hip_stream) {
+  return hard_common(false, grid, ndim, dims, batch, dtype, bins, range, curve, workspace, workspace_bytes,
+                     hip_stream);
+}
+
+int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
+                 const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
+                 void* hip_stream) {
+  return hard_common(true, grid, ndim, dims, batch, dtype, bins, range, curve, workspace, workspace_bytes,
+                     hip_stream);
 }
 
 size_t ecc_workspace_bytes_dir(int ndim, const int64_t* dims, int64_t batch, int ndir, int bins) {

@@ -47,7 +47,9 @@ __device__ __forceinline__ int coeff_3d(unsigned a, unsigned up, bool up0, unsig
 
 // Coefficient of the vertex (z,y,x) read straight from global memory, with
 // bounds checks; the reference path for every dtype and shape.
-template <typename T, int ND>
+// TOP: the order is reversed and vertices outside the grid come before every
+// vertex (top-cell construction, see TopCells below); the caller applies (-1)^d.
+template <typename T, int ND, bool TOP = false>
 __device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int64_t H, int64_t W,
                                         int64_t z, int64_t y, int64_t x) {
   const int64_t ip = (z * H + y) * W + x;
@@ -63,11 +65,12 @@ __device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int6
       for (int dx = -1; dx <= 1; ++dx) {
         if (dz == 0 && dy == 0 && dx == 0) continue;
         const int64_t qz = z + dz, qy = y + dy, qx = x + dx;
-        bool b = false;
+        bool b = TOP;
         if (qz >= 0 && qz < D && qy >= 0 && qy < H && qx >= 0 && qx < W) {
           const T vq = g[(qz * H + qy) * W + qx];
           const bool later = (dz > 0) || (dz == 0 && (dy > 0 || (dy == 0 && dx > 0)));
-          b = later ? (vq < vp) : (vq <= vp);
+          if (TOP) b = later ? (vq > vp) : (vq >= vp);
+          else b = later ? (vq < vp) : (vq <= vp);
         }
         if (dy == 0 && dx == 0) centre[dz + 1] = b;
         else ring[dz + 1] |= (b ? 1u : 0u) << ring_bit(dy, dx);
@@ -143,14 +146,26 @@ __device__ __forceinline__ float add_rn(float a, float b) {
   return a + b;
 }
 
+//
+// TopCells is the third way a sweep can take the field: negated, with everything
+// outside the grid coming first (-inf).  The vertex coefficient of that order is,
+// up to the sign (-1)^d, the coefficient of the top-cell construction (grid
+// points are squares / cubes; a lower cell belongs to the FIRST top cell around
+// it), so the same stencil serves both constructions; the value that is binned is
+// the original one.
 struct NoTilt {
-  static constexpr bool kOn = false;
+  static constexpr bool kOn = false, kNeg = false;
   float ax, ay, az;
 };
 struct Tilt {
-  static constexpr bool kOn = true;
+  static constexpr bool kOn = true, kNeg = false;
   float ax, ay, az;
 };
+struct TopCells {
+  static constexpr bool kOn = false, kNeg = true;
+  float ax, ay, az;
+};
+enum SweepMode { kPlain = 0, kTilted = 1, kTopCells = 2 };
 struct DirArgs {
   const float* u;  // device [ndir][ndim]
   float alpha;

@@ -108,7 +108,8 @@ __global__ void prepare_kernel(HardHeader* h, float* __restrict__ table, int bin
 // ---------------------------------------------------------------------------
 // generic sweep: one thread per vertex, neighbours read through the caches
 // ---------------------------------------------------------------------------
-template <typename T, int ND, bool LEVELS>
+// TOP: top-cell construction (reversed order, outside first, (-1)^d times the vertex formula)
+template <typename T, int ND, bool LEVELS, bool TOP>
 __global__ __launch_bounds__(kBlock) void sweep_generic_kernel(
     const T* __restrict__ grid, int64_t D, int64_t H, int64_t W, int64_t N, int bins,
     const HardHeader* __restrict__ hdr, const float* __restrict__ table,
@@ -125,7 +126,8 @@ __global__ __launch_bounds__(kBlock) void sweep_generic_kernel(
     const int64_t r = i / W;
     const int64_t y = r % H;
     const int64_t z = r / H;
-    const int c = coeff_at<T, ND>(g, D, H, W, z, y, x);
+    int c = coeff_at<T, ND, TOP>(g, D, H, W, z, y, x);
+    if (TOP && ND == 3) c = -c;
     if (c != 0) {
       const T v = g[i];
       int b;
@@ -324,20 +326,24 @@ static int blocks_for(int64_t N) {
 template <typename T>
 static void launch_sweep_generic(const void* grid, const Shape& s, bool levels, int bins,
                                  const HardHeader* hdr, const float* table,
-                                 unsigned long long* hist, hipStream_t st) {
+                                 unsigned long long* hist, hipStream_t st, bool top) {
   dim3 g(blocks_for(s.N), (unsigned)s.batch);
   size_t lds = (size_t)bins * sizeof(int);
   const T* p = static_cast<const T*>(grid);
-#define ECC_GO(ND, LV)                                                                        \
-  hipLaunchKernelGGL((sweep_generic_kernel<T, ND, LV>), g, dim3(kBlock), lds, st, p, s.D, s.H, \
+#define ECC_GO(ND, LV, TP)                                                                        \
+  hipLaunchKernelGGL((sweep_generic_kernel<T, ND, LV, TP>), g, dim3(kBlock), lds, st, p, s.D, s.H, \
                      s.W, s.N, bins, hdr, table, hist)
-  if (s.ndim == 2) { if (levels) ECC_GO(2, true); else ECC_GO(2, false); }
-  else             { if (levels) ECC_GO(3, true); else ECC_GO(3, false); }
+#define ECC_TOP(ND, LV) \
+  if (top) ECC_GO(ND, LV, true); else ECC_GO(ND, LV, false)
+  if (s.ndim == 2) { if (levels) { ECC_TOP(2, true); } else { ECC_TOP(2, false); } }
+  else             { if (levels) { ECC_TOP(3, true); } else { ECC_TOP(3, false); } }
+#undef ECC_TOP
 #undef ECC_GO
 }
 
 hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
-                       double lo, double hi, int64_t* curve, void* ws, hipStream_t st, const DirArgs* dir) {
+                       double lo, double hi, int64_t* curve, void* ws, hipStream_t st, const DirArgs* dir,
+                       bool top) {
   HardHeader* hdr = static_cast<HardHeader*>(ws);
   char* wsb = static_cast<char*>(ws);
   float* table = reinterpret_cast<float*>(wsb + kTableOffset);
@@ -385,8 +391,8 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)ib), dim3(256), 0, st, hdr, la.counters,
                        (int)(s.batch * la.nsub), hist, hist_len);
     profile_mark(st, false);
-    if (fast2d) launch_sweep2d_list(gf, s, la, st, dir);
-    else launch_sweep3d_list(gf, s, la, st, dir);
+    if (fast2d) launch_sweep2d_list(gf, s, la, st, dir, top);
+    else launch_sweep3d_list(gf, s, la, st, dir, top);
     profile_mark(st, true);
     // few blocks per item merge into the global histogram (same-address atomics), but
     // enough of them in all to keep the list reads in flight
@@ -395,8 +401,8 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     if (nblk > (int64_t)la.nsub) nblk = la.nsub;
     hipLaunchKernelGGL(binlist_kernel, dim3((unsigned)nblk, (unsigned)s.batch), dim3(kBlock),
                        (size_t)bins * 2 * sizeof(int), st, la, table, bins, hist);
-    if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir);
-    else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir);
+    if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir, top);
+    else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir, top);
     hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,
                        reinterpret_cast<long long*>(curve), bins);
     return hipGetLastError();
@@ -414,14 +420,14 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
                      device_range ? 1 : 0, lo, hi, hist, hist_len);
   profile_mark(st, false);
   if (fast2d) {
-    launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir);
+    launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir, top);
   } else if (fast3d) {
-    launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir);
+    launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir, top);
   } else
   switch (dtype) {
-    case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st); break;
-    case 1: launch_sweep_generic<uint16_t>(grid, s, levels, bins, hdr, table, hist, st); break;
-    default: launch_sweep_generic<float>(grid, s, levels, bins, hdr, table, hist, st); break;
+    case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, top); break;
+    case 1: launch_sweep_generic<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, top); break;
+    default: launch_sweep_generic<float>(grid, s, levels, bins, hdr, table, hist, st, top); break;
   }
   profile_mark(st, true);
   hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,

@@ -128,11 +128,7 @@ template <typename T> struct RowRegs<T, false> {
                                        unsigned soff) {
     raw.load(r, voff4, soff);
   }
-  __device__ __forceinline__ float value(int e, const bool (&)[kNC]) const {
-    float f = raw.get(e);
-    if (sizeof(T) == 4) f += 0.0f;  // -0 -> +0 so that equal values differ by +0
-    return f;
-  }
+  __device__ __forceinline__ float raw_value(int e) const { return raw.get(e); }
 };
 template <typename T> struct RowRegs<T, true> {
   float f[kNC];
@@ -141,11 +137,7 @@ template <typename T> struct RowRegs<T, true> {
 #pragma unroll
     for (int e = 0; e < kNC; ++e) f[e] = Raw1<T>::get(r, voff[e], soff);
   }
-  __device__ __forceinline__ float value(int e, const bool (&ok)[kNC]) const {
-    float v = f[e];
-    if (sizeof(T) == 4) v += 0.0f;
-    return ok[e] ? v : INFINITY;
-  }
+  __device__ __forceinline__ float raw_value(int e) const { return f[e]; }
 };
 
 // One strip: lanes hold columns c0 + 4*lane + e; output rows y0 .. y1-1
@@ -197,11 +189,22 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 #pragma unroll
   for (int e = 0; e < kNC; ++e)
     lx[e] = Tilt::kOn ? add_rn(mul_rn(tilt.ax, (float)(c0 + kNC * lane + e)), 0.0f) : 0.0f;
+  // (zeros come out as +0 in every mode, so that equal values differ by +0; a column
+  // outside the grid reads as "never before p": +inf, or -inf where the order is reversed)
   auto value_at = [&](const Row& r, int e, int y) -> float {
-    const float f = r.value(e, ok);
-    if (!Tilt::kOn) return f;
-    return add_rn(f, add_rn(lx[e], mul_rn(tilt.ay, (float)y)));
+    float f = r.raw_value(e);
+    if (Tilt::kNeg) {
+      // 0 - f, zeros coming out as +0.  Kept opaque: left to itself the compiler replaces later
+      // uses of it by a negated source operand, which turns +0 into -0 in a difference.
+      f = 0.0f - f;
+      asm volatile("" : "+v"(f));
+    }
+    else if (Tilt::kOn) f = add_rn(f, add_rn(lx[e], mul_rn(tilt.ay, (float)y)));
+    else if (sizeof(T) == 4) f += 0.0f;
+    if (EDGE) f = ok[e] ? f : (Tilt::kNeg ? -INFINITY : INFINITY);
+    return f;
   };
+  auto original = [](float f) -> float { return Tilt::kNeg ? -f : f; };  // the value that is binned
   Row pf[kPF];
   float cur[kNC], nxt[kNC];
   int yn = ya + 2;  // row of the grid that becomes nxt at the next step
@@ -234,13 +237,13 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
       Row t;
       t.load(rsrc, voff, voff4, 0);
 #pragma unroll
-      for (int e = 0; e < kNC; ++e) range.add(value_at(t, e, 0));
+      for (int e = 0; e < kNC; ++e) range.add(original(value_at(t, e, 0)));
     }
     if (y1 >= H) {
       Row t;
       t.load(rsrc, voff, voff4, (unsigned)(H - 1 - ya) * row_bytes);
 #pragma unroll
-      for (int e = 0; e < kNC; ++e) range.add(value_at(t, e, H - 1));
+      for (int e = 0; e < kNC; ++e) range.add(original(value_at(t, e, H - 1)));
     }
   }
 
@@ -255,7 +258,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     ++slot;
     if (Sink::kTrackRange && EDGE) {
 #pragma unroll
-      for (int e = 0; e < kNC; ++e) range.add_if(cur[e], ok[e]);
+      for (int e = 0; e < kNC; ++e) range.add_if(original(cur[e]), ok[e]);
     }
     float dE, dNE, dNW;
     lane_edge_differences(cur[0], cur[kNC - 1], nxt[0], nxt[kNC - 1], dE, dNE, dNW);
@@ -280,7 +283,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 
   unsigned oN[kNC], oNE[kNC], oNW[kNC];  // bit 0: the row above the first output row
 #pragma unroll
-  for (int e = 0; e < kNC; ++e) oN[e] = oNE[e] = oNW[e] = 1;
+  for (int e = 0; e < kNC; ++e) oN[e] = oNE[e] = oNW[e] = Tilt::kNeg ? 0 : 1;  // (reversed order: always before p)
   if (y0 > 0) {
     step();  // warm-up on row y0-1
 #pragma unroll
@@ -313,9 +316,15 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 #pragma unroll
     for (int e = 0; e < kNC; ++e) {
       if (bottom) {
-        wN[e] &= ~1u;
-        wNE[e] &= ~1u;
-        wNW[e] &= ~1u;
+        if (Tilt::kNeg) {  // reversed order: what lies outside the grid comes before p
+          wN[e] |= 1u;
+          wNE[e] |= 1u;
+          wNW[e] |= 1u;
+        } else {
+          wN[e] &= ~1u;
+          wNE[e] &= ~1u;
+          wNW[e] &= ~1u;
+        }
       }
       E[e] = wE[e] << pad;
       N[e] = wN[e] << pad;
@@ -364,7 +373,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
       const int c = 1 - (int)((pE >> b) & 1u) - (int)((pNn >> b) & 1u) - (int)((pW >> b) & 1u) -
                     (int)((pS >> b) & 1u);
       const int pos = 31 - b;  // column pos / 8, row pos % 8 of the chunk
-      const float v = ring[((pos & 7) * kWave + lane) * kNC + (pos >> 3)];
+      const float v = original(ring[((pos & 7) * kWave + lane) * kNC + (pos >> 3)]);
       if (Sink::kTrackRange && !EDGE) range.add_if(v, active);
       queue.push(active, v, c, c0 + kNC * lane + (pos >> 3), r + (pos & 7));
     }

@@ -8,8 +8,9 @@ namespace ecc {
 // Histogram mode: critical vertices are binned into the block's LDS histogram,
 // which is merged into the global one at the end.  run_if (may be null): the
 // kernel does nothing unless *run_if != 0 (fallback of the single-pass mode).
-// TILT: a directional launch (blockIdx.y = direction * batch + item, tilted field).
-template <typename T, bool LEVELS, bool TLDS, bool TILT>
+// MODE (SweepMode): kTilted is a directional launch (blockIdx.y = direction * batch + item,
+// tilted field), kTopCells the top-cell construction.
+template <typename T, bool LEVELS, bool TLDS, int MODE>
 __global__ __launch_bounds__(256) void sweep2d_kernel(
     const T* __restrict__ grid, int H, int W, int64_t N, int bins, int nstrip, int nseg, int rows_per_seg,
     const HardHeader* __restrict__ hdr, const float* __restrict__ table,
@@ -36,10 +37,13 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
   queue.sink.lo = LEVELS ? 0.f : hdr->lo;
   queue.sink.scale = LEVELS ? 0.f : hdr->scale;
   WaveRange range;
-  if constexpr (TILT) {
+  if constexpr (MODE == kTilted) {
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
     sweep2d_wave<T>(grid + (int64_t)item * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
                     load_tilt(dir, d));
+  } else if constexpr (MODE == kTopCells) {
+    sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                    TopCells());
   } else {
     sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
                     NoTilt());
@@ -55,7 +59,7 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
 // Single-pass mode: critical vertices (value, c) go to the item's list in the
 // workspace and the wave's min / max to the header; the bins are assigned later,
 // once the batch-global range is known.
-template <typename T, bool TILT>
+template <typename T, int MODE>
 __global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__ grid, int H, int W,
                                                            int64_t N, int nstrip, int nseg,
                                                            int rows_per_seg, ListArgs la, DirArgs dir) {
@@ -72,10 +76,13 @@ __global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__
   queue.sink.cap = la.cap;
   queue.sink.overflow = &la.hdr->overflow;
   WaveRange range;
-  if constexpr (TILT) {
+  if constexpr (MODE == kTilted) {
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
     sweep2d_wave<T>(grid + (int64_t)item * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
                     load_tilt(dir, d));
+  } else if constexpr (MODE == kTopCells) {
+    sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                    TopCells());
   } else {
     sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
                     NoTilt());
@@ -88,7 +95,7 @@ constexpr size_t kRingBytes2d = ring_bytes2d<float2>();
 template <typename T>
 static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
                        const float* table, unsigned long long* hist, hipStream_t st,
-                       const unsigned* run_if, const DirArgs* dir) {
+                       const unsigned* run_if, const DirArgs* dir, bool top) {
   const Plan2d pl = plan2d<T>(s);
   const bool tlds = !levels && (size_t)bins * 8 + kRingBytes2d <= 64 * 1024;
   const size_t lds = kRingBytes2d + (size_t)bins * (tlds ? 8 : 4);
@@ -100,27 +107,36 @@ static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, 
                      dir ? *dir : none)
   if constexpr (std::is_same<T, float>::value) {
     if (dir) {  // directional call: float grids, thresholds from a range
-      if (tlds) ECC_GO(false, true, true);
-      else ECC_GO(false, false, true);
+      if (tlds) ECC_GO(false, true, kTilted);
+      else ECC_GO(false, false, kTilted);
       return;
     }
   }
-  if (levels) ECC_GO(true, false, false);
-  else if (tlds) ECC_GO(false, true, false);
-  else ECC_GO(false, false, false);
+  if (top) {
+    if (levels) ECC_GO(true, false, kTopCells);
+    else if (tlds) ECC_GO(false, true, kTopCells);
+    else ECC_GO(false, false, kTopCells);
+    return;
+  }
+  if (levels) ECC_GO(true, false, kPlain);
+  else if (tlds) ECC_GO(false, true, kPlain);
+  else ECC_GO(false, false, kPlain);
 #undef ECC_GO
 }
 
 void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
-                         const DirArgs* dir) {
+                         const DirArgs* dir, bool top) {
   const Plan2d pl = plan2d<float>(s);
+  const DirArgs none = {nullptr, 0.f, 1, 2};
   if (dir)
-    hipLaunchKernelGGL((sweep2d_list_kernel<float, true>), pl.grid, dim3(256), kRingBytes2d, st, grid,
+    hipLaunchKernelGGL((sweep2d_list_kernel<float, kTilted>), pl.grid, dim3(256), kRingBytes2d, st, grid,
                        (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la, *dir);
+  else if (top)
+    hipLaunchKernelGGL((sweep2d_list_kernel<float, kTopCells>), pl.grid, dim3(256), kRingBytes2d, st, grid,
+                       (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la, none);
   else
-    hipLaunchKernelGGL((sweep2d_list_kernel<float, false>), pl.grid, dim3(256), kRingBytes2d, st, grid,
-                       (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la,
-                       DirArgs{nullptr, 0.f, 1, 2});
+    hipLaunchKernelGGL((sweep2d_list_kernel<float, kPlain>), pl.grid, dim3(256), kRingBytes2d, st, grid,
+                       (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la, none);
 }
 
 unsigned sweep2d_list_blocks(const Shape& s) { return plan2d<float>(s).grid.x; }
@@ -132,11 +148,11 @@ bool sweep2d_supported(const Shape& s, int bins) {
 
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st, const unsigned* run_if, const DirArgs* dir) {
+                    hipStream_t st, const unsigned* run_if, const DirArgs* dir, bool top) {
   switch (dtype) {
-    case 0: launch2d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr); break;
-    case 1: launch2d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr); break;
-    default: launch2d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir); break;
+    case 0: launch2d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, top); break;
+    case 1: launch2d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, top); break;
+    default: launch2d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir, top); break;
   }
 }
 

@@ -240,9 +240,13 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 #pragma unroll
     for (int j = 0; j <= R + 1; ++j) {
       float f = (float)raw[j];
-      if (TiltT::kOn) f = add_rn(f, add_rn(txy[j], tz));
+      if (TiltT::kNeg) {  // reversed order (top-cell construction); zeros still +0
+        f = 0.0f - f;
+        asm volatile("" : "+v"(f));  // opaque: a negated source operand downstream would make -0 of it
+      }
+      else if (TiltT::kOn) f = add_rn(f, add_rn(txy[j], tz));
       else if (sizeof(T) == 4) f += 0.0f;  // -0 -> +0 so that equal values differ by +0
-      if (SAFE) f = (inb && rok[j]) ? f : INFINITY;
+      if (SAFE) f = (inb && rok[j]) ? f : (TiltT::kNeg ? -INFINITY : INFINITY);
       dst[j] = f;
     }
   };
@@ -263,7 +267,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 #pragma unroll
   for (int jc = 0; jc <= R + 1; ++jc)
 #pragma unroll
-    for (int q = 0; q < 9; ++q) w.U[jc][q] = 1u;  // below the grid: "never before p" after complement
+    for (int q = 0; q < 9; ++q) w.U[jc][q] = TiltT::kNeg ? 0u : 1u;  // below the grid: "never before p" after complement (reversed order: always)
   if (z0 > 0) {
     // pa = plane z0-1, rawx = plane z0
     fix(pb, rawx);
@@ -288,8 +292,9 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
       if (Sink::kTrackRange) {
 #pragma unroll
         for (int j = 1; j <= R; ++j) {
-          if (SAFE) range.add_if(p[j], inb && rok[j]);
-          else range.add(p[j]);
+          const float v = TiltT::kNeg ? -p[j] : p[j];  // the range is that of the original values
+          if (SAFE) range.add_if(v, inb && rok[j]);
+          else range.add(v);
         }
       }
     };
@@ -348,7 +353,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 #pragma unroll
       for (int jc = 1; jc <= R; ++jc)
 #pragma unroll
-        for (int q = 0; q < 9; ++q) w.U[jc][q] &= ~1u;
+        for (int q = 0; q < 9; ++q) w.U[jc][q] = TiltT::kNeg ? (w.U[jc][q] | 1u) : (w.U[jc][q] & ~1u);
     }
     // plane z+i sits at bit n-1-i of every word; the plane below the chunk at bit n of U
     const unsigned planes = (n >= 32) ? 0xffffffffu : ((1u << n) - 1u);
@@ -411,7 +416,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
         float val = 0.f;  // the critical vertex's value: re-read, most likely an L2 hit
         if (active) val = (float)chunk0[(unsigned)(n - 1 - b) * (unsigned)plane + (unsigned)((yb - 1 + j) * W + x)];
         if (TiltT::kOn) val = add_rn(val, add_rn(txy[j], mul_rn(tilt.az, (float)(z + (n - 1 - b)))));
-        queue.push(active, val, P - Q, 0, 0);
+        queue.push(active, val, TiltT::kNeg ? Q - P : P - Q, 0, 0);  // top cells: (-1)^3 times the vertex coefficient
       }
     }
   }
@@ -465,7 +470,7 @@ __device__ __forceinline__ void sweep3d_wave(const T* __restrict__ g, int D, int
 constexpr int kXchInts = 2 * 4 * s3::kXchWords * kWave;  // exchange words of a block, in ints
 
 // Histogram mode; run_if (may be null): do nothing unless *run_if != 0.
-template <typename T, int R, bool LEVELS, bool TLDS, bool TILT>
+template <typename T, int R, bool LEVELS, bool TLDS, int MODE>
 __global__ __launch_bounds__(256) void sweep3d_kernel(
     const T* __restrict__ grid, int D, int H, int W, int64_t N, int bins, int nstrip, int ngroup,
     int nseg, int planes_per_seg, const HardHeader* __restrict__ hdr,
@@ -492,10 +497,13 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
   queue.sink.lo = LEVELS ? 0.f : hdr->lo;
   queue.sink.scale = LEVELS ? 0.f : hdr->scale;
   WaveRange range;
-  if constexpr (TILT) {
+  if constexpr (MODE == kTilted) {
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
     sweep3d_wave<T, R>(grid + (int64_t)item * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg, queue, xch,
                        range, load_tilt(dir, d));
+  } else if constexpr (MODE == kTopCells) {
+    sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
+                       queue, xch, range, TopCells());
   } else {
     sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
                        queue, xch, range, NoTilt());
@@ -509,7 +517,7 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
 }
 
 // Single-pass mode: critical vertices to the item's list, min / max to the header.
-template <typename T, int R, bool TILT>
+template <typename T, int R, int MODE>
 __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__ grid, int D, int H, int W,
                                                            int64_t N, int nstrip, int ngroup, int nseg,
                                                            int planes_per_seg, ListArgs la, DirArgs dir) {
@@ -525,10 +533,13 @@ __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__
   queue.sink.cap = la.cap;
   queue.sink.overflow = &la.hdr->overflow;
   WaveRange range;
-  if constexpr (TILT) {
+  if constexpr (MODE == kTilted) {
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
     sweep3d_wave<T, R>(grid + (int64_t)item * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg, queue, xch,
                        range, load_tilt(dir, d));
+  } else if constexpr (MODE == kTopCells) {
+    sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
+                       queue, xch, range, TopCells());
   } else {
     sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
                        queue, xch, range, NoTilt());
@@ -571,7 +582,7 @@ constexpr size_t kFixedLds3d = (size_t)4 * kQueueCap * sizeof(float2) + (size_t)
 template <typename T>
 static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
                        const float* table, unsigned long long* hist, hipStream_t st,
-                       const unsigned* run_if, const DirArgs* dir) {
+                       const unsigned* run_if, const DirArgs* dir, bool top) {
   constexpr int R = kRows3d;
   const Plan3d pl = plan3d<T>(s);
   const bool tlds = !levels && (size_t)bins * 8 + kFixedLds3d <= 60 * 1024;
@@ -584,28 +595,39 @@ static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, 
                      hist, run_if, dir ? *dir : none)
   if constexpr (std::is_same<T, float>::value) {
     if (dir) {  // directional call: float grids, thresholds from a range
-      if (tlds) ECC_GO(false, true, true);
-      else ECC_GO(false, false, true);
+      if (tlds) ECC_GO(false, true, kTilted);
+      else ECC_GO(false, false, kTilted);
       return;
     }
   }
-  if (levels) ECC_GO(true, false, false);
-  else if (tlds) ECC_GO(false, true, false);
-  else ECC_GO(false, false, false);
+  if (top) {
+    if (levels) ECC_GO(true, false, kTopCells);
+    else if (tlds) ECC_GO(false, true, kTopCells);
+    else ECC_GO(false, false, kTopCells);
+    return;
+  }
+  if (levels) ECC_GO(true, false, kPlain);
+  else if (tlds) ECC_GO(false, true, kPlain);
+  else ECC_GO(false, false, kPlain);
 #undef ECC_GO
 }
 
 void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
-                         const DirArgs* dir) {
+                         const DirArgs* dir, bool top) {
   const Plan3d pl = plan3d<float>(s);
+  const DirArgs none = {nullptr, 0.f, 1, 3};
   if (dir)
-    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, true>), pl.grid, dim3(256), kFixedLds3d, st, grid,
-                       (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg,
-                       la, *dir);
+    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, kTilted>), pl.grid, dim3(256), kFixedLds3d, st,
+                       grid, (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg,
+                       pl.planes_per_seg, la, *dir);
+  else if (top)
+    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, kTopCells>), pl.grid, dim3(256), kFixedLds3d, st,
+                       grid, (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg,
+                       pl.planes_per_seg, la, none);
   else
-    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, false>), pl.grid, dim3(256), kFixedLds3d, st, grid,
-                       (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg,
-                       la, DirArgs{nullptr, 0.f, 1, 3});
+    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, kPlain>), pl.grid, dim3(256), kFixedLds3d, st,
+                       grid, (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg,
+                       pl.planes_per_seg, la, none);
 }
 
 unsigned sweep3d_list_blocks(const Shape& s) { return plan3d<float>(s).grid.x; }
@@ -619,11 +641,11 @@ bool sweep3d_supported(const Shape& s, int bins) {
 
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st, const unsigned* run_if, const DirArgs* dir) {
+                    hipStream_t st, const unsigned* run_if, const DirArgs* dir, bool top) {
   switch (dtype) {
-    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr); break;
-    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr); break;
-    default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir); break;
+    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, top); break;
+    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, top); break;
+    default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir, top); break;
   }
 }
 
