@@ -210,6 +210,15 @@ struct HistSink {  // drain target: the block's LDS histogram
     else b = bin_from_table(v, table, bins, lo, scale);
     if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
   }
+  // the same with the entries already in registers: lane i < n holds (v, c)
+  __device__ __forceinline__ void take(int n, float v, int c) {
+    const int lane = threadIdx.x & (kWave - 1);
+    if (lane >= n) return;
+    int b;
+    if (LEVELS) b = (v < (float)bins) ? (int)v : bins;
+    else b = bin_from_table(v, table, bins, lo, scale);
+    if (b < bins) atomicAdd(&lhist[b], c);
+  }
 };
 
 // Drain target of the single-pass mode: a list of critical vertices (value, c)
@@ -240,6 +249,17 @@ struct ListSink {
     base = __builtin_amdgcn_readfirstlane(base);
     if (base + (unsigned)n <= cap) {
       if (lane < n) list[base + lane] = buf[lane];
+    } else if (lane == 0) {
+      atomicOr(overflow, 1u);
+    }
+  }
+  __device__ __forceinline__ void take(int n, float v, int c) {
+    const int lane = threadIdx.x & (kWave - 1);
+    unsigned base = 0;
+    if (lane == 0) base = atomicAdd(counter, (unsigned)n);
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (base + (unsigned)n <= cap) {
+      if (lane < n) list[base + lane] = make_float2(v, __int_as_float(c));
     } else if (lane == 0) {
       atomicOr(overflow, 1u);
     }

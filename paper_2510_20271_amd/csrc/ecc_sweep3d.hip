@@ -25,9 +25,11 @@
 // ring(m) = 1 - #arcs(m), an arc starting at edge neighbour k when
 // m_k & ~(m_{k-1} & m_{k-2}).  Hence c = P - Q with
 //   P = 1 + arcs(a & up)[up0] + arcs(a & dn)[dn0],   Q = arcs(a) + up0 + dn0,
-// both summed with bit-sliced full adders.  Only vertices with P != Q (the
-// critical ones) are walked bit by bit; their value is re-read (an L2 hit) and
-// binned into the block's LDS histogram.
+// both summed with bit-sliced full adders and subtracted the same way.  Only
+// vertices with c != 0 (the critical ones) are walked bit by bit, and that walk
+// only notes (position, c) in the wave's LDS queue; the queue is drained 64
+// entries at a time with every lane busy: the value is re-read there (an L2
+// hit) and binned into the block's LDS histogram or appended to the item's list.
 //
 // A chunk is up to 30 planes; the words keep shifting across chunks, so the bit
 // above a chunk's first plane is the last plane of the previous chunk (all ones
@@ -152,30 +154,96 @@ __device__ __forceinline__ void push_plane(Words<R>& w, const float (&v)[R + 2],
   }
 }
 
-// Bit-sliced P = 1 + sum of 8 bits (4-bit result), Q = sum of 6 bits (3-bit result);
-// returns the word of vertices with P != Q and the slices for later extraction.
+// Bit-sliced P = 1 + sum of 8 bits (4-bit result), Q = sum of 6 bits (3-bit result),
+// c = P - Q as four two's-complement slices (-5 <= c <= 7); returns the word of
+// vertices with c != 0.
 struct Slices {
-  unsigned p0, p1, p2, p3, q0, q1, q2;
+  unsigned d0, d1, d2, d3;
 };
 __device__ __forceinline__ unsigned count_pq(const unsigned (&s)[8], const unsigned (&t)[6], Slices& o) {
   const unsigned x1 = xor3(s[0], s[1], s[2]), c1 = maj3(s[0], s[1], s[2]);
   const unsigned x2 = xor3(s[3], s[4], s[5]), c2 = maj3(s[3], s[4], s[5]);
   const unsigned x3 = ~(s[6] ^ s[7]), c3 = s[6] | s[7];  // third input is the constant 1
-  o.p0 = xor3(x1, x2, x3);
+  const unsigned p0 = xor3(x1, x2, x3);
   const unsigned c4 = maj3(x1, x2, x3);
   const unsigned y1 = xor3(c1, c2, c3), d1 = maj3(c1, c2, c3);
-  o.p1 = y1 ^ c4;
+  const unsigned p1 = y1 ^ c4;
   const unsigned d2 = y1 & c4;
-  o.p2 = d1 ^ d2;
-  o.p3 = d1 & d2;
+  const unsigned p2 = d1 ^ d2;
+  const unsigned p3 = d1 & d2;
   const unsigned u1 = xor3(t[0], t[1], t[2]), e1 = maj3(t[0], t[1], t[2]);
   const unsigned u2 = xor3(t[3], t[4], t[5]), e2 = maj3(t[3], t[4], t[5]);
-  o.q0 = u1 ^ u2;
+  const unsigned q0 = u1 ^ u2;
   const unsigned e3 = u1 & u2;
-  o.q1 = xor3(e1, e2, e3);
-  o.q2 = maj3(e1, e2, e3);
-  return (o.p0 ^ o.q0) | (o.p1 ^ o.q1) | (o.p2 ^ o.q2) | o.p3;
+  const unsigned q1 = xor3(e1, e2, e3);
+  const unsigned q2 = maj3(e1, e2, e3);
+  // P - Q with a borrow chain
+  o.d0 = p0 ^ q0;
+  const unsigned b0 = ~p0 & q0;
+  o.d1 = xor3(p1, q1, b0);
+  const unsigned b1 = maj3(~p1, q1, b0);
+  o.d2 = xor3(p2, q2, b1);
+  const unsigned b2 = maj3(~p2, q2, b1);
+  o.d3 = p3 ^ b2;
+  return o.d0 | o.d1 | o.d2 | o.d3;
 }
+
+// Critical-vertex queue of a tube.  The walk over the critical bits only notes where
+// a vertex is (element offset inside its plane; plane counted from the segment's
+// first one) and its coefficient; the value is fetched when 64 entries are drained
+// together, so the walk stays short and the re-read costs one wait per 64 vertices.
+// The directional sweep also keeps the in-plane part of the vertex's tilt.
+template <typename Sink>
+struct TubeQueue {
+  uint2* buf;   // wave-private LDS, kQueueCap entries: (in-plane offset, plane << 8 | c & 0xff)
+  float* tbuf;  // wave-private LDS, kQueueCap in-plane tilts (directional sweep only)
+  int count;    // wave-uniform
+  Sink sink;
+
+  // fetch(in-plane offset, plane, queue slot) -> value of that vertex
+  template <typename F>
+  __device__ __forceinline__ void drain(int n, const F& fetch) {
+    const int lane = threadIdx.x & (kWave - 1);
+    float v = 0.f;
+    int c = 0;
+    if (lane < n) {
+      const uint2 e = buf[lane];
+      c = (int)(e.y << 24) >> 24;
+      v = fetch(e.x, e.y >> 8, lane);
+    }
+    sink.take(n, v, c);
+  }
+  template <bool TILT, typename F>
+  __device__ __forceinline__ void push(bool active, unsigned inplane, unsigned zrel, int c, float txy,
+                                       const F& fetch) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(active);
+    const int idx = count + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
+                                                           __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+    if (active) {
+      buf[idx] = make_uint2(inplane, (zrel << 8) | ((unsigned)c & 0xffu));
+      if (TILT) tbuf[idx] = txy;
+    }
+    count += __builtin_popcountll(m);
+    if (count >= kWave) {
+      drain(kWave, fetch);
+      const int rest = count - kWave;  // < 64
+      const int from = lane < rest ? lane + kWave : lane;
+      const uint2 e = buf[from];
+      const float t = TILT ? tbuf[from] : 0.f;
+      if (lane < rest) {
+        buf[lane] = e;
+        if (TILT) tbuf[lane] = t;
+      }
+      count = rest;
+    }
+  }
+  template <typename F>
+  __device__ __forceinline__ void flush(const F& fetch) {
+    if (count > 0) drain(count, fetch);  // wave-uniform
+    count = 0;
+  }
+};
 
 // arcs of the ring m (order E, NE, N, NW, W, SW, S, SE), gated by g
 __device__ __forceinline__ void arc_starts(const unsigned (&m)[8], unsigned g, unsigned* out) {
@@ -192,7 +260,7 @@ __device__ __forceinline__ void arc_starts(const unsigned (&m)[8], unsigned g, u
 template <typename T, int R, typename Sink, bool SAFE, bool SKIP_TOP, bool SKIP_BOTTOM, typename TiltT>
 __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item_elems, int D, int H,
                                            int W, int xs, int yb, int z0, int z1,
-                                           WaveQueue<Sink>& queue, unsigned* xch, WaveRange& range,
+                                           TubeQueue<Sink>& queue, unsigned* xch, WaveRange& range,
                                            const TiltT& tilt) {
   constexpr bool skip_top = SKIP_TOP, skip_bottom = SKIP_BOTTOM;
   const int lane = threadIdx.x & (kWave - 1);
@@ -249,6 +317,15 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
       if (SAFE) f = (inb && rok[j]) ? f : (TiltT::kNeg ? -INFINITY : INFINITY);
       dst[j] = f;
     }
+  };
+
+  // value of a queued critical vertex: plane zrel of the segment (the launch plan keeps a
+  // segment's element offsets below 2^32), in-plane offset inpl
+  const T* const seg0 = g + (int64_t)z0 * plane;
+  auto fetch = [&](unsigned inpl, unsigned zrel, int slot) {
+    float val = (float)seg0[zrel * (unsigned)plane + inpl];
+    if (TiltT::kOn) val = add_rn(val, add_rn(queue.tbuf[slot], mul_rn(tilt.az, (float)(z0 + (int)zrel))));
+    return val;
   };
 
   Words<R> w;
@@ -357,7 +434,6 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
     }
     // plane z+i sits at bit n-1-i of every word; the plane below the chunk at bit n of U
     const unsigned planes = (n >= 32) ? 0xffffffffu : ((1u << n) - 1u);
-    const T* const chunk0 = g + (int64_t)z * plane;  // first plane of the chunk (32-bit offsets from here)
 
 #pragma unroll
     for (int j = 1; j <= R; ++j) {
@@ -405,22 +481,21 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
       unsigned nz = count_pq(s, t, sl) & planes;
       const bool row_ok = !SAFE || rok[j];
       if (!(out_lane && row_ok)) nz = 0u;
+      const unsigned inpl = (unsigned)((yb - 1 + j) * W + x);
       while (ballot(nz != 0)) {
         const bool active = nz != 0;
         const int b = active ? 31 - __clz(nz) : 0;
         nz &= ~(1u << b);
-        const int P = (int)((sl.p0 >> b) & 1u) + 2 * (int)((sl.p1 >> b) & 1u) +
-                      4 * (int)((sl.p2 >> b) & 1u) + 8 * (int)((sl.p3 >> b) & 1u);
-        const int Q = (int)((sl.q0 >> b) & 1u) + 2 * (int)((sl.q1 >> b) & 1u) +
-                      4 * (int)((sl.q2 >> b) & 1u);
-        float val = 0.f;  // the critical vertex's value: re-read, most likely an L2 hit
-        if (active) val = (float)chunk0[(unsigned)(n - 1 - b) * (unsigned)plane + (unsigned)((yb - 1 + j) * W + x)];
-        if (TiltT::kOn) val = add_rn(val, add_rn(txy[j], mul_rn(tilt.az, (float)(z + (n - 1 - b)))));
-        queue.push(active, val, TiltT::kNeg ? Q - P : P - Q, 0, 0);  // top cells: (-1)^3 times the vertex coefficient
+        const unsigned cu = ((sl.d0 >> b) & 1u) | (((sl.d1 >> b) & 1u) << 1) | (((sl.d2 >> b) & 1u) << 2) |
+                            (((sl.d3 >> b) & 1u) << 3);
+        const int c = (int)(cu ^ 8u) - 8;
+        // top cells: (-1)^3 times the vertex coefficient
+        queue.template push<TiltT::kOn>(active, inpl, (unsigned)(z - z0 + n - 1 - b), TiltT::kNeg ? -c : c, txy[j],
+                                        fetch);
       }
     }
   }
-  queue.flush();
+  queue.flush(fetch);
 }
 
 }  // namespace s3
@@ -432,7 +507,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 template <typename T, int R, typename Sink, typename TiltT>
 __device__ __forceinline__ void sweep3d_wave(const T* __restrict__ g, int D, int H, int W, int64_t N,
                                              int nstrip, int ngroup, int nseg, int planes_per_seg,
-                                             WaveQueue<Sink>& queue, unsigned* xch, WaveRange& range,
+                                             s3::TubeQueue<Sink>& queue, unsigned* xch, WaveRange& range,
                                              const TiltT& tilt) {
   // unit = ((seg * nstrip) + strip) * ngroup4 + group, group fastest
   const int ngroup4 = (ngroup + 3) & ~3;
@@ -478,18 +553,20 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
     const unsigned* __restrict__ run_if, DirArgs dir) {
   if (run_if && *run_if == 0) return;
   extern __shared__ int smem[];
-  // [2][4 waves][9][64] exchange words, [4 waves] queues, histogram, table
+  // [2][4 waves][9][64] exchange words, [4 waves] queues (entries, tilts), histogram, table
   unsigned* xch = reinterpret_cast<unsigned*>(smem);
-  float2* qbuf = reinterpret_cast<float2*>(smem + kXchInts) + (threadIdx.x >> 6) * kQueueCap;
-  int* lhist = smem + kXchInts + 4 * kQueueCap * 2;
+  uint2* qbuf = reinterpret_cast<uint2*>(smem + kXchInts) + (threadIdx.x >> 6) * kQueueCap;
+  float* tbuf = reinterpret_cast<float*>(smem + kXchInts + 4 * kQueueCap * 2) + (threadIdx.x >> 6) * kQueueCap;
+  int* lhist = smem + kXchInts + 4 * kQueueCap * 3;
   float* ltable = reinterpret_cast<float*>(lhist + bins);
   for (int b = threadIdx.x; b < bins; b += 256) {
     lhist[b] = 0;
     if (TLDS) ltable[b] = table[b];
   }
   __syncthreads();
-  WaveQueue<HistSink<LEVELS>> queue;
+  s3::TubeQueue<HistSink<LEVELS>> queue;
   queue.buf = qbuf;
+  queue.tbuf = tbuf;
   queue.count = 0;
   queue.sink.lhist = lhist;
   queue.sink.table = TLDS ? ltable : table;
@@ -523,9 +600,10 @@ __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__
                                                            int planes_per_seg, ListArgs la, DirArgs dir) {
   extern __shared__ int smem[];
   unsigned* xch = reinterpret_cast<unsigned*>(smem);
-  float2* qbuf = reinterpret_cast<float2*>(smem + kXchInts) + (threadIdx.x >> 6) * kQueueCap;
-  WaveQueue<ListSink> queue;
+  uint2* qbuf = reinterpret_cast<uint2*>(smem + kXchInts) + (threadIdx.x >> 6) * kQueueCap;
+  s3::TubeQueue<ListSink> queue;
   queue.buf = qbuf;
+  queue.tbuf = reinterpret_cast<float*>(smem + kXchInts + 4 * kQueueCap * 2) + (threadIdx.x >> 6) * kQueueCap;
   queue.count = 0;
   const unsigned sub = blockIdx.y * la.nsub + (blockIdx.x & (la.nsub - 1u));
   queue.sink.list = la.lists + (size_t)sub * la.cap;
@@ -569,15 +647,20 @@ static Plan3d plan3d(const Shape& s) {
   const int64_t max_seg = (D + s3::kChunk - 1) / s3::kChunk;
   if (nseg > max_seg) nseg = max_seg;
   if (nseg < 1) nseg = 1;
-  // whole chunks per segment
-  const int64_t planes = ((D + nseg - 1) / nseg + s3::kChunk - 1) / s3::kChunk * s3::kChunk;
+  // whole chunks per segment; a segment's element offsets stay below 2^32 and its plane
+  // count below 2^24 (what the critical-vertex queue stores)
+  int64_t planes = ((D + nseg - 1) / nseg + s3::kChunk - 1) / s3::kChunk * s3::kChunk;
+  int64_t fit = (((int64_t)1 << 32) - 1) / ((int64_t)H * W);
+  if (fit > (1 << 24) - 1) fit = (1 << 24) - 1;
+  fit = fit / s3::kChunk * s3::kChunk;  // >= one chunk: a supported plane has fewer than 2^27 elements
+  if (planes > fit) planes = fit;
   p.planes_per_seg = (int)planes;
   p.nseg = (int)((D + p.planes_per_seg - 1) / p.planes_per_seg);
   const int64_t units = (int64_t)p.nseg * p.nstrip * ngroup4;
   p.grid = dim3((unsigned)(units / 4), (unsigned)s.batch);
   return p;
 }
-constexpr size_t kFixedLds3d = (size_t)4 * kQueueCap * sizeof(float2) + (size_t)kXchInts * 4;
+constexpr size_t kFixedLds3d = (size_t)4 * kQueueCap * (sizeof(uint2) + sizeof(float)) + (size_t)kXchInts * 4;
 
 template <typename T>
 static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
