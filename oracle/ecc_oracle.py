@@ -132,12 +132,16 @@ def ecc_cellmax(X: np.ndarray, t: np.ndarray) -> np.ndarray:
 # ----------------------------------------------------------------------------
 
 
-def _precedes(X: np.ndarray):
-    """dict offset -> boolean array: neighbour p+offset exists and precedes p."""
+def _precedes(X: np.ndarray, descending: bool = False):
+    """dict offset -> boolean array: neighbour p+offset exists and precedes p.
+    descending: the filtration runs from high values to low ones (superlevel sets),
+    so larger values come first; ties still go by the index."""
     nd = X.ndim
     Xd = np.asarray(X, dtype=np.float64)
     if not np.all(np.isfinite(Xd)):
         raise ValueError("grid must be finite")
+    if descending:
+        Xd = -Xd
     idx = np.arange(Xd.size, dtype=np.int64).reshape(Xd.shape)
     Xp = np.pad(Xd, 1, mode="constant", constant_values=np.inf)
     Ip = np.pad(idx, 1, mode="constant", constant_values=np.iinfo(np.int64).max)
@@ -152,10 +156,10 @@ def _precedes(X: np.ndarray):
     return prec
 
 
-def coeff(X: np.ndarray) -> np.ndarray:
+def coeff(X: np.ndarray, descending: bool = False) -> np.ndarray:
     """c(p) of one 2D or 3D grid, int8, same shape as X."""
     nd = X.ndim
-    prec = _precedes(X)
+    prec = _precedes(X, descending)
     c = np.ones(X.shape, dtype=np.int64)  # the vertex itself
     for o in itertools.product((-1, 0, 1), repeat=nd):
         dim = sum(1 for a in o if a)
@@ -222,14 +226,15 @@ def ecc_top_bruteforce(X: np.ndarray, t: np.ndarray) -> np.ndarray:
     return np.array([euler_characteristic_topcells(X <= tb) for tb in t], dtype=np.int64)
 
 
-def coeff_top(X: np.ndarray) -> np.ndarray:
+def coeff_top(X: np.ndarray, descending: bool = False) -> np.ndarray:
     """Per-top-cell coefficient: every cell is charged to the FIRST top cell around
     it (X, then C-order index).  That is the vertex coefficient of the reversed
-    order with everything outside the grid coming before, times (-1)^d."""
+    order with everything outside the grid coming before, times (-1)^d.
+    descending: superlevel filtration, larger values come first."""
     X = np.asarray(X)
     d = X.ndim
     idx = np.arange(X.size, dtype=np.int64).reshape(X.shape)
-    big = X.astype(np.float64)
+    big = -X.astype(np.float64) if descending else X.astype(np.float64)
     c = np.zeros(X.shape, dtype=np.int64)
     import itertools
     pad_v = np.pad(big, 1, constant_values=np.inf)        # outside: never first
@@ -260,6 +265,50 @@ def ecc_top(X: np.ndarray, t: np.ndarray) -> np.ndarray:
 
 def ecc_top_batch(Xb: np.ndarray, t: np.ndarray) -> np.ndarray:
     return np.stack([ecc_top(x, t) for x in Xb])
+
+
+# ----------------------------------------------------------------------------
+# superlevel filtration: Omega^tau = {p : X(p) >= tau} in place of Eq. 1, for
+# either construction.  The curve is read at the LOWER edges of the bins,
+# t'_0 = lo and t'_b = t_{b-1}, so that its first entry is the whole grid.
+# ----------------------------------------------------------------------------
+
+
+def thresholds_lower(t_upper: np.ndarray, lo: float) -> np.ndarray:
+    """Lower bin edges that go with the upper edges t_upper of the same bins:
+    float32(lo), then t_upper without its last entry."""
+    return np.concatenate([[np.float64(np.float32(lo))], np.asarray(t_upper, dtype=np.float64)[:-1]])
+
+
+def thresholds_levels_super(bins: int) -> np.ndarray:
+    """Integer grids without a range: t'_b = b (X >= b)."""
+    return np.arange(bins, dtype=np.float64)
+
+
+def bin_index_super(x: np.ndarray, t: np.ndarray) -> np.ndarray:
+    """max{ b : t_b <= x }; -1 when x is below every threshold (in no superlevel set)."""
+    return np.searchsorted(t, np.asarray(x, dtype=np.float64), side="right") - 1
+
+
+def ecc_super_bruteforce(X: np.ndarray, t: np.ndarray, top: bool = False) -> np.ndarray:
+    chi = euler_characteristic_topcells if top else euler_characteristic_mask
+    Xd = np.asarray(X, dtype=np.float64)
+    return np.array([chi(Xd >= tb) for tb in t], dtype=np.int64)
+
+
+def ecc_super(X: np.ndarray, t: np.ndarray, top: bool = False) -> np.ndarray:
+    """Superlevel curve through the per-point coefficients of the descending order:
+    a point with t_b <= X(p) is in the sets of thresholds 0 .. b."""
+    c = coeff_top(X, descending=True) if top else coeff(X, descending=True)
+    nb = len(t)
+    b = bin_index_super(np.asarray(X).ravel(), t)
+    hist = np.zeros(nb + 1, dtype=np.int64)          # slot nb collects the dropped points (b = -1)
+    np.add.at(hist, b, c.ravel().astype(np.int64))
+    return np.cumsum(hist[:nb][::-1])[::-1]
+
+
+def ecc_super_batch(Xb: np.ndarray, t: np.ndarray, top: bool = False) -> np.ndarray:
+    return np.stack([ecc_super(x, t, top) for x in Xb])
 
 
 # ----------------------------------------------------------------------------

@@ -371,3 +371,66 @@ def test_topcell_coefficient_is_the_reversed_vertex_coefficient_in_the_interior(
         b = (-1) ** len(shape) * O.coeff(-X)
         inner = tuple(slice(1, -1) for _ in shape)
         assert np.array_equal(a[inner], b[inner])
+
+
+# ---- superlevel filtration --------------------------------------------------------
+
+
+def test_superlevel_closed_forms():
+    t = np.array([0.0, 1.0, 2.0, 3.0])
+    const = np.full((4, 5), 2.0)
+    assert O.ecc_super_bruteforce(const, t).tolist() == [1, 1, 1, 0]        # one box until tau passes the value
+    ramp = np.arange(12, dtype=np.float64).reshape(3, 4)
+    tt = np.arange(13, dtype=np.float64)
+    assert O.ecc_super_bruteforce(ramp, tt).tolist() == [1] * 12 + [0]      # a shrinking staircase, then nothing
+    peaks = np.zeros((5, 5))
+    peaks[1, 1] = peaks[3, 3] = 5.0
+    peaks[1, 3] = 4.0
+    assert O.ecc_super_bruteforce(peaks, np.array([0.0, 4.0, 5.0])).tolist() == [1, 3, 2]
+    pit = np.ones((3, 3))
+    pit[1, 1] = 0.0
+    assert O.ecc_super_bruteforce(pit, np.array([0.0, 1.0])).tolist() == [1, 0]          # box, then a ring
+    assert O.ecc_super_bruteforce(pit, np.array([0.0, 1.0]), top=True).tolist() == [1, 0]
+    diag = np.eye(2)
+    assert O.ecc_super_bruteforce(diag, np.array([1.0])).tolist() == [2]                 # two vertices
+    assert O.ecc_super_bruteforce(diag, np.array([1.0]), top=True).tolist() == [1]       # two squares sharing a corner
+
+
+@pytest.mark.parametrize("top", [False, True])
+@pytest.mark.parametrize("shape", [(1, 1), (1, 5), (4, 1), (3, 3), (5, 6), (2, 2, 2), (1, 3, 4), (3, 4, 5)])
+def test_superlevel_coefficients_reproduce_the_brute_force_curve(shape, top):
+    rng = np.random.default_rng(sum(shape) + 100 * top)
+    for levels in (2, 3, 50):
+        for _ in range(8):
+            X = rng.integers(0, levels, size=shape).astype(np.float32)
+            t = O.thresholds_levels_super(levels)
+            c = O.coeff_top(X, descending=True) if top else O.coeff(X, descending=True)
+            assert c.sum() == 1
+            got = O.ecc_super(X, t, top)
+            assert got[0] == 1                                              # X >= 0 is the whole grid
+            assert np.array_equal(got, O.ecc_super_bruteforce(X, t, top))
+            # thresholds that leave points out on both sides
+            t2 = np.array([1.0, levels / 2, levels - 1.5])
+            assert np.array_equal(O.ecc_super(X, t2, top), O.ecc_super_bruteforce(X, t2, top))
+
+
+@pytest.mark.parametrize("top", [False, True])
+def test_superlevel_is_the_sublevel_curve_of_the_negated_grid(top):
+    # {X >= tau} = {-X <= -tau}: the sublevel functions, pinned on their own, give the same numbers
+    rng = np.random.default_rng(8)
+    for shape in ((6, 7), (4, 5, 6)):
+        X = rng.integers(-4, 5, size=shape).astype(np.float64)
+        t = np.array([-3.0, -1.0, 0.0, 0.5, 2.0, 4.0])
+        sub = (O.ecc_top_bruteforce if top else O.ecc_bruteforce)(-X, -t[::-1])[::-1]
+        assert np.array_equal(O.ecc_super(X, t, top), sub)
+        sub3 = (O.ecc_top if top else O.ecc_hard)(-X, -t[::-1])[::-1]
+        assert np.array_equal(O.ecc_super(X, t, top), sub3)
+
+
+def test_lower_thresholds_are_the_upper_ones_shifted_by_a_bin():
+    up = O.thresholds_equal_width(-1.5, 2.25, 7)
+    lowr = O.thresholds_lower(up, -1.5)
+    assert lowr[0] == np.float32(-1.5) and np.array_equal(lowr[1:], up[:-1])
+    x = np.array([-2.0, -1.5, -1.4, 2.25, 3.0, up[2], np.nextafter(up[2], -np.inf)])
+    b = O.bin_index_super(x, lowr)
+    assert b.tolist() == [-1, 0, 0, 6, 6, 3, 2]
