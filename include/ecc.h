@@ -152,6 +152,31 @@ int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch,
                  void* hip_stream);
 
 /*
+ * Hard ECC with the construction and the direction of the filtration chosen by
+ * the caller (the Background section fixes neither beyond "cubical complex" and
+ * sublevel sets; superlevel sets are the same definition, Eq. 1-2, on the
+ * descending order):
+ *   construction  ECC_VERTEX (as ecc_hard) or ECC_TOPCELL (as ecc_hard_top)
+ *   filtration    ECC_SUBLEVEL: curve[i][b] = chi({p : X(p) <= t_b}), as those two;
+ *                 ECC_SUPERLEVEL: curve[i][b] = chi({p : X(p) >= t'_b}), read at the
+ *                 LOWER edges of the same bins: t'_0 = float32(lo), t'_b = t_{b-1}
+ *                 (so curve[i][0] is the whole grid when lo is the minimum); integer
+ *                 grids without a range: t'_b = b.  The comparison X >= t'_b is made
+ *                 in float32 on that table, like X <= t_b for sublevel sets.
+ * The superlevel curve is the sum of per-point coefficients over the points with
+ * X(p) >= t'_b (Eq. 3 on the descending order), binned by max{b : t'_b <= X(p)}
+ * and summed from the last bin down.  Everything else -- arguments, range, bins,
+ * output, workspace, errors -- is as for ecc_hard.
+ */
+#define ECC_VERTEX 0
+#define ECC_TOPCELL 1
+#define ECC_SUBLEVEL 0
+#define ECC_SUPERLEVEL 1
+int ecc_hard_ex(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int construction,
+                int filtration, int bins, const double* range, int64_t* curve, void* workspace,
+                size_t workspace_bytes, void* hip_stream);
+
+/*
  * Directional hard curves (Background: the Euler characteristic transform looks at
  * a shape along directions; Eq. 6 tilts the filtration by alpha <u, p>).  For
  * every direction u_k the field

@@ -101,7 +101,7 @@ size_t ecc_workspace_bytes(int ndim, const int64_t* dims, int64_t batch, int bin
   return a > b ? a : b;
 }
 
-static int hard_common(bool top, const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
+static int hard_common(int conv, const char* who, const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
              const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
              void* hip_stream) {
   ecc::Shape s;
@@ -128,22 +128,34 @@ static int hard_common(bool top, const void* grid, int ndim, const int64_t* dims
   if ((rc = check_workspace(workspace, workspace_bytes, ecc::hard_workspace_bytes(s, bins))) != ECC_OK)
     return rc;
   return device_status(ecc::launch_hard(grid, s, dtype, bins, range != nullptr, lo, hi, curve, workspace,
-                                        static_cast<hipStream_t>(hip_stream), nullptr, top),
-                       top ? "ecc_hard_top" : "ecc_hard");
+                                        static_cast<hipStream_t>(hip_stream), nullptr, conv),
+                       who);
 }
 
 int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
              const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
              void* hip_stream) {
-  return hard_common(false, grid, ndim, dims, batch, dtype, bins, range, curve, workspace, workspace_bytes,
+  return hard_common(0, "ecc_hard", grid, ndim, dims, batch, dtype, bins, range, curve, workspace, workspace_bytes,
                      hip_stream);
 }
 
 int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
                  const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
                  void* hip_stream) {
-  return hard_common(true, grid, ndim, dims, batch, dtype, bins, range, curve, workspace, workspace_bytes,
+  return hard_common(ecc::kConvTop, "ecc_hard_top", grid, ndim, dims, batch, dtype, bins, range, curve, workspace, workspace_bytes,
                      hip_stream);
+}
+
+int ecc_hard_ex(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int construction,
+                int filtration, int bins, const double* range, int64_t* curve, void* workspace,
+                size_t workspace_bytes, void* hip_stream) {
+  if (construction != ECC_VERTEX && construction != ECC_TOPCELL)
+    return fail(ECC_ERR_INVALID_ARG, "construction must be ECC_VERTEX or ECC_TOPCELL, got %d", construction);
+  if (filtration != ECC_SUBLEVEL && filtration != ECC_SUPERLEVEL)
+    return fail(ECC_ERR_INVALID_ARG, "filtration must be ECC_SUBLEVEL or ECC_SUPERLEVEL, got %d", filtration);
+  const int conv = (construction == ECC_TOPCELL ? ecc::kConvTop : 0) | (filtration == ECC_SUPERLEVEL ? ecc::kConvSuper : 0);
+  return hard_common(conv, "ecc_hard_ex", grid, ndim, dims, batch, dtype, bins, range, curve, workspace,
+                     workspace_bytes, hip_stream);
 }
 
 size_t ecc_workspace_bytes_dir(int ndim, const int64_t* dims, int64_t batch, int ndir, int bins) {

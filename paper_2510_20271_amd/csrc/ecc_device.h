@@ -8,6 +8,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ecc_internal.h"
+
 namespace ecc {
 
 constexpr int kWave = 64;
@@ -47,9 +49,12 @@ __device__ __forceinline__ int coeff_3d(unsigned a, unsigned up, bool up0, unsig
 
 // Coefficient of the vertex (z,y,x) read straight from global memory, with
 // bounds checks; the reference path for every dtype and shape.
-// TOP: the order is reversed and vertices outside the grid come before every
-// vertex (top-cell construction, see TopCells below); the caller applies (-1)^d.
-template <typename T, int ND, bool TOP = false>
+// REV: larger values come first (ties still by index).  OUTFIRST: vertices outside
+// the grid come before every vertex instead of after.  Both together give, up to the
+// sign (-1)^d the caller applies, the top-cell construction (see TopCells below);
+// REV alone the vertex construction of superlevel sets; OUTFIRST alone the top-cell
+// construction of superlevel sets.
+template <typename T, int ND, bool OUTFIRST = false, bool REV = false>
 __device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int64_t H, int64_t W,
                                         int64_t z, int64_t y, int64_t x) {
   const int64_t ip = (z * H + y) * W + x;
@@ -65,11 +70,11 @@ __device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int6
       for (int dx = -1; dx <= 1; ++dx) {
         if (dz == 0 && dy == 0 && dx == 0) continue;
         const int64_t qz = z + dz, qy = y + dy, qx = x + dx;
-        bool b = TOP;
+        bool b = OUTFIRST;
         if (qz >= 0 && qz < D && qy >= 0 && qy < H && qx >= 0 && qx < W) {
           const T vq = g[(qz * H + qy) * W + qx];
           const bool later = (dz > 0) || (dz == 0 && (dy > 0 || (dy == 0 && dx > 0)));
-          if (TOP) b = later ? (vq > vp) : (vq >= vp);
+          if (REV) b = later ? (vq > vp) : (vq >= vp);
           else b = later ? (vq < vp) : (vq <= vp);
         }
         if (dy == 0 && dx == 0) centre[dz + 1] = b;
@@ -127,6 +132,31 @@ __device__ __forceinline__ int bin_from_table(float x, const float* __restrict__
   return b;
 }
 
+// Superlevel curves (X >= tau) are read at the LOWER edges of the same bins:
+// t'_0 = float32(lo), t'_b = t_{b-1}.  bin(x) = max{ b : t'_b <= x }; `bins` when
+// x is below every threshold (in no superlevel set).
+__device__ __forceinline__ float threshold_lower_at(int b, int bins, double lo, double hi) {
+  return (b == 0) ? __double2float_rn(lo) : threshold_at(b - 1, bins, lo, hi);
+}
+__device__ __forceinline__ int bin_super_from_table(float x, const float* __restrict__ t, int bins,
+                                                    float lo, float scale) {
+  float f = (x - lo) * scale;
+  int b = (f > 0.0f) ? (int)fminf(f, (float)(bins - 1)) : 0;
+  while (b < bins - 1 && x >= t[b + 1]) ++b;
+  while (b >= 0 && x < t[b]) --b;
+  return b < 0 ? bins : b;
+}
+// integer grids without a range: thresholds t_b = b; X <= b (sublevel) or X >= b (superlevel)
+template <bool SUPER>
+__device__ __forceinline__ int bin_levels(float v, int bins) {
+  if (SUPER) return (v < (float)bins) ? (int)v : bins - 1;
+  return (v < (float)bins) ? (int)v : bins;
+}
+template <bool SUPER>
+__device__ __forceinline__ int bin_table(float x, const float* __restrict__ t, int bins, float lo, float scale) {
+  return SUPER ? bin_super_from_table(x, t, bins, lo, scale) : bin_from_table(x, t, bins, lo, scale);
+}
+
 template <typename T> __device__ __forceinline__ float as_float(T v) { return (float)v; }
 
 // ---- tilted filtration (directional curves) ------------------------------------
@@ -154,18 +184,41 @@ __device__ __forceinline__ float add_rn(float a, float b) {
 // it), so the same stencil serves both constructions; the value that is binned is
 // the original one.
 struct NoTilt {
-  static constexpr bool kOn = false, kNeg = false;
+  static constexpr bool kOn = false, kNeg = false, kTop = false;
   float ax, ay, az;
 };
 struct Tilt {
-  static constexpr bool kOn = true, kNeg = false;
+  static constexpr bool kOn = true, kNeg = false, kTop = false;
   float ax, ay, az;
 };
 struct TopCells {
-  static constexpr bool kOn = false, kNeg = true;
+  static constexpr bool kOn = false, kNeg = true, kTop = true;
   float ax, ay, az;
 };
-enum SweepMode { kPlain = 0, kTilted = 1, kTopCells = 2 };
+// Superlevel sets (X >= tau): the same two constructions on the descending order.
+// Vertex construction: the negated field, outside last (kNeg only).  Top-cell
+// construction: the descending order reversed is the field's own order, so the
+// field is swept as it is with the top-cell conventions (kTop only).
+struct Super {
+  static constexpr bool kOn = false, kNeg = true, kTop = false;
+  float ax, ay, az;
+};
+struct TopSuper {
+  static constexpr bool kOn = false, kNeg = false, kTop = true;
+  float ax, ay, az;
+};
+// kNeg: the field is negated as it is loaded (zeros stay +0).  kTop: what lies
+// outside the grid comes before every vertex, and the coefficient is (-1)^d times
+// the stencil's.  The value that is binned is always the original one.
+enum SweepMode { kPlain = 0, kTilted = 1, kTopCells = 2, kSuper = 3, kTopSuper = 4 };
+__host__ __device__ constexpr bool mode_is_super(int mode) { return mode == kSuper || mode == kTopSuper; }
+template <int MODE> struct ModeTransform { typedef NoTilt type; };
+template <> struct ModeTransform<kTopCells> { typedef TopCells type; };
+template <> struct ModeTransform<kSuper> { typedef Super type; };
+template <> struct ModeTransform<kTopSuper> { typedef TopSuper type; };
+constexpr int mode_of_conv(int conv) {
+  return conv == 0 ? kPlain : conv == kConvTop ? kTopCells : conv == kConvSuper ? kSuper : kTopSuper;
+}
 struct DirArgs {
   const float* u;  // device [ndir][ndim]
   float alpha;
@@ -188,7 +241,7 @@ __device__ __forceinline__ Tilt load_tilt(const DirArgs& d, int dir) {
 // A sink names its entry type (what the queue stores per critical vertex), makes
 // an entry from (value, c, column, row) and consumes the first n entries of the
 // queue buffer with the whole wave (n is wave-uniform, n <= 64).
-template <bool LEVELS>
+template <bool LEVELS, bool SUPER = false>
 struct HistSink {  // drain target: the block's LDS histogram
   typedef float2 Entry;
   static constexpr bool kTrackRange = false;
@@ -206,8 +259,8 @@ struct HistSink {  // drain target: the block's LDS histogram
     const Entry e = buf[lane];
     const float v = e.x;
     int b;
-    if (LEVELS) b = (v < (float)bins) ? (int)v : bins;
-    else b = bin_from_table(v, table, bins, lo, scale);
+    if (LEVELS) b = bin_levels<SUPER>(v, bins);
+    else b = bin_table<SUPER>(v, table, bins, lo, scale);
     if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
   }
   // the same with the entries already in registers: lane i < n holds (v, c)
@@ -215,8 +268,8 @@ struct HistSink {  // drain target: the block's LDS histogram
     const int lane = threadIdx.x & (kWave - 1);
     if (lane >= n) return;
     int b;
-    if (LEVELS) b = (v < (float)bins) ? (int)v : bins;
-    else b = bin_from_table(v, table, bins, lo, scale);
+    if (LEVELS) b = bin_levels<SUPER>(v, bins);
+    else b = bin_table<SUPER>(v, table, bins, lo, scale);
     if (b < bins) atomicAdd(&lhist[b], c);
   }
 };

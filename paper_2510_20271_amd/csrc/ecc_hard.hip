@@ -83,10 +83,11 @@ __global__ __launch_bounds__(kBlock) void minmax_f32_kernel(const float* __restr
 // thresholds + zeroed histogram
 // ---------------------------------------------------------------------------
 // t_b = float32(lo + (b+1)(hi-lo)/B) in float64 with every operation rounded
-// on its own (no contraction), t_{B-1} = float32(hi).
+// on its own (no contraction), t_{B-1} = float32(hi); lower != 0: the lower edges
+// of the same bins (superlevel curves).
 __global__ void prepare_kernel(HardHeader* h, float* __restrict__ table, int bins, int from_device,
                                double lo_host, double hi_host, unsigned long long* hist,
-                               int64_t hist_len) {
+                               int64_t hist_len, int lower) {
   double lo, hi;
   if (from_device) {
     lo = (double)key_float(h->min_key);
@@ -97,7 +98,8 @@ __global__ void prepare_kernel(HardHeader* h, float* __restrict__ table, int bin
   }
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t b = tid; b < bins; b += stride) table[b] = threshold_at((int)b, bins, lo, hi);
+  for (int64_t b = tid; b < bins; b += stride)
+    table[b] = lower ? threshold_lower_at((int)b, bins, lo, hi) : threshold_at((int)b, bins, lo, hi);
   for (int64_t i = tid; i < hist_len; i += stride) hist[i] = 0ull;
   if (tid == 0) {
     h->lo = __double2float_rn(lo);
@@ -108,8 +110,10 @@ __global__ void prepare_kernel(HardHeader* h, float* __restrict__ table, int bin
 // ---------------------------------------------------------------------------
 // generic sweep: one thread per vertex, neighbours read through the caches
 // ---------------------------------------------------------------------------
-// TOP: top-cell construction (reversed order, outside first, (-1)^d times the vertex formula)
-template <typename T, int ND, bool LEVELS, bool TOP>
+// CONV: kConvTop (top-cell construction: outside first, (-1)^d times the vertex formula) and /
+// or kConvSuper (superlevel sets: descending order, lower bin edges); the order the stencil
+// runs on is reversed when exactly one of the two is set
+template <typename T, int ND, bool LEVELS, int CONV>
 __global__ __launch_bounds__(kBlock) void sweep_generic_kernel(
     const T* __restrict__ grid, int64_t D, int64_t H, int64_t W, int64_t N, int bins,
     const HardHeader* __restrict__ hdr, const float* __restrict__ table,
@@ -126,13 +130,14 @@ __global__ __launch_bounds__(kBlock) void sweep_generic_kernel(
     const int64_t r = i / W;
     const int64_t y = r % H;
     const int64_t z = r / H;
-    int c = coeff_at<T, ND, TOP>(g, D, H, W, z, y, x);
+    constexpr bool TOP = (CONV & kConvTop) != 0, SUPER = (CONV & kConvSuper) != 0;
+    int c = coeff_at<T, ND, TOP, TOP != SUPER>(g, D, H, W, z, y, x);
     if (TOP && ND == 3) c = -c;
     if (c != 0) {
       const T v = g[i];
       int b;
-      if (LEVELS) b = ((int64_t)v < (int64_t)bins) ? (int)v : bins;
-      else b = bin_from_table(as_float(v), table, bins, lo, scale);
+      if (LEVELS) b = bin_levels<SUPER>(as_float(v), bins);
+      else b = bin_table<SUPER>(as_float(v), table, bins, lo, scale);
       if (b < bins) atomicAdd(&lhist[b], c);
     }
   }
@@ -150,8 +155,9 @@ __global__ __launch_bounds__(kBlock) void sweep_generic_kernel(
 // Every block builds the threshold table from the range the sweep found (LDS);
 // block (0, 0) also leaves it, with the factor of the bin guess, in the
 // workspace for the histogram-mode sweep that runs if a list overflowed.
+// lower != 0: superlevel curves (lower bin edges, bin = last threshold <= value).
 __global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, float* __restrict__ table, int bins,
-                                                         unsigned long long* __restrict__ hist) {
+                                                         unsigned long long* __restrict__ hist, int lower) {
   extern __shared__ int lhist[];
   float* ltable = reinterpret_cast<float*>(lhist + bins);
   const double lo_d = (double)key_float(la.hdr->min_key), hi_d = (double)key_float(la.hdr->max_key);
@@ -160,7 +166,7 @@ __global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, float* __r
   const bool overflow = la.hdr->overflow != 0u;  // the two-pass sweep that follows does the work
   if (overflow && !first) return;
   for (int b = threadIdx.x; b < bins; b += kBlock) {
-    const float t = threshold_at(b, bins, lo_d, hi_d);
+    const float t = lower ? threshold_lower_at(b, bins, lo_d, hi_d) : threshold_at(b, bins, lo_d, hi_d);
     ltable[b] = t;
     lhist[b] = 0;
     if (first) table[b] = t;
@@ -178,7 +184,8 @@ __global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, float* __r
     const unsigned n = min(la.counters[sub], la.cap);
     for (unsigned i = threadIdx.x; i < n; i += kBlock) {
       const float2 e = list[i];
-      const int b = bin_from_table(e.x, ltable, bins, lo, scale);
+      const int b = lower ? bin_super_from_table(e.x, ltable, bins, lo, scale)
+                          : bin_from_table(e.x, ltable, bins, lo, scale);
       if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
     }
   }
@@ -191,15 +198,18 @@ __global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, float* __r
 }
 
 // ---------------------------------------------------------------------------
-// inclusive prefix sum, one block per batch item, in place (int64)
+// inclusive prefix sum, one block per batch item, in place (int64); suffix != 0:
+// inclusive suffix sum instead (superlevel curves: a point of bin b is in the sets
+// of the thresholds 0 .. b), which is the prefix sum over the mirrored index
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void scan_kernel(long long* __restrict__ curve, int bins) {
+__global__ __launch_bounds__(kBlock) void scan_kernel(long long* __restrict__ curve, int bins, int suffix) {
   long long* c = curve + (int64_t)blockIdx.x * bins;
+  auto at = [&](int b) -> long long& { return c[suffix ? bins - 1 - b : b]; };
   const int per = (bins + kBlock - 1) / kBlock;
   const int b0 = threadIdx.x * per;
   const int b1 = min(b0 + per, bins);
   long long s = 0;
-  for (int b = b0; b < b1; ++b) s += c[b];
+  for (int b = b0; b < b1; ++b) s += at(b);
   __shared__ long long part[kBlock];
   part[threadIdx.x] = s;
   __syncthreads();
@@ -212,8 +222,8 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(long long* __restrict__ cu
   }
   long long run = part[threadIdx.x] - s;  // exclusive prefix of this thread's span
   for (int b = b0; b < b1; ++b) {
-    run += c[b];
-    c[b] = run;
+    run += at(b);
+    at(b) = run;
   }
 }
 
@@ -326,24 +336,30 @@ static int blocks_for(int64_t N) {
 template <typename T>
 static void launch_sweep_generic(const void* grid, const Shape& s, bool levels, int bins,
                                  const HardHeader* hdr, const float* table,
-                                 unsigned long long* hist, hipStream_t st, bool top) {
+                                 unsigned long long* hist, hipStream_t st, int conv) {
   dim3 g(blocks_for(s.N), (unsigned)s.batch);
   size_t lds = (size_t)bins * sizeof(int);
   const T* p = static_cast<const T*>(grid);
-#define ECC_GO(ND, LV, TP)                                                                        \
-  hipLaunchKernelGGL((sweep_generic_kernel<T, ND, LV, TP>), g, dim3(kBlock), lds, st, p, s.D, s.H, \
+#define ECC_GO(ND, LV, CV)                                                                        \
+  hipLaunchKernelGGL((sweep_generic_kernel<T, ND, LV, CV>), g, dim3(kBlock), lds, st, p, s.D, s.H, \
                      s.W, s.N, bins, hdr, table, hist)
-#define ECC_TOP(ND, LV) \
-  if (top) ECC_GO(ND, LV, true); else ECC_GO(ND, LV, false)
-  if (s.ndim == 2) { if (levels) { ECC_TOP(2, true); } else { ECC_TOP(2, false); } }
-  else             { if (levels) { ECC_TOP(3, true); } else { ECC_TOP(3, false); } }
-#undef ECC_TOP
+#define ECC_CONV(ND, LV)                 \
+  switch (conv) {                        \
+    case 1: ECC_GO(ND, LV, 1); break;    \
+    case 2: ECC_GO(ND, LV, 2); break;    \
+    case 3: ECC_GO(ND, LV, 3); break;    \
+    default: ECC_GO(ND, LV, 0); break;   \
+  }
+  if (s.ndim == 2) { if (levels) { ECC_CONV(2, true); } else { ECC_CONV(2, false); } }
+  else             { if (levels) { ECC_CONV(3, true); } else { ECC_CONV(3, false); } }
+#undef ECC_CONV
 #undef ECC_GO
 }
 
 hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
                        double lo, double hi, int64_t* curve, void* ws, hipStream_t st, const DirArgs* dir,
-                       bool top) {
+                       int conv) {
+  const int super = (conv & kConvSuper) ? 1 : 0;
   HardHeader* hdr = static_cast<HardHeader*>(ws);
   char* wsb = static_cast<char*>(ws);
   float* table = reinterpret_cast<float*>(wsb + kTableOffset);
@@ -391,8 +407,8 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)ib), dim3(256), 0, st, hdr, la.counters,
                        (int)(s.batch * la.nsub), hist, hist_len);
     profile_mark(st, false);
-    if (fast2d) launch_sweep2d_list(gf, s, la, st, dir, top);
-    else launch_sweep3d_list(gf, s, la, st, dir, top);
+    if (fast2d) launch_sweep2d_list(gf, s, la, st, dir, conv);
+    else launch_sweep3d_list(gf, s, la, st, dir, conv);
     profile_mark(st, true);
     // few blocks per item merge into the global histogram (same-address atomics), but
     // enough of them in all to keep the list reads in flight
@@ -400,11 +416,11 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     nblk = nblk < 32 ? 32 : (nblk > 256 ? 256 : nblk);
     if (nblk > (int64_t)la.nsub) nblk = la.nsub;
     hipLaunchKernelGGL(binlist_kernel, dim3((unsigned)nblk, (unsigned)s.batch), dim3(kBlock),
-                       (size_t)bins * 2 * sizeof(int), st, la, table, bins, hist);
-    if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir, top);
-    else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir, top);
+                       (size_t)bins * 2 * sizeof(int), st, la, table, bins, hist, super);
+    if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir, conv);
+    else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir, conv);
     hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,
-                       reinterpret_cast<long long*>(curve), bins);
+                       reinterpret_cast<long long*>(curve), bins, super);
     return hipGetLastError();
   }
 
@@ -417,21 +433,21 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
                        static_cast<const float*>(grid), total, hdr);
   }
   hipLaunchKernelGGL(prepare_kernel, dim3(prep_blocks), dim3(kBlock), 0, st, hdr, table, bins,
-                     device_range ? 1 : 0, lo, hi, hist, hist_len);
+                     device_range ? 1 : 0, lo, hi, hist, hist_len, super);
   profile_mark(st, false);
   if (fast2d) {
-    launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir, top);
+    launch_sweep2d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir, conv);
   } else if (fast3d) {
-    launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir, top);
+    launch_sweep3d(grid, s, dtype, levels, bins, hdr, table, hist, st, nullptr, dir, conv);
   } else
   switch (dtype) {
-    case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, top); break;
-    case 1: launch_sweep_generic<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, top); break;
-    default: launch_sweep_generic<float>(grid, s, levels, bins, hdr, table, hist, st, top); break;
+    case 0: launch_sweep_generic<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, conv); break;
+    case 1: launch_sweep_generic<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, conv); break;
+    default: launch_sweep_generic<float>(grid, s, levels, bins, hdr, table, hist, st, conv); break;
   }
   profile_mark(st, true);
   hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st,
-                     reinterpret_cast<long long*>(curve), bins);
+                     reinterpret_cast<long long*>(curve), bins, super);
   return hipGetLastError();
 }
 

@@ -16,12 +16,14 @@ struct Shape {
 };
 
 // ---- hard path ------------------------------------------------------------
+// convention bits (`conv` below): bit 0 top-cell construction (grid points are squares /
+// cubes) instead of the vertex one, bit 1 superlevel sets instead of sublevel sets
+constexpr int kConvTop = 1, kConvSuper = 2;
 size_t hard_workspace_bytes(const Shape& s, int bins);
 struct DirArgs;  // directional launch (tilted field, blockIdx.y over directions x items); null: plain
-// top: top-cell construction (grid points are squares / cubes) instead of the vertex one
 hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
                        double lo, double hi, int64_t* curve, void* ws, hipStream_t st,
-                       const DirArgs* dir = nullptr, bool top = false);
+                       const DirArgs* dir = nullptr, int conv = 0);
 // directional curves; sv: the shape with batch = directions x items, batch: items per direction
 size_t hard_dir_workspace_bytes(const Shape& sv, int bins);
 hipError_t launch_hard_dir(const float* grid, const Shape& sv, const float* u, float alpha, int batch,
@@ -42,17 +44,17 @@ struct ListArgs {
 bool sweep2d_supported(const Shape& s, int bins);
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st, const unsigned* run_if, const DirArgs* dir = nullptr, bool top = false);
+                    hipStream_t st, const unsigned* run_if, const DirArgs* dir = nullptr, int conv = 0);
 void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
-                         const DirArgs* dir = nullptr, bool top = false);
+                         const DirArgs* dir = nullptr, int conv = 0);
 unsigned sweep2d_list_blocks(const Shape& s);  // blocks per item of that launch
 
 bool sweep3d_supported(const Shape& s, int bins);
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st, const unsigned* run_if, const DirArgs* dir = nullptr, bool top = false);
+                    hipStream_t st, const unsigned* run_if, const DirArgs* dir = nullptr, int conv = 0);
 void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
-                         const DirArgs* dir = nullptr, bool top = false);
+                         const DirArgs* dir = nullptr, int conv = 0);
 unsigned sweep3d_list_blocks(const Shape& s);
 
 // ---- sweep-kernel timing (measurement aid) ----------------------------------

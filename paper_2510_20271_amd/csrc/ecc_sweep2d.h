@@ -201,7 +201,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     }
     else if (Tilt::kOn) f = add_rn(f, add_rn(lx[e], mul_rn(tilt.ay, (float)y)));
     else if (sizeof(T) == 4) f += 0.0f;
-    if (EDGE) f = ok[e] ? f : (Tilt::kNeg ? -INFINITY : INFINITY);
+    if (EDGE) f = ok[e] ? f : (Tilt::kTop ? -INFINITY : INFINITY);
     return f;
   };
   auto original = [](float f) -> float { return Tilt::kNeg ? -f : f; };  // the value that is binned
@@ -283,7 +283,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 
   unsigned oN[kNC], oNE[kNC], oNW[kNC];  // bit 0: the row above the first output row
 #pragma unroll
-  for (int e = 0; e < kNC; ++e) oN[e] = oNE[e] = oNW[e] = Tilt::kNeg ? 0 : 1;  // (reversed order: always before p)
+  for (int e = 0; e < kNC; ++e) oN[e] = oNE[e] = oNW[e] = Tilt::kTop ? 0 : 1;  // (reversed order: always before p)
   if (y0 > 0) {
     step();  // warm-up on row y0-1
 #pragma unroll
@@ -316,7 +316,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 #pragma unroll
     for (int e = 0; e < kNC; ++e) {
       if (bottom) {
-        if (Tilt::kNeg) {  // reversed order: what lies outside the grid comes before p
+        if (Tilt::kTop) {  // reversed order: what lies outside the grid comes before p
           wN[e] |= 1u;
           wNE[e] |= 1u;
           wNW[e] |= 1u;

@@ -9,7 +9,8 @@ namespace ecc {
 // which is merged into the global one at the end.  run_if (may be null): the
 // kernel does nothing unless *run_if != 0 (fallback of the single-pass mode).
 // MODE (SweepMode): kTilted is a directional launch (blockIdx.y = direction * batch + item,
-// tilted field), kTopCells the top-cell construction.
+// tilted field), kTopCells the top-cell construction, kSuper / kTopSuper the two
+// constructions on superlevel sets.
 template <typename T, bool LEVELS, bool TLDS, int MODE>
 __global__ __launch_bounds__(256) void sweep2d_kernel(
     const T* __restrict__ grid, int H, int W, int64_t N, int bins, int nstrip, int nseg, int rows_per_seg,
@@ -28,7 +29,7 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
     if (TLDS) ltable[b] = table[b];
   }
   __syncthreads();
-  WaveQueue<HistSink<LEVELS>> queue;
+  WaveQueue<HistSink<LEVELS, mode_is_super(MODE)>> queue;
   queue.buf = qbuf;
   queue.count = 0;
   queue.sink.lhist = lhist;
@@ -41,12 +42,9 @@ __global__ __launch_bounds__(256) void sweep2d_kernel(
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
     sweep2d_wave<T>(grid + (int64_t)item * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
                     load_tilt(dir, d));
-  } else if constexpr (MODE == kTopCells) {
-    sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
-                    TopCells());
   } else {
     sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
-                    NoTilt());
+                    typename ModeTransform<MODE>::type());
   }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
@@ -80,12 +78,9 @@ __global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
     sweep2d_wave<T>(grid + (int64_t)item * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
                     load_tilt(dir, d));
-  } else if constexpr (MODE == kTopCells) {
-    sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
-                    TopCells());
   } else {
     sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
-                    NoTilt());
+                    typename ModeTransform<MODE>::type());
   }
   range.commit(la.hdr);
 }
@@ -95,7 +90,7 @@ constexpr size_t kRingBytes2d = ring_bytes2d<float2>();
 template <typename T>
 static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
                        const float* table, unsigned long long* hist, hipStream_t st,
-                       const unsigned* run_if, const DirArgs* dir, bool top) {
+                       const unsigned* run_if, const DirArgs* dir, int conv) {
   const Plan2d pl = plan2d<T>(s);
   const bool tlds = !levels && (size_t)bins * 8 + kRingBytes2d <= 64 * 1024;
   const size_t lds = kRingBytes2d + (size_t)bins * (tlds ? 8 : 4);
@@ -112,31 +107,40 @@ static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, 
       return;
     }
   }
-  if (top) {
-    if (levels) ECC_GO(true, false, kTopCells);
-    else if (tlds) ECC_GO(false, true, kTopCells);
-    else ECC_GO(false, false, kTopCells);
-    return;
+#define ECC_MODE(M)                       \
+  do {                                    \
+    if (levels) ECC_GO(true, false, M);   \
+    else if (tlds) ECC_GO(false, true, M); \
+    else ECC_GO(false, false, M);         \
+  } while (0)
+  switch (mode_of_conv(conv)) {
+    case kTopCells: ECC_MODE(kTopCells); break;
+    case kSuper: ECC_MODE(kSuper); break;
+    case kTopSuper: ECC_MODE(kTopSuper); break;
+    default: ECC_MODE(kPlain); break;
   }
-  if (levels) ECC_GO(true, false, kPlain);
-  else if (tlds) ECC_GO(false, true, kPlain);
-  else ECC_GO(false, false, kPlain);
+#undef ECC_MODE
 #undef ECC_GO
 }
 
 void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
-                         const DirArgs* dir, bool top) {
+                         const DirArgs* dir, int conv) {
   const Plan2d pl = plan2d<float>(s);
   const DirArgs none = {nullptr, 0.f, 1, 2};
-  if (dir)
-    hipLaunchKernelGGL((sweep2d_list_kernel<float, kTilted>), pl.grid, dim3(256), kRingBytes2d, st, grid,
-                       (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la, *dir);
-  else if (top)
-    hipLaunchKernelGGL((sweep2d_list_kernel<float, kTopCells>), pl.grid, dim3(256), kRingBytes2d, st, grid,
-                       (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la, none);
-  else
-    hipLaunchKernelGGL((sweep2d_list_kernel<float, kPlain>), pl.grid, dim3(256), kRingBytes2d, st, grid,
-                       (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la, none);
+#define ECC_LIST(M, DIR)                                                                                 \
+  hipLaunchKernelGGL((sweep2d_list_kernel<float, M>), pl.grid, dim3(256), kRingBytes2d, st, grid, (int)s.H, \
+                     (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la, DIR)
+  if (dir) {
+    ECC_LIST(kTilted, *dir);
+    return;
+  }
+  switch (mode_of_conv(conv)) {
+    case kTopCells: ECC_LIST(kTopCells, none); break;
+    case kSuper: ECC_LIST(kSuper, none); break;
+    case kTopSuper: ECC_LIST(kTopSuper, none); break;
+    default: ECC_LIST(kPlain, none); break;
+  }
+#undef ECC_LIST
 }
 
 unsigned sweep2d_list_blocks(const Shape& s) { return plan2d<float>(s).grid.x; }
@@ -148,11 +152,11 @@ bool sweep2d_supported(const Shape& s, int bins) {
 
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st, const unsigned* run_if, const DirArgs* dir, bool top) {
+                    hipStream_t st, const unsigned* run_if, const DirArgs* dir, int conv) {
   switch (dtype) {
-    case 0: launch2d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, top); break;
-    case 1: launch2d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, top); break;
-    default: launch2d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir, top); break;
+    case 0: launch2d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 1: launch2d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    default: launch2d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir, conv); break;
   }
 }
 

@@ -314,7 +314,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
       }
       else if (TiltT::kOn) f = add_rn(f, add_rn(txy[j], tz));
       else if (sizeof(T) == 4) f += 0.0f;  // -0 -> +0 so that equal values differ by +0
-      if (SAFE) f = (inb && rok[j]) ? f : (TiltT::kNeg ? -INFINITY : INFINITY);
+      if (SAFE) f = (inb && rok[j]) ? f : (TiltT::kTop ? -INFINITY : INFINITY);
       dst[j] = f;
     }
   };
@@ -344,7 +344,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 #pragma unroll
   for (int jc = 0; jc <= R + 1; ++jc)
 #pragma unroll
-    for (int q = 0; q < 9; ++q) w.U[jc][q] = TiltT::kNeg ? 0u : 1u;  // below the grid: "never before p" after complement (reversed order: always)
+    for (int q = 0; q < 9; ++q) w.U[jc][q] = TiltT::kTop ? 0u : 1u;  // below the grid: "never before p" after complement (reversed order: always)
   if (z0 > 0) {
     // pa = plane z0-1, rawx = plane z0
     fix(pb, rawx);
@@ -430,7 +430,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 #pragma unroll
       for (int jc = 1; jc <= R; ++jc)
 #pragma unroll
-        for (int q = 0; q < 9; ++q) w.U[jc][q] = TiltT::kNeg ? (w.U[jc][q] | 1u) : (w.U[jc][q] & ~1u);
+        for (int q = 0; q < 9; ++q) w.U[jc][q] = TiltT::kTop ? (w.U[jc][q] | 1u) : (w.U[jc][q] & ~1u);
     }
     // plane z+i sits at bit n-1-i of every word; the plane below the chunk at bit n of U
     const unsigned planes = (n >= 32) ? 0xffffffffu : ((1u << n) - 1u);
@@ -490,7 +490,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
                             (((sl.d3 >> b) & 1u) << 3);
         const int c = (int)(cu ^ 8u) - 8;
         // top cells: (-1)^3 times the vertex coefficient
-        queue.template push<TiltT::kOn>(active, inpl, (unsigned)(z - z0 + n - 1 - b), TiltT::kNeg ? -c : c, txy[j],
+        queue.template push<TiltT::kOn>(active, inpl, (unsigned)(z - z0 + n - 1 - b), TiltT::kTop ? -c : c, txy[j],
                                         fetch);
       }
     }
@@ -564,7 +564,7 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
     if (TLDS) ltable[b] = table[b];
   }
   __syncthreads();
-  s3::TubeQueue<HistSink<LEVELS>> queue;
+  s3::TubeQueue<HistSink<LEVELS, mode_is_super(MODE)>> queue;
   queue.buf = qbuf;
   queue.tbuf = tbuf;
   queue.count = 0;
@@ -578,12 +578,9 @@ __global__ __launch_bounds__(256) void sweep3d_kernel(
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
     sweep3d_wave<T, R>(grid + (int64_t)item * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg, queue, xch,
                        range, load_tilt(dir, d));
-  } else if constexpr (MODE == kTopCells) {
-    sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
-                       queue, xch, range, TopCells());
   } else {
     sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
-                       queue, xch, range, NoTilt());
+                       queue, xch, range, typename ModeTransform<MODE>::type());
   }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
@@ -615,12 +612,9 @@ __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
     sweep3d_wave<T, R>(grid + (int64_t)item * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg, queue, xch,
                        range, load_tilt(dir, d));
-  } else if constexpr (MODE == kTopCells) {
-    sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
-                       queue, xch, range, TopCells());
   } else {
     sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
-                       queue, xch, range, NoTilt());
+                       queue, xch, range, typename ModeTransform<MODE>::type());
   }
   range.commit(la.hdr);
 }
@@ -665,7 +659,7 @@ constexpr size_t kFixedLds3d = (size_t)4 * kQueueCap * (sizeof(uint2) + sizeof(f
 template <typename T>
 static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
                        const float* table, unsigned long long* hist, hipStream_t st,
-                       const unsigned* run_if, const DirArgs* dir, bool top) {
+                       const unsigned* run_if, const DirArgs* dir, int conv) {
   constexpr int R = kRows3d;
   const Plan3d pl = plan3d<T>(s);
   const bool tlds = !levels && (size_t)bins * 8 + kFixedLds3d <= 60 * 1024;
@@ -683,34 +677,41 @@ static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, 
       return;
     }
   }
-  if (top) {
-    if (levels) ECC_GO(true, false, kTopCells);
-    else if (tlds) ECC_GO(false, true, kTopCells);
-    else ECC_GO(false, false, kTopCells);
-    return;
+#define ECC_MODE(M)                       \
+  do {                                    \
+    if (levels) ECC_GO(true, false, M);   \
+    else if (tlds) ECC_GO(false, true, M); \
+    else ECC_GO(false, false, M);         \
+  } while (0)
+  switch (mode_of_conv(conv)) {
+    case kTopCells: ECC_MODE(kTopCells); break;
+    case kSuper: ECC_MODE(kSuper); break;
+    case kTopSuper: ECC_MODE(kTopSuper); break;
+    default: ECC_MODE(kPlain); break;
   }
-  if (levels) ECC_GO(true, false, kPlain);
-  else if (tlds) ECC_GO(false, true, kPlain);
-  else ECC_GO(false, false, kPlain);
+#undef ECC_MODE
 #undef ECC_GO
 }
 
 void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
-                         const DirArgs* dir, bool top) {
+                         const DirArgs* dir, int conv) {
   const Plan3d pl = plan3d<float>(s);
   const DirArgs none = {nullptr, 0.f, 1, 3};
-  if (dir)
-    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, kTilted>), pl.grid, dim3(256), kFixedLds3d, st,
-                       grid, (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg,
-                       pl.planes_per_seg, la, *dir);
-  else if (top)
-    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, kTopCells>), pl.grid, dim3(256), kFixedLds3d, st,
-                       grid, (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg,
-                       pl.planes_per_seg, la, none);
-  else
-    hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, kPlain>), pl.grid, dim3(256), kFixedLds3d, st,
-                       grid, (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg,
-                       pl.planes_per_seg, la, none);
+#define ECC_LIST(M, DIR)                                                                                  \
+  hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, M>), pl.grid, dim3(256), kFixedLds3d, st, grid,   \
+                     (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg, la, \
+                     DIR)
+  if (dir) {
+    ECC_LIST(kTilted, *dir);
+    return;
+  }
+  switch (mode_of_conv(conv)) {
+    case kTopCells: ECC_LIST(kTopCells, none); break;
+    case kSuper: ECC_LIST(kSuper, none); break;
+    case kTopSuper: ECC_LIST(kTopSuper, none); break;
+    default: ECC_LIST(kPlain, none); break;
+  }
+#undef ECC_LIST
 }
 
 unsigned sweep3d_list_blocks(const Shape& s) { return plan3d<float>(s).grid.x; }
@@ -724,11 +725,11 @@ bool sweep3d_supported(const Shape& s, int bins) {
 
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
-                    hipStream_t st, const unsigned* run_if, const DirArgs* dir, bool top) {
+                    hipStream_t st, const unsigned* run_if, const DirArgs* dir, int conv) {
   switch (dtype) {
-    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, top); break;
-    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, top); break;
-    default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir, top); break;
+    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir, conv); break;
   }
 }
 

@@ -81,6 +81,23 @@ def test_hard_rejects_bad_arguments(kw, status, word):
     assert word in lib.ecc_last_error().decode()
 
 
+@pytest.mark.parametrize("kw,status,word", [
+    (dict(construction=2), INVALID, "construction"),
+    (dict(filtration=-1), INVALID, "filtration"),
+    (dict(bins=0), INVALID, "bins"),
+    (dict(dtype=7), INVALID, "dtype"),
+    (dict(ws_bytes=8), WORKSPACE, "workspace"),
+])
+def test_hard_ex_rejects_bad_arguments(kw, status, word):
+    lib = _lib.load()
+    a = dict(construction=1, filtration=1, bins=8, dtype=0, ws_bytes=1 << 20)
+    a.update(kw)
+    rc = lib.ecc_hard_ex(FAKE, 2, _dims(4, 4), 1, a["dtype"], a["construction"], a["filtration"], a["bins"], None,
+                         FAKE, FAKE, a["ws_bytes"], None)
+    assert rc == status
+    assert word in lib.ecc_last_error().decode()
+
+
 def test_hard_rejects_null_dims():
     lib = _lib.load()
     rc = lib.ecc_hard(FAKE, 2, None, 1, 0, 8, None, FAKE, FAKE, 1 << 20, None)

@@ -1,5 +1,5 @@
 """Randomised parity sweep: random shapes, dtypes, batch sizes, bin counts and threshold modes
-through every hard entry point, each compared bit for bit with the CPU oracle.  The cases are
+through every hard entry point and convention, each compared bit for bit with the CPU oracle.  The cases are
 drawn from a fixed seed, so a failure names its case."""
 import numpy as np
 import pytest
@@ -56,6 +56,14 @@ def test_random_case(seed):
     np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, t), err_msg=info)
     got = host(api.ecc_hard_top(dev(X), nd, bins, range=rng_arg))
     np.testing.assert_array_equal(got, O.ecc_top_batch(X, t), err_msg="top " + info)
+    # superlevel sets, both constructions: lower edges of the same bins
+    if mode == "range" or is_float:
+        ts = O.thresholds_lower(t, lo)
+    else:
+        ts = O.thresholds_levels_super(bins)
+    for top in (False, True):
+        got = host(api.ecc_hard(dev(X), nd, bins, range=rng_arg, top=top, superlevel=True))
+        np.testing.assert_array_equal(got, O.ecc_super_batch(X, ts, top), err_msg=f"super top={top} " + info)
     if is_float:
         U = rng.standard_normal((2, nd)).astype(np.float32)
         alpha = float(rng.choice([0.0, 0.01, 0.5]))
