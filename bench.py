@@ -7,10 +7,13 @@ smoothed Gaussian random fields, 1024 equal-width bins over the batch-global
 [min, max] computed on the device.  Inputs are resident in HBM before the
 timed region.  The same run also times, as extra fields of the one JSON line,
 the 3D 512^3 float32 volume (C4), the hard path with the range supplied, the
-two integer workloads (C1, C3), soft forward + backward over the 32 x 512^2
+two integer workloads (C1, C3), directional curves (16 directions over one
+4096^2 field, ecc_hard_dir), soft forward + backward over the 32 x 512^2
 batch (C5), and the CPU oracle on the host cores (a baseline, not the target).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--quick]
+    python bench.py --only c2|c2r|c4|c5|dir|calib   one workload (profiling runs)
+    python bench.py --sweep                         the grid sizes of the paper's Tables 1-2
 """
 from __future__ import annotations
 
