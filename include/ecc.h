@@ -136,6 +136,26 @@ int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Soft ECC with the coefficient of the TILTED field: Eq. 6 and Eq. 8-10 exactly
+ * as in ecc_soft_fwd / ecc_soft_bwd, except that c(p) is the coefficient (Eq. 3)
+ * of Y(p) = X(p) + alpha <u,p> instead of the coefficient of X.  Y is formed in
+ * float32 as ecc_hard_dir forms it (see there), so for lambda -> infinity
+ * chi[i][j] tends to the directional hard curve of item i at tau_j -- with the
+ * coefficient of X (the paper's Eq. 6 read literally) it tends to
+ * sum_p c_X(p) 1[Y(p) <= tau_j], which is not an Euler characteristic.  The
+ * sigmoid argument and the derivatives are unchanged (c is still a constant).
+ * Arguments, outputs, workspace (ecc_workspace_bytes) and errors: as the two
+ * entry points above.
+ */
+int ecc_soft_fwd_tilted(const float* grid, int ndim, const int64_t* dims, int64_t batch,
+                        const float* u, float alpha, const float* tau, int T, float lambda,
+                        float* chi, void* workspace, size_t workspace_bytes, void* hip_stream);
+int ecc_soft_bwd_tilted(const float* grid, int ndim, const int64_t* dims, int64_t batch,
+                        const float* u, float alpha, const float* tau, int T, float lambda,
+                        const float* grad_chi, float* grad_X, float* dchi_dtau, float* dchi_du,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Hard ECC of the top-cell construction (the Background section leaves the
  * construction of the cubical complex open): the grid points are the
  * top-dimensional cells -- pixels are closed unit squares, voxels closed unit

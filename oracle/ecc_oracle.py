@@ -408,6 +408,12 @@ def soft_bwd(X, u, alpha, tau, lam, g=None, c=None):
     return grad_X.reshape(np.asarray(X).shape), dtau, du
 
 
+def coeff_tilted(X, u, alpha) -> np.ndarray:
+    """c(p) of the tilted field (the soft curve then tends to the directional hard curve
+    as lambda grows; with the coefficient of X itself it tends to no Euler characteristic)."""
+    return coeff(tilt_field(X, u, alpha))
+
+
 def soft_fwd_batch(Xb, u, alpha, tau, lam):
     return np.stack([soft_fwd(x, u, alpha, tau, lam) for x in Xb])
 

@@ -34,6 +34,12 @@ SIGNATURES = {
     "ecc_soft_bwd": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp,
                                     ctypes.c_float, c_vp, ctypes.c_int, ctypes.c_float, c_vp, c_vp,
                                     c_vp, c_vp, c_vp, ctypes.c_size_t, c_vp]),
+    "ecc_soft_fwd_tilted": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp,
+                                           ctypes.c_float, c_vp, ctypes.c_int, ctypes.c_float, c_vp, c_vp,
+                                           ctypes.c_size_t, c_vp]),
+    "ecc_soft_bwd_tilted": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp,
+                                           ctypes.c_float, c_vp, ctypes.c_int, ctypes.c_float, c_vp, c_vp,
+                                           c_vp, c_vp, c_vp, ctypes.c_size_t, c_vp]),
     "ecc_workspace_bytes_dir": (ctypes.c_size_t, [ctypes.c_int, ctypes.POINTER(c_i64), c_i64, ctypes.c_int,
                                                   ctypes.c_int]),
     "ecc_hard_dir": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp, ctypes.c_int,

@@ -153,21 +153,22 @@ def ecc_coeff(grid: torch.Tensor, ndim: int, c_out=None):
     return c_out
 
 
-def ecc_soft_fwd(grid, ndim, u, alpha, tau, lam, chi=None, workspace=None):
+def ecc_soft_fwd(grid, ndim, u, alpha, tau, lam, chi=None, workspace=None, tilted_c=False):
+    """tilted_c=True: c(p) of the tilted field X + alpha <u,p> (ecc_soft_fwd_tilted)."""
     _need_device(grid, u, tau, chi, workspace)
     batch, item = grid.shape[0], tuple(grid.shape[1:])
     T = tau.numel()
     if chi is None:
         chi = torch.empty((batch, T), dtype=torch.float32, device=grid.device)
     workspace = _workspace(item, batch, max(T, 1), grid.device, workspace)
-    _check(_lib.load().ecc_soft_fwd(_ptr(grid), ndim, _dims(item), batch, _ptr(u), float(alpha),
-                                    _ptr(tau), T, float(lam), _ptr(chi), _ptr(workspace),
-                                    workspace.numel(), _stream()))
+    fn = _lib.load().ecc_soft_fwd_tilted if tilted_c else _lib.load().ecc_soft_fwd
+    _check(fn(_ptr(grid), ndim, _dims(item), batch, _ptr(u), float(alpha), _ptr(tau), T, float(lam), _ptr(chi),
+              _ptr(workspace), workspace.numel(), _stream()))
     return chi
 
 
 def ecc_soft_bwd(grid, ndim, u, alpha, tau, lam, grad_chi=None, grad_X=None, dchi_dtau=None,
-                 dchi_du=None, workspace=None):
+                 dchi_du=None, workspace=None, tilted_c=False):
     """Returns (grad_X [batch,*item], dchi_dtau [batch,T], dchi_du [batch,T,ndim])."""
     _need_device(grid, u, tau, grad_chi, grad_X, dchi_dtau, dchi_du, workspace)
     batch, item = grid.shape[0], tuple(grid.shape[1:])
@@ -180,10 +181,10 @@ def ecc_soft_bwd(grid, ndim, u, alpha, tau, lam, grad_chi=None, grad_X=None, dch
     if dchi_du is None:
         dchi_du = torch.empty((batch, T, ndim), dtype=torch.float32, device=dev)
     workspace = _workspace(item, batch, max(T, 1), dev, workspace)
-    _check(_lib.load().ecc_soft_bwd(_ptr(grid), ndim, _dims(item), batch, _ptr(u), float(alpha),
-                                    _ptr(tau), T, float(lam), _ptr(grad_chi), _ptr(grad_X),
-                                    _ptr(dchi_dtau), _ptr(dchi_du), _ptr(workspace),
-                                    workspace.numel(), _stream()))
+    fn = _lib.load().ecc_soft_bwd_tilted if tilted_c else _lib.load().ecc_soft_bwd
+    _check(fn(_ptr(grid), ndim, _dims(item), batch, _ptr(u), float(alpha), _ptr(tau), T, float(lam),
+              _ptr(grad_chi), _ptr(grad_X), _ptr(dchi_dtau), _ptr(dchi_du), _ptr(workspace),
+              workspace.numel(), _stream()))
     return grad_X, dchi_dtau, dchi_du
 
 

@@ -221,9 +221,9 @@ int ecc_coeff(const void* grid, int ndim, const int64_t* dims, int64_t batch, in
       ecc::launch_coeff(grid, s, dtype, c_out, static_cast<hipStream_t>(hip_stream)), "ecc_coeff");
 }
 
-int ecc_soft_fwd(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
-                 float alpha, const float* tau, int T, float lambda, float* chi, void* workspace,
-                 size_t workspace_bytes, void* hip_stream) {
+static int soft_fwd_common(const char* who, bool tiltc, const float* grid, int ndim, const int64_t* dims,
+                           int64_t batch, const float* u, float alpha, const float* tau, int T, float lambda,
+                           float* chi, void* workspace, size_t workspace_bytes, void* hip_stream) {
   ecc::Shape s;
   int rc = make_shape(ndim, dims, batch, &s);
   if (rc != ECC_OK) return rc;
@@ -232,14 +232,14 @@ int ecc_soft_fwd(const float* grid, int ndim, const int64_t* dims, int64_t batch
   if ((rc = check_workspace(workspace, workspace_bytes, ecc::soft_workspace_bytes(s, T))) != ECC_OK)
     return rc;
   return device_status(ecc::launch_soft_fwd(grid, s, u, alpha, tau, T, lambda, chi, workspace,
-                                            static_cast<hipStream_t>(hip_stream)),
-                       "ecc_soft_fwd");
+                                            static_cast<hipStream_t>(hip_stream), tiltc),
+                       who);
 }
 
-int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
-                 float alpha, const float* tau, int T, float lambda, const float* grad_chi,
-                 float* grad_X, float* dchi_dtau, float* dchi_du, void* workspace,
-                 size_t workspace_bytes, void* hip_stream) {
+static int soft_bwd_common(const char* who, bool tiltc, const float* grid, int ndim, const int64_t* dims,
+                           int64_t batch, const float* u, float alpha, const float* tau, int T, float lambda,
+                           const float* grad_chi, float* grad_X, float* dchi_dtau, float* dchi_du,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
   ecc::Shape s;
   int rc = make_shape(ndim, dims, batch, &s);
   if (rc != ECC_OK) return rc;
@@ -250,8 +250,38 @@ int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch
     return rc;
   return device_status(
       ecc::launch_soft_bwd(grid, s, u, alpha, tau, T, lambda, grad_chi, grad_X, dchi_dtau, dchi_du,
-                           workspace, static_cast<hipStream_t>(hip_stream)),
-      "ecc_soft_bwd");
+                           workspace, static_cast<hipStream_t>(hip_stream), tiltc),
+      who);
+}
+
+int ecc_soft_fwd(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
+                 float alpha, const float* tau, int T, float lambda, float* chi, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  return soft_fwd_common("ecc_soft_fwd", false, grid, ndim, dims, batch, u, alpha, tau, T, lambda, chi,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
+                 float alpha, const float* tau, int T, float lambda, const float* grad_chi,
+                 float* grad_X, float* dchi_dtau, float* dchi_du, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  return soft_bwd_common("ecc_soft_bwd", false, grid, ndim, dims, batch, u, alpha, tau, T, lambda, grad_chi,
+                         grad_X, dchi_dtau, dchi_du, workspace, workspace_bytes, hip_stream);
+}
+
+int ecc_soft_fwd_tilted(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
+                        float alpha, const float* tau, int T, float lambda, float* chi, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  return soft_fwd_common("ecc_soft_fwd_tilted", true, grid, ndim, dims, batch, u, alpha, tau, T, lambda, chi,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+int ecc_soft_bwd_tilted(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
+                        float alpha, const float* tau, int T, float lambda, const float* grad_chi,
+                        float* grad_X, float* dchi_dtau, float* dchi_du, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  return soft_bwd_common("ecc_soft_bwd_tilted", true, grid, ndim, dims, batch, u, alpha, tau, T, lambda,
+                         grad_chi, grad_X, dchi_dtau, dchi_du, workspace, workspace_bytes, hip_stream);
 }
 
 int ecc_profile_begin(int max_launches) {

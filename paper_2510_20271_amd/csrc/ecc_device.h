@@ -54,11 +54,11 @@ __device__ __forceinline__ int coeff_3d(unsigned a, unsigned up, bool up0, unsig
 // sign (-1)^d the caller applies, the top-cell construction (see TopCells below);
 // REV alone the vertex construction of superlevel sets; OUTFIRST alone the top-cell
 // construction of superlevel sets.
-template <typename T, int ND, bool OUTFIRST = false, bool REV = false>
-__device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int64_t H, int64_t W,
-                                        int64_t z, int64_t y, int64_t x) {
-  const int64_t ip = (z * H + y) * W + x;
-  const T vp = g[ip];
+// The field is given by value(index, z, y, x), called for in-grid vertices only.
+template <int ND, bool OUTFIRST, bool REV, typename F>
+__device__ __forceinline__ int coeff_of(const F& value, int64_t D, int64_t H, int64_t W, int64_t z, int64_t y,
+                                        int64_t x) {
+  const auto vp = value((z * H + y) * W + x, z, y, x);
   unsigned ring[3] = {0u, 0u, 0u};
   bool centre[3] = {false, false, false};
   constexpr int z0 = (ND == 3) ? -1 : 0, z1 = (ND == 3) ? 1 : 0;
@@ -72,7 +72,7 @@ __device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int6
         const int64_t qz = z + dz, qy = y + dy, qx = x + dx;
         bool b = OUTFIRST;
         if (qz >= 0 && qz < D && qy >= 0 && qy < H && qx >= 0 && qx < W) {
-          const T vq = g[(qz * H + qy) * W + qx];
+          const auto vq = value((qz * H + qy) * W + qx, qz, qy, qx);
           const bool later = (dz > 0) || (dz == 0 && (dy > 0 || (dy == 0 && dx > 0)));
           if (REV) b = later ? (vq > vp) : (vq >= vp);
           else b = later ? (vq < vp) : (vq <= vp);
@@ -84,6 +84,11 @@ __device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int6
   }
   if (ND == 2) return coeff_ring(ring[1]);
   return coeff_3d(ring[1], ring[2], centre[2], ring[0], centre[0]);
+}
+template <typename T, int ND, bool OUTFIRST = false, bool REV = false>
+__device__ __forceinline__ int coeff_at(const T* __restrict__ g, int64_t D, int64_t H, int64_t W,
+                                        int64_t z, int64_t y, int64_t x) {
+  return coeff_of<ND, OUTFIRST, REV>([g](int64_t i, int64_t, int64_t, int64_t) { return g[i]; }, D, H, W, z, y, x);
 }
 
 // ---- bins -----------------------------------------------------------------
@@ -231,6 +236,22 @@ __device__ __forceinline__ Tilt load_tilt(const DirArgs& d, int dir) {
   t.ay = mul_rn(d.alpha, d.u[dir * d.ndim + 1]);
   t.az = d.ndim == 3 ? mul_rn(d.alpha, d.u[dir * d.ndim + 2]) : 0.0f;
   return t;
+}
+
+// The tilted field at one vertex, as every sweep forms it.
+template <int ND>
+__device__ __forceinline__ float tilted_value(float v, const Tilt& t, int64_t z, int64_t y, int64_t x) {
+  float tt = add_rn(mul_rn(t.ax, (float)x), mul_rn(t.ay, (float)y));
+  if (ND == 3) tt = add_rn(tt, mul_rn(t.az, (float)z));
+  return add_rn(v, tt);
+}
+// Coefficient of the tilted field at one vertex (read straight from global memory).
+template <int ND>
+__device__ __forceinline__ int coeff_tilted_at(const float* __restrict__ g, const Tilt& t, int64_t D, int64_t H,
+                                               int64_t W, int64_t z, int64_t y, int64_t x) {
+  return coeff_of<ND, false, false>(
+      [g, &t](int64_t i, int64_t qz, int64_t qy, int64_t qx) { return tilted_value<ND>(g[i], t, qz, qy, qx); }, D, H,
+      W, z, y, x);
 }
 
 // ---- critical-vertex queue of a wave ----------------------------------------

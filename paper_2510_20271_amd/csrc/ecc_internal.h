@@ -63,21 +63,23 @@ hipError_t profile_end(float* mean_ms, int* launches);
 void profile_mark(hipStream_t st, bool after);  // no-op unless recording
 
 // ---- soft path ------------------------------------------------------------
+// tiltc: c(p) is the coefficient of the tilted field X + alpha <u,p> (formed as the
+// directional hard curves form it) instead of the coefficient of X
 size_t soft_workspace_bytes(const Shape& s, int T);
 hipError_t launch_soft_fwd(const float* grid, const Shape& s, const float* u, float alpha,
                            const float* tau, int T, float lambda, float* chi, void* ws,
-                           hipStream_t st);
+                           hipStream_t st, bool tiltc = false);
 hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, float alpha,
                            const float* tau, int T, float lambda, const float* g, float* grad_X,
-                           float* dtau, float* du, void* ws, hipStream_t st);
+                           float* dtau, float* du, void* ws, hipStream_t st, bool tiltc = false);
 
 // fused 2D soft path (strip sweep + sigmoid sinks)
 bool soft2d_supported(const Shape& s, int T);
 size_t soft2d_workspace_bytes(const Shape& s, int T);
 void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
-                       int T, float lambda, float* chi, void* ws, hipStream_t st);
+                       int T, float lambda, float* chi, void* ws, hipStream_t st, bool tiltc = false);
 void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
                        int T, float lambda, const float* gup, float* grad_X, float* dtau, float* du,
-                       void* ws, hipStream_t st);
+                       void* ws, hipStream_t st, bool tiltc = false);
 
 }  // namespace ecc

@@ -41,7 +41,9 @@ __device__ __forceinline__ float exp_neg(float z, float kneg) {
 // Fill the list for this block's tile.  Returns the number of entries.  When
 // zero_out != nullptr, vertices with c == 0 get 0 written there.  rel (may be
 // null) receives the coordinates relative to the tile's first vertex.
-template <int ND>
+// TILTC: c(p) is the coefficient of the tilted field (as the directional hard curves
+// form it) instead of the field's own.
+template <int ND, bool TILTC>
 __device__ __forceinline__ int build_list(const float* __restrict__ g, int64_t D, int64_t H,
                                           int64_t W, int64_t N, int64_t tile0,
                                           const float* __restrict__ u, float alpha, SoftList& L,
@@ -50,13 +52,19 @@ __device__ __forceinline__ int build_list(const float* __restrict__ g, int64_t D
   const int tid = threadIdx.x;
   int cs[kPerThread];
   int n = 0;
+  Tilt tilt;
+  if (TILTC) {
+    const DirArgs da = {u, alpha, 1, ND};
+    tilt = load_tilt(da, 0);
+  }
 #pragma unroll
   for (int k = 0; k < kPerThread; ++k) {
     const int64_t i = tile0 + k * kSoftBlock + tid;
     int c = 0;
     if (i < N) {
       const int64_t x = i % W, r = i / W;
-      c = coeff_at<float, ND>(g, D, H, W, r / H, r % H, x);
+      if (TILTC) c = coeff_tilted_at<ND>(g, tilt, D, H, W, r / H, r % H, x);
+      else c = coeff_at<float, ND>(g, D, H, W, r / H, r % H, x);
       if (c == 0 && zero_out) zero_out[i] = 0.0f;
     }
     cs[k] = c;
@@ -107,7 +115,7 @@ __device__ __forceinline__ int build_list(const float* __restrict__ g, int64_t D
 // ---------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------
-template <int ND>
+template <int ND, bool TILTC>
 __global__ __launch_bounds__(kSoftBlock) void soft_fwd_kernel(
     const float* __restrict__ grid, int64_t D, int64_t H, int64_t W, int64_t N,
     const float* __restrict__ u, float alpha, const float* __restrict__ tau, int T, float kneg,
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(kSoftBlock) void soft_fwd_kernel(
   __shared__ int scratch[kSoftBlock / kWave + 1];
   const float* g = grid + (int64_t)blockIdx.y * N;
   const int64_t tile0 = (int64_t)blockIdx.x * kTile;
-  const int cnt = build_list<ND>(g, D, H, W, N, tile0, u, alpha, L, nullptr, nullptr, scratch);
+  const int cnt = build_list<ND, TILTC>(g, D, H, W, N, tile0, u, alpha, L, nullptr, nullptr, scratch);
   float* out = partial + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * T;
   const int tid = threadIdx.x;
   for (int jc = 0; jc < T; jc += kSoftBlock) {
@@ -159,7 +167,7 @@ __global__ void soft_fwd_reduce_kernel(const float* __restrict__ partial, int nt
 // ---------------------------------------------------------------------------
 // backward
 // ---------------------------------------------------------------------------
-template <int ND>
+template <int ND, bool TILTC>
 __global__ __launch_bounds__(kSoftBlock) void soft_bwd_kernel(
     const float* __restrict__ grid, int64_t D, int64_t H, int64_t W, int64_t N,
     const float* __restrict__ u, float alpha, const float* __restrict__ tau, int T, float kneg,
@@ -172,7 +180,7 @@ __global__ __launch_bounds__(kSoftBlock) void soft_bwd_kernel(
   const float* g = grid + (int64_t)blockIdx.y * N;
   const int64_t tile0 = (int64_t)blockIdx.x * kTile;
   float* gx = grad_X ? grad_X + (int64_t)blockIdx.y * N : nullptr;
-  const int cnt = build_list<ND>(g, D, H, W, N, tile0, u, alpha, L, rel, gx, scratch);
+  const int cnt = build_list<ND, TILTC>(g, D, H, W, N, tile0, u, alpha, L, rel, gx, scratch);
   const int tid = threadIdx.x;
 
   if (gx) {  // Eq. 8 contracted with the upstream gradient, one thread per critical vertex
@@ -276,20 +284,20 @@ static float kneg_of(float lambda) { return (float)(-(double)lambda * 1.44269504
 
 hipError_t launch_soft_fwd(const float* grid, const Shape& s, const float* u, float alpha,
                            const float* tau, int T, float lambda, float* chi, void* ws,
-                           hipStream_t st) {
+                           hipStream_t st, bool tiltc) {
   if (use_soft2d(s, T)) {
-    launch_soft2d_fwd(grid, s, u, alpha, tau, T, lambda, chi, ws, st);
+    launch_soft2d_fwd(grid, s, u, alpha, tau, T, lambda, chi, ws, st, tiltc);
     return hipGetLastError();
   }
   float* partial = static_cast<float*>(ws);
   const int ntiles = (int)tiles_of(s);
   dim3 g((unsigned)ntiles, (unsigned)s.batch);
-  if (s.ndim == 2)
-    hipLaunchKernelGGL(soft_fwd_kernel<2>, g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u,
-                       alpha, tau, T, kneg_of(lambda), partial);
-  else
-    hipLaunchKernelGGL(soft_fwd_kernel<3>, g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u,
-                       alpha, tau, T, kneg_of(lambda), partial);
+#define ECC_GO(ND, TC)                                                                                  \
+  hipLaunchKernelGGL((soft_fwd_kernel<ND, TC>), g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u, \
+                     alpha, tau, T, kneg_of(lambda), partial)
+  if (s.ndim == 2) { if (tiltc) ECC_GO(2, true); else ECC_GO(2, false); }
+  else             { if (tiltc) ECC_GO(3, true); else ECC_GO(3, false); }
+#undef ECC_GO
   const int64_t total = s.batch * T;
   hipLaunchKernelGGL(soft_fwd_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                      st, partial, ntiles, T, total, chi);
@@ -298,20 +306,20 @@ hipError_t launch_soft_fwd(const float* grid, const Shape& s, const float* u, fl
 
 hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, float alpha,
                            const float* tau, int T, float lambda, const float* gup, float* grad_X,
-                           float* dtau, float* du, void* ws, hipStream_t st) {
+                           float* dtau, float* du, void* ws, hipStream_t st, bool tiltc) {
   if (use_soft2d(s, T)) {
-    launch_soft2d_bwd(grid, s, u, alpha, tau, T, lambda, gup, grad_X, dtau, du, ws, st);
+    launch_soft2d_bwd(grid, s, u, alpha, tau, T, lambda, gup, grad_X, dtau, du, ws, st, tiltc);
     return hipGetLastError();
   }
   float* partial = (dtau || du) ? static_cast<float*>(ws) : nullptr;
   const int ntiles = (int)tiles_of(s);
   dim3 g((unsigned)ntiles, (unsigned)s.batch);
-  if (s.ndim == 2)
-    hipLaunchKernelGGL(soft_bwd_kernel<2>, g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u,
-                       alpha, tau, T, kneg_of(lambda), lambda, gup, grad_X, partial);
-  else
-    hipLaunchKernelGGL(soft_bwd_kernel<3>, g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u,
-                       alpha, tau, T, kneg_of(lambda), lambda, gup, grad_X, partial);
+#define ECC_GO(ND, TC)                                                                                  \
+  hipLaunchKernelGGL((soft_bwd_kernel<ND, TC>), g, dim3(kSoftBlock), 0, st, grid, s.D, s.H, s.W, s.N, u, \
+                     alpha, tau, T, kneg_of(lambda), lambda, gup, grad_X, partial)
+  if (s.ndim == 2) { if (tiltc) ECC_GO(2, true); else ECC_GO(2, false); }
+  else             { if (tiltc) ECC_GO(3, true); else ECC_GO(3, false); }
+#undef ECC_GO
   if (partial) {
     const int64_t total = s.batch * T;
     hipLaunchKernelGGL(soft_bwd_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,

@@ -44,8 +44,13 @@ struct SoftCommon {
   int T;
   int nt;  // threshold slots in use: ceil(T / 64)
   float kneg;
+  // The sweep ran on the tilted field (c of the tilted field): the value it hands over
+  // is the tilted one in float32; X is read again so that y is formed as always.
+  const float* xsrc;  // this item's grid, or null when the sweep ran on X itself
+  int xW;
   __device__ __forceinline__ Entry make(float v, int c, int col, int row) const {
     Entry e;
+    if (xsrc) v = xsrc[(int64_t)row * xW + col];  // wave-uniform condition
     e.y = (double)v + alpha * (ux * (double)col + uy * (double)row);
     e.c = (float)c;
     e.col = col;
@@ -60,6 +65,8 @@ struct SoftCommon {
     T = T_;
     nt = (T_ + kWave - 1) / kWave;
     kneg = kneg_;
+    xsrc = nullptr;
+    xW = 0;
     const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
     for (int t = 0; t < kSoftTL; ++t) {
@@ -151,6 +158,8 @@ __device__ __forceinline__ void soft_lds(int* smem, float*& ring, SoftEntry*& qb
 }
 
 // partial[(item * units + unit) * T + j]
+// TILTC: the sweep runs on the tilted field, so c(p) is that field's coefficient
+template <bool TILTC>
 __global__ __launch_bounds__(256) void soft2d_fwd_kernel(const float* __restrict__ grid, int H, int W,
                                                          int64_t N, int nstrip, int nseg, int rows_per_seg,
                                                          const float* __restrict__ u, float alpha,
@@ -167,7 +176,16 @@ __global__ __launch_bounds__(256) void soft2d_fwd_kernel(const float* __restrict
 #pragma unroll
   for (int t = 0; t < kSoftTL; ++t) queue.sink.acc[t] = 0.f;
   WaveRange range;
-  sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range, NoTilt());
+  if constexpr (TILTC) {
+    queue.sink.xsrc = grid + (int64_t)blockIdx.y * N;
+    queue.sink.xW = W;
+    const DirArgs da = {u, alpha, 1, 2};
+    sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                        load_tilt(da, 0));
+  } else {
+    sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                        NoTilt());
+  }
   const int unit = blockIdx.x * 4 + (threadIdx.x >> 6), units = nstrip * nseg;
   if (unit < units) {
     float* out = partial + ((int64_t)blockIdx.y * units + unit) * T;
@@ -181,6 +199,7 @@ __global__ __launch_bounds__(256) void soft2d_fwd_kernel(const float* __restrict
 }
 
 // partial[((item * units + unit) * T + j) * 4 + {0: A0, 1: Ax, 2: Ay}]
+template <bool TILTC>
 __global__ __launch_bounds__(256) void soft2d_bwd_kernel(const float* __restrict__ grid, int H, int W,
                                                          int64_t N, int nstrip, int nseg, int rows_per_seg,
                                                          const float* __restrict__ u, float alpha,
@@ -214,7 +233,16 @@ __global__ __launch_bounds__(256) void soft2d_bwd_kernel(const float* __restrict
   s.col0 = (unit % nstrip) * kStripOut - kNC;
   s.row0 = (unit / nstrip) * rows_per_seg;
   WaveRange range;
-  sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range, NoTilt());
+  if constexpr (TILTC) {
+    queue.sink.xsrc = grid + (int64_t)blockIdx.y * N;
+    queue.sink.xW = W;
+    const DirArgs da = {u, alpha, 1, 2};
+    sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                        load_tilt(da, 0));
+  } else {
+    sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                        NoTilt());
+  }
   if (partial && unit < units) {
     float* out = partial + ((int64_t)blockIdx.y * units + unit) * (int64_t)T * 4;
     const int lane = threadIdx.x & (kWave - 1);
@@ -298,23 +326,32 @@ size_t soft2d_workspace_bytes(const Shape& s, int T) {
 }
 
 void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
-                       int T, float lambda, float* chi, void* ws, hipStream_t st) {
+                       int T, float lambda, float* chi, void* ws, hipStream_t st, bool tiltc) {
   const Plan2d pl = plan2d<float>(s);
   float* partial = static_cast<float*>(ws);
-  hipLaunchKernelGGL(soft2d_fwd_kernel, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
-                     pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), partial);
+  if (tiltc)
+    hipLaunchKernelGGL(soft2d_fwd_kernel<true>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
+                       pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), partial);
+  else
+    hipLaunchKernelGGL(soft2d_fwd_kernel<false>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
+                       pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), partial);
   hipLaunchKernelGGL(soft2d_fwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
                      dim3(256), 0, st, partial, pl.nstrip * pl.nseg, T, chi);
 }
 
 void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
                        int T, float lambda, const float* gup, float* grad_X, float* dtau, float* du,
-                       void* ws, hipStream_t st) {
+                       void* ws, hipStream_t st, bool tiltc) {
   const Plan2d pl = plan2d<float>(s);
   float* partial = (dtau || du) ? static_cast<float*>(ws) : nullptr;
-  hipLaunchKernelGGL(soft2d_bwd_kernel, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
-                     pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), lambda, gup,
-                     grad_X, partial);
+  if (tiltc)
+    hipLaunchKernelGGL(soft2d_bwd_kernel<true>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
+                       pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), lambda, gup,
+                       grad_X, partial);
+  else
+    hipLaunchKernelGGL(soft2d_bwd_kernel<false>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
+                       pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), lambda, gup,
+                       grad_X, partial);
   if (partial) {
     hipLaunchKernelGGL(soft2d_bwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
                        dim3(256), 0, st, partial, pl.nstrip * pl.nseg, pl.nstrip, pl.rows_per_seg, T, alpha,

@@ -22,29 +22,32 @@ class SoftECCFunction(torch.autograd.Function):
     """chi[b, j] = sum_p c(p) sigmoid(lambda (tau_j - X_b(p) - alpha <u, p>)), p = (x, y[, z])."""
 
     @staticmethod
-    def forward(ctx, grid, u, tau, alpha: float, lam: float):
+    def forward(ctx, grid, u, tau, alpha: float, lam: float, tilted_c: bool = False):
         ndim = grid.dim() - 1
         grid_c = grid.detach().contiguous().float()
         u_c = u.detach().contiguous().float()
         tau_c = tau.detach().contiguous().float()
         ctx.save_for_backward(grid_c, u_c, tau_c)
-        ctx.alpha, ctx.lam, ctx.ndim = float(alpha), float(lam), ndim
-        return api.ecc_soft_fwd(grid_c, ndim, u_c, alpha, tau_c, lam)
+        ctx.alpha, ctx.lam, ctx.ndim, ctx.tilted_c = float(alpha), float(lam), ndim, bool(tilted_c)
+        return api.ecc_soft_fwd(grid_c, ndim, u_c, alpha, tau_c, lam, tilted_c=ctx.tilted_c)
 
     @staticmethod
     def backward(ctx, grad_chi):
         grid, u, tau = ctx.saved_tensors
         g = grad_chi.contiguous().float()
-        grad_X, dtau, du = api.ecc_soft_bwd(grid, ctx.ndim, u, ctx.alpha, tau, ctx.lam, grad_chi=g)
+        grad_X, dtau, du = api.ecc_soft_bwd(grid, ctx.ndim, u, ctx.alpha, tau, ctx.lam, grad_chi=g,
+                                            tilted_c=ctx.tilted_c)
         grad_grid = grad_X if ctx.needs_input_grad[0] else None
         grad_u = torch.einsum("bj,bjd->d", g, du) if ctx.needs_input_grad[1] else None
         grad_tau = (g * dtau).sum(0) if ctx.needs_input_grad[2] else None
-        return grad_grid, grad_u, grad_tau, None, None
+        return grad_grid, grad_u, grad_tau, None, None, None
 
 
-def soft_ecc(grid, u, tau, alpha: float, lam: float):
-    """Functional form: grid [batch, (D,) H, W] float32 on the GPU, u [ndim], tau [T]."""
-    return SoftECCFunction.apply(grid, u, tau, alpha, lam)
+def soft_ecc(grid, u, tau, alpha: float, lam: float, tilted_c: bool = False):
+    """Functional form: grid [batch, (D,) H, W] float32 on the GPU, u [ndim], tau [T].
+    tilted_c: take c(p) from the tilted field X + alpha <u, p> (so that a sharp sigmoid gives
+    the directional hard curve) instead of from X; c stays a constant for the derivatives."""
+    return SoftECCFunction.apply(grid, u, tau, alpha, lam, tilted_c)
 
 
 class SoftECCLayer(torch.nn.Module):
@@ -54,14 +57,16 @@ class SoftECCLayer(torch.nn.Module):
     theta: the direction's angle(s): u = (cos t, sin t) in 2D; in 3D u = (sin p cos t,
            sin p sin t, cos p) with theta = (t, p).  ||u|| = 1 by construction.
     alpha (weight of the tilt) and lam (sharpness of the sigmoid) are fixed.
+    tilted_c: c(p) of the tilted field instead of the field's own (see soft_ecc).
     """
 
     def __init__(self, ndim: int, T: int, tau_min: float, tau_max: float, alpha: float = 0.01,
-                 lam: float = 20.0, theta=None, learn_tau: bool = True, learn_theta: bool = True):
+                 lam: float = 20.0, theta=None, learn_tau: bool = True, learn_theta: bool = True,
+                 tilted_c: bool = False):
         super().__init__()
         if ndim not in (2, 3):
             raise ValueError("ndim must be 2 or 3")
-        self.ndim, self.alpha, self.lam = ndim, float(alpha), float(lam)
+        self.ndim, self.alpha, self.lam, self.tilted_c = ndim, float(alpha), float(lam), bool(tilted_c)
         tau = torch.linspace(float(tau_min), float(tau_max), T, dtype=torch.float32)
         if theta is None:
             theta = [0.3] if ndim == 2 else [0.3, 0.5 * math.pi]
@@ -77,4 +82,4 @@ class SoftECCLayer(torch.nn.Module):
                             torch.cos(t[1])])
 
     def forward(self, grid: torch.Tensor) -> torch.Tensor:
-        return soft_ecc(grid, self.direction(), self.tau, self.alpha, self.lam)
+        return soft_ecc(grid, self.direction(), self.tau, self.alpha, self.lam, self.tilted_c)

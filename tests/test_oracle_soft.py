@@ -166,3 +166,29 @@ def test_batch_wrappers():
         np.testing.assert_array_equal(gx[i], a)
         np.testing.assert_array_equal(dt[i], b)
         np.testing.assert_array_equal(du[i], c)
+
+
+def test_tilted_coefficient_makes_the_sharp_limit_a_directional_hard_curve():
+    rng = np.random.default_rng(12)
+    for shape, u in (((8, 9), [0.6, 0.8]), ((4, 5, 6), [0.48, -0.6, 0.64])):
+        X = rng.integers(0, 4, size=shape).astype(np.float32)      # ties that the tilt breaks its own way
+        u = np.array(u, np.float32)
+        alpha = 0.3
+        Y = O.tilt_field(X, u, alpha).astype(np.float64)
+        ys = np.unique(Y)
+        gaps = np.diff(ys)
+        k = np.argsort(gaps)[-6:]                                   # thresholds in the six widest gaps
+        tau = np.sort((ys[k] + ys[k + 1]) / 2)
+        assert gaps[k].min() > 1e-3
+        hard = O.ecc_hard_dir(X[None], u[None], alpha, tau)[0, 0]
+        soft = O.soft_fwd(X, u, alpha, tau, 1e5, c=O.coeff_tilted(X, u, alpha))
+        assert np.allclose(soft, hard, atol=1e-9)
+    # where the coefficient of X itself goes wrong: a constant grid swept against the x axis.
+    # Every sublevel set of Y = -x that is not empty is a box (chi = 1), but c_X puts its one
+    # nonzero coefficient on the vertex (0, 0), which enters last
+    X = np.zeros((3, 3), np.float32)
+    u = np.array([-1.0, 0.0], np.float32)
+    tau = np.array([-2.5, -1.5, -0.5, 0.5])
+    assert O.ecc_hard_dir(X[None], u[None], 1.0, tau)[0, 0].tolist() == [0, 1, 1, 1]
+    assert np.allclose(O.soft_fwd(X, u, 1.0, tau, 1e4, c=O.coeff_tilted(X, u, 1.0)), [0, 1, 1, 1], atol=1e-9)
+    assert np.allclose(O.soft_fwd(X, u, 1.0, tau, 1e4), [0, 0, 0, 1], atol=1e-9)
