@@ -9,7 +9,7 @@ timed region.  The same run also times, as extra fields of the one JSON line,
 the 3D 512^3 float32 volume (C4), the hard path with the range supplied, the
 two integer workloads (C1, C3), directional curves (16 directions over one
 4096^2 field, ecc_hard_dir), soft forward + backward over the 32 x 512^2
-batch (C5), and the CPU oracle on the host cores (a baseline, not the target).
+batch (C5) and over one 256^3 volume, and the CPU oracle on the host cores (a baseline, not the target).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--quick]
     python bench.py --only c2|c2r|c4|c5|dir|calib   one workload (profiling runs)
@@ -302,6 +302,26 @@ def main():
             dt = time.perf_counter() - t0
             extra["c5_soft"]["cpu_oracle_ms_full_batch_extrapolated"] = round(dt / 2 * X5.shape[0] * 1e3, 1)
             extra["c5_soft"]["cpu_oracle_sample"] = "2 of 32 items, numpy float64"
+
+    # ---------------- soft forward + backward on a volume (fused 3D path) ---------
+    if args.only == "" and not args.quick:
+        V = synth.grf((256, 256, 256), 3.0, 5151)[None]
+        T3 = 64
+        gv = torch.from_numpy(V).cuda()
+        uv = torch.tensor([0.48, -0.6, 0.64], dtype=torch.float32, device="cuda")
+        tv = torch.linspace(float(V.min()), float(V.max()), T3, device="cuda")
+        Gv = torch.from_numpy(synth.upstream_grad(1, T3)).cuda()
+        wsv = torch.empty(api.ecc_workspace_bytes(V.shape[1:], 1, T3), dtype=torch.uint8, device="cuda")
+        gxv = torch.empty_like(gv)
+
+        def stepv():
+            api.ecc_soft_fwd(gv, 3, uv, 0.01, tv, 20.0, workspace=wsv)
+            api.ecc_soft_bwd(gv, 3, uv, 0.01, tv, 20.0, grad_chi=Gv, grad_X=gxv, workspace=wsv)
+        msv = time_steps(stepv, args.steps, args.warmup)
+        extra["soft_3d"] = {"workload": "soft fwd+bwd, one 256^3 float32 GRF sigma=3, T=64, lambda=20, alpha=0.01",
+                            "ms_fwd_plus_bwd": round(msv, 4)}
+        log(f"[bench] soft 3D 256^3: fwd+bwd {msv:.3f} ms")
+        del gv, gxv, wsv
 
     line = {
         "metric": "hard_ecc_throughput", "value": round(value, 2), "unit": "Gvoxel/s", "n_gpus": 1,

@@ -189,15 +189,15 @@ __device__ __forceinline__ float add_rn(float a, float b) {
 // it), so the same stencil serves both constructions; the value that is binned is
 // the original one.
 struct NoTilt {
-  static constexpr bool kOn = false, kNeg = false, kTop = false;
+  static constexpr bool kOn = false, kNeg = false, kTop = false, kRaw = false;
   float ax, ay, az;
 };
 struct Tilt {
-  static constexpr bool kOn = true, kNeg = false, kTop = false;
+  static constexpr bool kOn = true, kNeg = false, kTop = false, kRaw = false;
   float ax, ay, az;
 };
 struct TopCells {
-  static constexpr bool kOn = false, kNeg = true, kTop = true;
+  static constexpr bool kOn = false, kNeg = true, kTop = true, kRaw = false;
   float ax, ay, az;
 };
 // Superlevel sets (X >= tau): the same two constructions on the descending order.
@@ -205,12 +205,17 @@ struct TopCells {
 // construction: the descending order reversed is the field's own order, so the
 // field is swept as it is with the top-cell conventions (kTop only).
 struct Super {
-  static constexpr bool kOn = false, kNeg = true, kTop = false;
+  static constexpr bool kOn = false, kNeg = true, kTop = false, kRaw = false;
   float ax, ay, az;
 };
 struct TopSuper {
-  static constexpr bool kOn = false, kNeg = false, kTop = true;
+  static constexpr bool kOn = false, kNeg = false, kTop = true, kRaw = false;
   float ax, ay, az;
+};
+// Tilted sweep whose consumer wants the untilted value of a critical vertex (the soft
+// path with the tilted field's coefficient): kRaw.
+struct TiltRaw : Tilt {
+  static constexpr bool kRaw = true;
 };
 // kNeg: the field is negated as it is loaded (zeros stay +0).  kTop: what lies
 // outside the grid comes before every vertex, and the coefficient is (-1)^d times
@@ -285,7 +290,7 @@ struct HistSink {  // drain target: the block's LDS histogram
     if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
   }
   // the same with the entries already in registers: lane i < n holds (v, c)
-  __device__ __forceinline__ void take(int n, float v, int c) {
+  __device__ __forceinline__ void take(int n, float v, int c, unsigned = 0, unsigned = 0) {
     const int lane = threadIdx.x & (kWave - 1);
     if (lane >= n) return;
     int b;
@@ -327,7 +332,7 @@ struct ListSink {
       atomicOr(overflow, 1u);
     }
   }
-  __device__ __forceinline__ void take(int n, float v, int c) {
+  __device__ __forceinline__ void take(int n, float v, int c, unsigned = 0, unsigned = 0) {
     const int lane = threadIdx.x & (kWave - 1);
     unsigned base = 0;
     if (lane == 0) base = atomicAdd(counter, (unsigned)n);

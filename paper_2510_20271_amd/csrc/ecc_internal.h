@@ -82,4 +82,13 @@ void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float 
                        int T, float lambda, const float* gup, float* grad_X, float* dtau, float* du,
                        void* ws, hipStream_t st, bool tiltc = false);
 
+// fused 3D soft path (tube sweep + sigmoid sinks)
+bool soft3d_supported(const Shape& s, int T);
+size_t soft3d_workspace_bytes(const Shape& s, int T);
+void launch_soft3d_fwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
+                       int T, float lambda, float* chi, void* ws, hipStream_t st, bool tiltc = false);
+void launch_soft3d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
+                       int T, float lambda, const float* gup, float* grad_X, float* dtau, float* du,
+                       void* ws, hipStream_t st, bool tiltc = false);
+
 }  // namespace ecc

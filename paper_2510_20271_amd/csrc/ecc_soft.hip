@@ -19,6 +19,7 @@
 #include "ecc_device.h"
 #include "ecc_internal.h"
 
+#include <algorithm>
 #include <cstdlib>
 
 namespace ecc {
@@ -270,14 +271,19 @@ static int64_t tiles_of(const Shape& s) { return (s.N + kTile - 1) / kTile; }
 
 size_t soft_workspace_bytes(const Shape& s, int T) {
   const size_t a = (size_t)256 + (size_t)s.batch * (size_t)tiles_of(s) * (size_t)T * 4 * sizeof(float);
-  const size_t b = soft2d_workspace_bytes(s, T);
-  return a > b ? a : b;
+  const size_t b = soft2d_workspace_bytes(s, T), c = soft3d_workspace_bytes(s, T);
+  return std::max(a, std::max(b, c));
 }
 
 // ECC_SOFT_TILES=1 keeps the tile kernels of this file for every shape
 static bool use_soft2d(const Shape& s, int T) {
   static const bool tiles_only = getenv("ECC_SOFT_TILES") != nullptr;
   return !tiles_only && soft2d_supported(s, T);
+}
+
+static bool use_soft3d(const Shape& s, int T) {
+  static const bool tiles_only = getenv("ECC_SOFT_TILES") != nullptr;
+  return !tiles_only && soft3d_supported(s, T);
 }
 
 static float kneg_of(float lambda) { return (float)(-(double)lambda * 1.4426950408889634); }
@@ -287,6 +293,10 @@ hipError_t launch_soft_fwd(const float* grid, const Shape& s, const float* u, fl
                            hipStream_t st, bool tiltc) {
   if (use_soft2d(s, T)) {
     launch_soft2d_fwd(grid, s, u, alpha, tau, T, lambda, chi, ws, st, tiltc);
+    return hipGetLastError();
+  }
+  if (use_soft3d(s, T)) {
+    launch_soft3d_fwd(grid, s, u, alpha, tau, T, lambda, chi, ws, st, tiltc);
     return hipGetLastError();
   }
   float* partial = static_cast<float*>(ws);
@@ -309,6 +319,10 @@ hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, fl
                            float* dtau, float* du, void* ws, hipStream_t st, bool tiltc) {
   if (use_soft2d(s, T)) {
     launch_soft2d_bwd(grid, s, u, alpha, tau, T, lambda, gup, grad_X, dtau, du, ws, st, tiltc);
+    return hipGetLastError();
+  }
+  if (use_soft3d(s, T)) {
+    launch_soft3d_bwd(grid, s, u, alpha, tau, T, lambda, gup, grad_X, dtau, du, ws, st, tiltc);
     return hipGetLastError();
   }
   float* partial = (dtau || du) ? static_cast<float*>(ws) : nullptr;
