@@ -244,45 +244,68 @@ __global__ __launch_bounds__(256) void soft3d_bwd_kernel(const float* __restrict
   }
 }
 
-// Reduction over units: block (x = group of 64 thresholds, y = item); the four
-// waves take units w, w+4, ... in order, then wave 0 adds the four sums in order.
-__global__ __launch_bounds__(256) void soft3d_fwd_reduce_kernel(const float* __restrict__ partial, int units,
-                                                                int T, float* __restrict__ chi) {
-  __shared__ double red[4][kWave];
+// Reduction over units: block (x = group of 64 thresholds, y = item) of 16 waves; wave w
+// adds units w, w+16, ... in order (eight loads in flight at a time: a lone volume has
+// thousands of units and one block per 64 thresholds), then wave 0 adds the 16 sums in order.
+constexpr int kRedWaves = 16, kRedUnroll = 8;
+
+__global__ __launch_bounds__(kRedWaves * kWave) void soft3d_fwd_reduce_kernel(const float* __restrict__ partial,
+                                                                              int units, int T,
+                                                                              float* __restrict__ chi) {
+  __shared__ double red[kRedWaves][kWave];
   const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
   const int j = blockIdx.x * kWave + lane;
   const float* p = partial + (int64_t)blockIdx.y * units * T + j;
   double s = 0.0;
-  if (j < T)
-    for (int q = wv; q < units; q += 4) s += (double)p[(int64_t)q * T];
+  if (j < T) {
+    int q = wv;
+    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
+      float v[kRedUnroll];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) s += (double)v[k];
+    }
+    for (; q < units; q += kRedWaves) s += (double)p[(int64_t)q * T];
+  }
   red[wv][lane] = s;
   __syncthreads();
-  if (wv == 0 && j < T)
-    chi[(int64_t)blockIdx.y * T + j] = (float)(((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane]);
+  if (wv == 0 && j < T) {
+    double r = red[0][lane];
+    for (int w = 1; w < kRedWaves; ++w) r += red[w][lane];
+    chi[(int64_t)blockIdx.y * T + j] = (float)r;
+  }
 }
 
 // dchi_dtau = lambda sum A0;  dchi_du = -alpha lambda sum (origin * A0 + A_xyz)
-__global__ __launch_bounds__(256) void soft3d_bwd_reduce_kernel(const float* __restrict__ partial, int units,
-                                                                int nstrip, int ngroup, int planes_per_seg,
-                                                                int T, float alpha, float lambda,
-                                                                float* __restrict__ dtau,
-                                                                float* __restrict__ du) {
-  __shared__ double red[4][4][kWave];
+__global__ __launch_bounds__(kRedWaves * kWave) void soft3d_bwd_reduce_kernel(
+    const float* __restrict__ partial, int units, int nstrip, int ngroup, int planes_per_seg, int T, float alpha,
+    float lambda, float* __restrict__ dtau, float* __restrict__ du) {
+  __shared__ double red[4][kRedWaves][kWave];
   const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
   const int j = blockIdx.x * kWave + lane;
   const float4* p = reinterpret_cast<const float4*>(partial) + (int64_t)blockIdx.y * units * T + j;
   double s0 = 0.0, sx = 0.0, sy = 0.0, sz = 0.0;
-  if (j < T)
-    for (int q = wv; q < units; q += 4) {
-      const float4 e = p[(int64_t)q * T];
-      int ox, oy, oz;
-      unit_origin(q, nstrip, ngroup, planes_per_seg, kRows3d, ox, oy, oz);
-      const double a0 = (double)e.x;
-      s0 += a0;
-      sx += (double)ox * a0 + (double)e.y;
-      sy += (double)oy * a0 + (double)e.z;
-      sz += (double)oz * a0 + (double)e.w;
+  auto add = [&](int q, const float4& e) {
+    int ox, oy, oz;
+    unit_origin(q, nstrip, ngroup, planes_per_seg, kRows3d, ox, oy, oz);
+    const double a0 = (double)e.x;
+    s0 += a0;
+    sx += (double)ox * a0 + (double)e.y;
+    sy += (double)oy * a0 + (double)e.z;
+    sz += (double)oz * a0 + (double)e.w;
+  };
+  if (j < T) {
+    int q = wv;
+    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
+      float4 v[kRedUnroll];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) add(q + k * kRedWaves, v[k]);
     }
+    for (; q < units; q += kRedWaves) add(q, p[(int64_t)q * T]);
+  }
   red[0][wv][lane] = s0;
   red[1][wv][lane] = sx;
   red[2][wv][lane] = sy;
@@ -291,7 +314,10 @@ __global__ __launch_bounds__(256) void soft3d_bwd_reduce_kernel(const float* __r
   if (wv == 0 && j < T) {
     const int64_t k = (int64_t)blockIdx.y * T + j;
     double r[4];
-    for (int c = 0; c < 4; ++c) r[c] = ((red[c][0][lane] + red[c][1][lane]) + red[c][2][lane]) + red[c][3][lane];
+    for (int c = 0; c < 4; ++c) {
+      r[c] = red[c][0][lane];
+      for (int w = 1; w < kRedWaves; ++w) r[c] += red[c][w][lane];
+    }
     if (dtau) dtau[k] = (float)((double)lambda * r[0]);
     if (du)
       for (int c = 0; c < 3; ++c) du[k * 3 + c] = (float)(-(double)alpha * (double)lambda * r[1 + c]);
@@ -329,7 +355,7 @@ void launch_soft3d_fwd(const float* grid, const Shape& s, const float* u, float 
   else ECC_GO(false);
 #undef ECC_GO
   hipLaunchKernelGGL(soft3d_fwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                     dim3(256), 0, st, partial, (int)pl.grid.x * 4, T, chi);
+                     dim3(kRedWaves * kWave), 0, st, partial, (int)pl.grid.x * 4, T, chi);
 }
 
 void launch_soft3d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
@@ -361,7 +387,7 @@ void launch_soft3d_bwd(const float* grid, const Shape& s, const float* u, float 
 #undef ECC_GO
   if (partial) {
     hipLaunchKernelGGL(soft3d_bwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                       dim3(256), 0, st, partial, (int)pl.grid.x * 4, pl.nstrip, pl.ngroup, pl.planes_per_seg, T,
+                       dim3(kRedWaves * kWave), 0, st, partial, (int)pl.grid.x * 4, pl.nstrip, pl.ngroup, pl.planes_per_seg, T,
                        alpha, lambda, dtau, du);
   }
 }
