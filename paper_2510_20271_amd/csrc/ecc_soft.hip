@@ -161,7 +161,15 @@ __global__ void soft_fwd_reduce_kernel(const float* __restrict__ partial, int nt
   const int j = (int)(k - item * T);
   const float* p = partial + item * ntiles * (int64_t)T + j;
   double s = 0.0;
-  for (int t = 0; t < ntiles; ++t) s += (double)p[(int64_t)t * T];
+  int t = 0;
+  for (; t + 8 <= ntiles; t += 8) {  // eight loads in flight, added in tile order
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = p[(int64_t)(t + q) * T];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) s += (double)v[q];
+  }
+  for (; t < ntiles; ++t) s += (double)p[(int64_t)t * T];
   chi[k] = (float)s;
 }
 
@@ -250,15 +258,25 @@ __global__ void soft_bwd_reduce_kernel(const float* __restrict__ partial, int nt
   const int j = (int)(k - item * T);
   const float* p = partial + (item * ntiles * (int64_t)T + j) * 4;
   double s0 = 0.0, s[3] = {0.0, 0.0, 0.0};
-  for (int t = 0; t < ntiles; ++t) {
-    const float* q = p + (int64_t)t * T * 4;
+  auto add = [&](int t, const float4& e) {
     const int64_t i0 = (int64_t)t * kTile;
     const int64_t r0 = i0 / W;
     const double o[3] = {(double)(i0 % W), (double)(r0 % H), (double)(r0 / H)};
-    const double a0 = (double)q[0];
+    const float q[3] = {e.y, e.z, e.w};
+    const double a0 = (double)e.x;
     s0 += a0;
-    for (int c = 0; c < nd; ++c) s[c] += o[c] * a0 + (double)q[1 + c];
+    for (int c = 0; c < nd; ++c) s[c] += o[c] * a0 + (double)q[c];
+  };
+  const float4* p4 = reinterpret_cast<const float4*>(p);
+  int t = 0;
+  for (; t + 8 <= ntiles; t += 8) {  // eight loads in flight, added in tile order
+    float4 v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = p4[(int64_t)(t + q) * T];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) add(t + q, v[q]);
   }
+  for (; t < ntiles; ++t) add(t, p4[(int64_t)t * T]);
   if (dtau) dtau[k] = (float)((double)lambda * s0);
   if (du)
     for (int c = 0; c < nd; ++c) du[k * nd + c] = (float)(-(double)alpha * (double)lambda * s[c]);

@@ -258,43 +258,67 @@ __global__ __launch_bounds__(256) void soft2d_bwd_kernel(const float* __restrict
   }
 }
 
-// Reduction over units: block (x = group of 64 thresholds, y = item); the four
-// waves take units w, w+4, ... in order, then wave 0 adds the four sums in order.
-__global__ __launch_bounds__(256) void soft2d_fwd_reduce_kernel(const float* __restrict__ partial,
-                                                                int units, int T,
-                                                                float* __restrict__ chi) {
-  __shared__ double red[4][kWave];
+// Reduction over units: block (x = group of 64 thresholds, y = item) of 16 waves; wave w
+// adds units w, w+16, ... in order (eight loads in flight at a time: a lone large image
+// has thousands of units and one block per 64 thresholds), then wave 0 adds the 16 sums
+// in order.
+constexpr int kRedWaves = 16, kRedUnroll = 8;
+
+__global__ __launch_bounds__(kRedWaves * kWave) void soft2d_fwd_reduce_kernel(const float* __restrict__ partial,
+                                                                              int units, int T,
+                                                                              float* __restrict__ chi) {
+  __shared__ double red[kRedWaves][kWave];
   const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
   const int j = blockIdx.x * kWave + lane;
   const float* p = partial + (int64_t)blockIdx.y * units * T + j;
   double s = 0.0;
-  if (j < T)
-    for (int q = wv; q < units; q += 4) s += (double)p[(int64_t)q * T];
+  if (j < T) {
+    int q = wv;
+    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
+      float v[kRedUnroll];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) s += (double)v[k];
+    }
+    for (; q < units; q += kRedWaves) s += (double)p[(int64_t)q * T];
+  }
   red[wv][lane] = s;
   __syncthreads();
-  if (wv == 0 && j < T) chi[(int64_t)blockIdx.y * T + j] = (float)(((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane]);
+  if (wv == 0 && j < T) {
+    double r = red[0][lane];
+    for (int w = 1; w < kRedWaves; ++w) r += red[w][lane];
+    chi[(int64_t)blockIdx.y * T + j] = (float)r;
+  }
 }
 
 // dchi_dtau = lambda sum A0;  dchi_du = -alpha lambda sum (origin * A0 + A_xy)
-__global__ __launch_bounds__(256) void soft2d_bwd_reduce_kernel(const float* __restrict__ partial,
-                                                                int units, int nstrip, int rows_per_seg,
-                                                                int T, float alpha, float lambda,
-                                                                float* __restrict__ dtau,
-                                                                float* __restrict__ du) {
-  __shared__ double red[3][4][kWave];
+__global__ __launch_bounds__(kRedWaves * kWave) void soft2d_bwd_reduce_kernel(
+    const float* __restrict__ partial, int units, int nstrip, int rows_per_seg, int T, float alpha, float lambda,
+    float* __restrict__ dtau, float* __restrict__ du) {
+  __shared__ double red[3][kRedWaves][kWave];
   const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
   const int j = blockIdx.x * kWave + lane;
-  const float* p = partial + ((int64_t)blockIdx.y * units * T + j) * 4;
+  const float4* p = reinterpret_cast<const float4*>(partial) + (int64_t)blockIdx.y * units * T + j;
   double s0 = 0.0, sx = 0.0, sy = 0.0;
-  if (j < T)
-    for (int q = wv; q < units; q += 4) {
-      const float4 e = *reinterpret_cast<const float4*>(p + (int64_t)q * T * 4);
-      const double ox = (double)((q % nstrip) * kStripOut - kNC), oy = (double)((q / nstrip) * rows_per_seg);
-      const double a0 = (double)e.x;
-      s0 += a0;
-      sx += ox * a0 + (double)e.y;
-      sy += oy * a0 + (double)e.z;
+  auto add = [&](int q, const float4& e) {
+    const double ox = (double)((q % nstrip) * kStripOut - kNC), oy = (double)((q / nstrip) * rows_per_seg);
+    const double a0 = (double)e.x;
+    s0 += a0;
+    sx += ox * a0 + (double)e.y;
+    sy += oy * a0 + (double)e.z;
+  };
+  if (j < T) {
+    int q = wv;
+    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
+      float4 v[kRedUnroll];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) add(q + k * kRedWaves, v[k]);
     }
+    for (; q < units; q += kRedWaves) add(q, p[(int64_t)q * T]);
+  }
   red[0][wv][lane] = s0;
   red[1][wv][lane] = sx;
   red[2][wv][lane] = sy;
@@ -302,7 +326,10 @@ __global__ __launch_bounds__(256) void soft2d_bwd_reduce_kernel(const float* __r
   if (wv == 0 && j < T) {
     const int64_t k = (int64_t)blockIdx.y * T + j;
     double r[3];
-    for (int c = 0; c < 3; ++c) r[c] = ((red[c][0][lane] + red[c][1][lane]) + red[c][2][lane]) + red[c][3][lane];
+    for (int c = 0; c < 3; ++c) {
+      r[c] = red[c][0][lane];
+      for (int w = 1; w < kRedWaves; ++w) r[c] += red[c][w][lane];
+    }
     if (dtau) dtau[k] = (float)((double)lambda * r[0]);
     if (du) {
       du[k * 2 + 0] = (float)(-(double)alpha * (double)lambda * r[1]);
@@ -336,7 +363,7 @@ void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float 
     hipLaunchKernelGGL(soft2d_fwd_kernel<false>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
                        pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), partial);
   hipLaunchKernelGGL(soft2d_fwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                     dim3(256), 0, st, partial, pl.nstrip * pl.nseg, T, chi);
+                     dim3(kRedWaves * kWave), 0, st, partial, pl.nstrip * pl.nseg, T, chi);
 }
 
 void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
@@ -354,7 +381,7 @@ void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float 
                        grad_X, partial);
   if (partial) {
     hipLaunchKernelGGL(soft2d_bwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                       dim3(256), 0, st, partial, pl.nstrip * pl.nseg, pl.nstrip, pl.rows_per_seg, T, alpha,
+                       dim3(kRedWaves * kWave), 0, st, partial, pl.nstrip * pl.nseg, pl.nstrip, pl.rows_per_seg, T, alpha,
                        lambda, dtau, du);
   }
 }
