@@ -218,7 +218,7 @@ def main():
     if args.only == "" and not args.quick:
         for name, X, nd, bins in (("c1", synth.config_c1()[None], 2, 256), ("c3", synth.config_c3()[None], 3, 4096)):
             if X.dtype == np.uint16:
-                gi = torch.from_numpy(X.view(np.int16)).cuda()
+                gi = torch.from_numpy(X.view(np.int16)).cuda().view(torch.uint16)
             else:
                 gi = torch.from_numpy(X).cuda()
             wsi = torch.empty(api.ecc_workspace_bytes(X.shape[1:], 1, bins), dtype=torch.uint8, device="cuda")

@@ -35,7 +35,20 @@
 extern "C" {
 #endif
 
-typedef enum { ECC_U8 = 0, ECC_U16 = 1, ECC_F32 = 2 } ecc_dtype;
+/*
+ * Element types.  ECC_U8, ECC_U16 and ECC_F32 are read as they are by every
+ * entry point.  The others are taken by the hard curves only (ecc_hard,
+ * ecc_hard_top, ecc_hard_ex): the grid is first rounded to float32 (to nearest
+ * even) into the workspace and the curve is that of the rounded grid.  Rounding
+ * is monotone, so every set {p : fl32(X(p)) <= t} is a sublevel set of X and the
+ * curve is exact for the float32 thresholds it is read at (float16, bfloat16 and
+ * int16 convert without rounding at all); values beyond the float32 range are
+ * not allowed.  They need the larger workspace of ecc_workspace_bytes_dtype.
+ */
+typedef enum {
+  ECC_U8 = 0, ECC_U16 = 1, ECC_F32 = 2,
+  ECC_F16 = 3, ECC_I32 = 4, ECC_F64 = 5, ECC_BF16 = 6, ECC_I16 = 7
+} ecc_dtype;
 
 typedef enum {
   ECC_OK = 0,
@@ -63,6 +76,13 @@ size_t ecc_workspace_bytes(int ndim, const int64_t* dims /* host */, int64_t bat
                            int bins_or_T);
 
 /*
+ * The same for the hard curves with element type `dtype` (any ecc_dtype): adds the
+ * room for the float32 copy of the grid that ECC_F16 .. ECC_I16 need.
+ */
+size_t ecc_workspace_bytes_dtype(int ndim, const int64_t* dims /* host */, int64_t batch, int dtype,
+                                 int bins);
+
+/*
  * Hard ECC (Eq. 3 of the paper, Methods "full sweep"): per-vertex coefficient
  * c(p) from the 3x3 / 3x3x3 neighbourhood, histogram of c(p) over threshold
  * bins, inclusive prefix sum.
@@ -75,7 +95,7 @@ size_t ecc_workspace_bytes(int ndim, const int64_t* dims /* host */, int64_t bat
  *             range given (any dtype): t_b = float32(lo + (b+1)(hi-lo)/B)
  *               evaluated in float64, and t_{B-1} = float32(hi);
  *             NULL, integer dtype:  t_b = b   (one bin per level);
- *             NULL, ECC_F32:        lo, hi = min, max over the WHOLE batch
+ *             NULL, floating dtype: lo, hi = min, max over the WHOLE batch
  *               (one extra read pass over the grid), then as above.
  *   curve   device out, int64 [batch][B]: curve[i][b] = ECC of item i at t_b.
  *           A point with X(p) > t_{B-1} is in no sublevel set and is dropped;

@@ -17,6 +17,8 @@ SIGNATURES = {
     "ecc_last_error": (ctypes.c_char_p, []),
     "ecc_version": (ctypes.c_char_p, []),
     "ecc_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.POINTER(c_i64), c_i64, ctypes.c_int]),
+    "ecc_workspace_bytes_dtype": (ctypes.c_size_t, [ctypes.c_int, ctypes.POINTER(c_i64), c_i64, ctypes.c_int,
+                                                    ctypes.c_int]),
     "ecc_hard": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, ctypes.c_int,
                                 ctypes.c_int, ctypes.POINTER(ctypes.c_double), c_vp, c_vp,
                                 ctypes.c_size_t, c_vp]),

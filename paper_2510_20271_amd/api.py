@@ -11,8 +11,10 @@ import torch
 
 from . import _lib
 
-ECC_U8, ECC_U16, ECC_F32 = 0, 1, 2
-_DTYPES = {torch.uint8: ECC_U8, torch.uint16: ECC_U16, torch.int16: ECC_U16, torch.float32: ECC_F32}
+ECC_U8, ECC_U16, ECC_F32, ECC_F16, ECC_I32, ECC_F64, ECC_BF16, ECC_I16 = 0, 1, 2, 3, 4, 5, 6, 7
+# (the hard curves take all of these; ecc_coeff and the soft path uint8 / uint16 / float32 resp. float32)
+_DTYPES = {torch.uint8: ECC_U8, torch.uint16: ECC_U16, torch.float32: ECC_F32, torch.float16: ECC_F16,
+           torch.int32: ECC_I32, torch.float64: ECC_F64, torch.bfloat16: ECC_BF16, torch.int16: ECC_I16}
 
 
 class EccError(RuntimeError):
@@ -53,8 +55,12 @@ def ecc_workspace_bytes(item_shape, batch: int, bins_or_T: int) -> int:
     return int(_lib.load().ecc_workspace_bytes(len(item_shape), _dims(item_shape), batch, bins_or_T))
 
 
-def _workspace(item_shape, batch, n, device, workspace):
-    need = ecc_workspace_bytes(item_shape, batch, n)
+def ecc_workspace_bytes_dtype(item_shape, batch: int, dtype: int, bins: int) -> int:
+    return int(_lib.load().ecc_workspace_bytes_dtype(len(item_shape), _dims(item_shape), batch, dtype, bins))
+
+
+def _workspace(item_shape, batch, n, device, workspace, dtype=ECC_F32):
+    need = ecc_workspace_bytes_dtype(item_shape, batch, dtype, n)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
     return workspace
@@ -75,7 +81,7 @@ def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, w
     batch, item = grid.shape[0], tuple(grid.shape[1:])
     if curve is None:
         curve = torch.empty((batch, bins), dtype=torch.int64, device=grid.device)
-    workspace = _workspace(item, batch, max(bins, 1), grid.device, workspace)
+    workspace = _workspace(item, batch, max(bins, 1), grid.device, workspace, _DTYPES[grid.dtype])
     rng = None
     if range is not None:
         rng = (ctypes.c_double * 2)(float(range[0]), float(range[1]))
@@ -99,7 +105,7 @@ def ecc_hard_ex(grid: torch.Tensor, ndim: int, construction: int, filtration: in
     batch, item = grid.shape[0], tuple(grid.shape[1:])
     if curve is None:
         curve = torch.empty((batch, bins), dtype=torch.int64, device=grid.device)
-    workspace = _workspace(item, batch, max(bins, 1), grid.device, workspace)
+    workspace = _workspace(item, batch, max(bins, 1), grid.device, workspace, _DTYPES[grid.dtype])
     rng = None
     if range is not None:
         rng = (ctypes.c_double * 2)(float(range[0]), float(range[1]))

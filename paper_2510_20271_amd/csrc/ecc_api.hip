@@ -50,8 +50,22 @@ int make_shape(int ndim, const int64_t* dims, int64_t batch, ecc::Shape* s) {
 
 int check_dtype(int dtype) {
   if (dtype != ECC_U8 && dtype != ECC_U16 && dtype != ECC_F32)
-    return fail(ECC_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+    return fail(ECC_ERR_INVALID_ARG, "unknown dtype %d (this entry point takes ECC_U8, ECC_U16, ECC_F32)", dtype);
   return ECC_OK;
+}
+// the hard curves also take the element types that are rounded to float32 first
+bool converted_dtype(int dtype) { return dtype >= ECC_F16 && dtype <= ECC_I16; }
+bool integer_dtype(int dtype) { return dtype == ECC_U8 || dtype == ECC_U16 || dtype == ECC_I32 || dtype == ECC_I16; }
+size_t dtype_size(int dtype) {
+  switch (dtype) {
+    case ECC_U8: return 1;
+    case ECC_U16: case ECC_F16: case ECC_BF16: case ECC_I16: return 2;
+    case ECC_F64: return 8;
+    default: return 4;
+  }
+}
+size_t convert_bytes(const ecc::Shape& s, int dtype) {
+  return converted_dtype(dtype) ? (((size_t)s.N * s.batch * sizeof(float) + 255) / 256) * 256 : 0;
 }
 
 int device_status(hipError_t e, const char* what) {
@@ -101,13 +115,21 @@ size_t ecc_workspace_bytes(int ndim, const int64_t* dims, int64_t batch, int bin
   return a > b ? a : b;
 }
 
+size_t ecc_workspace_bytes_dtype(int ndim, const int64_t* dims, int64_t batch, int dtype, int bins) {
+  ecc::Shape s;
+  if (make_shape(ndim, dims, batch, &s) != ECC_OK) return 0;
+  if (!converted_dtype(dtype) && check_dtype(dtype) != ECC_OK) return 0;
+  const size_t base = ecc_workspace_bytes(ndim, dims, batch, bins);
+  return base ? base + convert_bytes(s, dtype) : 0;
+}
+
 static int hard_common(int conv, const char* who, const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
              const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
              void* hip_stream) {
   ecc::Shape s;
   int rc = make_shape(ndim, dims, batch, &s);
   if (rc != ECC_OK) return rc;
-  if ((rc = check_dtype(dtype)) != ECC_OK) return rc;
+  if (!converted_dtype(dtype) && (rc = check_dtype(dtype)) != ECC_OK) return rc;
   if (!grid) return fail(ECC_ERR_INVALID_ARG, "grid is NULL");
   if (!curve) return fail(ECC_ERR_INVALID_ARG, "curve is NULL");
   if (bins < 1) return fail(ECC_ERR_INVALID_ARG, "bins must be >= 1, got %d", bins);
@@ -120,15 +142,33 @@ static int hard_common(int conv, const char* who, const void* grid, int ndim, co
     if (!std::isfinite(lo) || !std::isfinite(hi) || lo > hi)
       return fail(ECC_ERR_INVALID_ARG, "range must be finite with lo <= hi");
   }
-  const size_t esz = dtype == ECC_U8 ? 1 : dtype == ECC_U16 ? 2 : 4;
-  if (reinterpret_cast<uintptr_t>(grid) % esz)
+  if (reinterpret_cast<uintptr_t>(grid) % dtype_size(dtype))
     return fail(ECC_ERR_INVALID_ARG, "grid is not aligned to its element size");
   if (reinterpret_cast<uintptr_t>(curve) % 8)
     return fail(ECC_ERR_INVALID_ARG, "curve is not 8-byte aligned");
-  if ((rc = check_workspace(workspace, workspace_bytes, ecc::hard_workspace_bytes(s, bins))) != ECC_OK)
+  const size_t base_bytes = ecc::hard_workspace_bytes(s, bins);
+  if ((rc = check_workspace(workspace, workspace_bytes, base_bytes + convert_bytes(s, dtype))) != ECC_OK)
     return rc;
-  return device_status(ecc::launch_hard(grid, s, dtype, bins, range != nullptr, lo, hi, curve, workspace,
-                                        static_cast<hipStream_t>(hip_stream), nullptr, conv),
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (converted_dtype(dtype)) {
+    // rounded to float32 behind the path's own workspace, then the float32 path; one bin per level
+    // (integer types without a range) is the equal-width table over (-1, B-1], or the lower edges
+    // of the one over [0, B) for superlevel sets
+    float* f32 = reinterpret_cast<float*>(static_cast<char*>(workspace) + base_bytes);
+    if ((rc = device_status(ecc::launch_convert(grid, dtype, s.N * s.batch, f32, st), who)) != ECC_OK) return rc;
+    bool have_range = range != nullptr;
+    if (!have_range && integer_dtype(dtype)) {
+      have_range = true;
+      const bool super = (conv & ecc::kConvSuper) != 0;
+      lo = super ? 0.0 : -1.0;
+      hi = super ? (double)bins : (double)bins - 1.0;
+    }
+    return device_status(ecc::launch_hard(f32, s, ECC_F32, bins, have_range, lo, hi, curve, workspace, st, nullptr,
+                                          conv),
+                         who);
+  }
+  return device_status(ecc::launch_hard(grid, s, dtype, bins, range != nullptr, lo, hi, curve, workspace, st,
+                                        nullptr, conv),
                        who);
 }
 

@@ -501,6 +501,36 @@ hipError_t launch_hard_dir(const float* grid, const Shape& sv, const float* u, f
   return launch_hard(tilted, sv, 2, bins, have_range, lo, hi, curve, ws, st, nullptr);
 }
 
+// ---------------------------------------------------------------------------
+// further element types: rounded to float32 (to nearest even) into the workspace
+// ---------------------------------------------------------------------------
+template <typename S> __device__ __forceinline__ float to_f32(S v) { return (float)v; }
+struct Bf16 { uint16_t bits; };
+template <> __device__ __forceinline__ float to_f32<Bf16>(Bf16 v) { return __uint_as_float((unsigned)v.bits << 16); }
+
+template <typename S>
+__global__ __launch_bounds__(kBlock) void convert_kernel(const S* __restrict__ src, int64_t n,
+                                                         float* __restrict__ dst) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = to_f32<S>(src[i]);
+}
+
+hipError_t launch_convert(const void* grid, int dtype, int64_t n, float* out, hipStream_t st) {
+  int64_t nb = (n + kBlock - 1) / kBlock;
+  nb = nb < 1 ? 1 : (nb > 16384 ? 16384 : nb);
+#define ECC_GO(S) \
+  hipLaunchKernelGGL(convert_kernel<S>, dim3((unsigned)nb), dim3(kBlock), 0, st, static_cast<const S*>(grid), n, out)
+  switch (dtype) {
+    case 3: ECC_GO(_Float16); break;
+    case 4: ECC_GO(int32_t); break;
+    case 5: ECC_GO(double); break;
+    case 6: ECC_GO(Bf16); break;
+    default: ECC_GO(int16_t); break;
+  }
+#undef ECC_GO
+  return hipGetLastError();
+}
+
 hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st) {
   dim3 g(blocks_for(s.N), (unsigned)s.batch);
 #define ECC_GO(T, ND)                                                                          \

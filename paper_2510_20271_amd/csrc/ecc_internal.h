@@ -29,6 +29,8 @@ size_t hard_dir_workspace_bytes(const Shape& sv, int bins);
 hipError_t launch_hard_dir(const float* grid, const Shape& sv, const float* u, float alpha, int batch,
                            int bins, bool have_range, double lo, double hi, int64_t* curve, void* ws,
                            hipStream_t st);
+// element types beyond uint8 / uint16 / float32 (codes 3..7 of ecc_dtype): n elements rounded to float32
+hipError_t launch_convert(const void* grid, int dtype, int64_t n, float* out, hipStream_t st);
 hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st);
 
 // fast sweeps (one wave per column strip, lane-mask stencil)

@@ -57,7 +57,7 @@ INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
     (dict(dims=(0, 4)), INVALID, "dims"),
     (dict(batch=0), INVALID, "batch"),
     (dict(batch=70000), UNSUPPORTED, "batch"),
-    (dict(dtype=7), INVALID, "dtype"),
+    (dict(dtype=9), INVALID, "dtype"),
     (dict(grid=None), INVALID, "grid"),
     (dict(curve=None), INVALID, "curve"),
     (dict(bins=0), INVALID, "bins"),
@@ -85,7 +85,7 @@ def test_hard_rejects_bad_arguments(kw, status, word):
     (dict(construction=2), INVALID, "construction"),
     (dict(filtration=-1), INVALID, "filtration"),
     (dict(bins=0), INVALID, "bins"),
-    (dict(dtype=7), INVALID, "dtype"),
+    (dict(dtype=9), INVALID, "dtype"),
     (dict(ws_bytes=8), WORKSPACE, "workspace"),
 ])
 def test_hard_ex_rejects_bad_arguments(kw, status, word):
@@ -96,6 +96,23 @@ def test_hard_ex_rejects_bad_arguments(kw, status, word):
                          FAKE, FAKE, a["ws_bytes"], None)
     assert rc == status
     assert word in lib.ecc_last_error().decode()
+
+
+def test_workspace_bytes_dtype_host_only():
+    lib = _lib.load()
+    base = lib.ecc_workspace_bytes(2, _dims(100, 200), 3, 64)
+    for dt in (0, 1, 2):
+        assert lib.ecc_workspace_bytes_dtype(2, _dims(100, 200), 3, dt, 64) == base
+    for dt in (3, 4, 5, 6, 7):  # room for the float32 copy of the grid
+        assert lib.ecc_workspace_bytes_dtype(2, _dims(100, 200), 3, dt, 64) >= base + 3 * 100 * 200 * 4
+    assert lib.ecc_workspace_bytes_dtype(2, _dims(100, 200), 3, 8, 64) == 0
+    # a converted type with only the plain workspace is refused; ecc_coeff does not take it at all
+    rc = lib.ecc_hard(FAKE, 2, _dims(100, 200), 3, 5, 64, None, FAKE, FAKE, base, None)
+    assert rc == WORKSPACE and "workspace" in lib.ecc_last_error().decode()
+    rc = lib.ecc_coeff(FAKE, 2, _dims(4, 4), 1, 5, FAKE, None)
+    assert rc == INVALID and "dtype" in lib.ecc_last_error().decode()
+    rc = lib.ecc_hard(ctypes.c_void_p(0x1004), 2, _dims(4, 4), 1, 5, 8, None, FAKE, FAKE, 1 << 20, None)
+    assert rc == INVALID and "aligned" in lib.ecc_last_error().decode()
 
 
 def test_hard_rejects_null_dims():
