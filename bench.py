@@ -96,7 +96,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path shards by batch item / "
-              "z-slab with one all-reduce of the histogram, see DESIGN.md)", file=sys.stderr)
+              "z-slab with one all-reduce of the histogram, which this single-GPU build does not include)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
