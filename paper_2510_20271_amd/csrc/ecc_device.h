@@ -259,6 +259,24 @@ __device__ __forceinline__ int coeff_tilted_at(const float* __restrict__ g, cons
       W, z, y, x);
 }
 
+// Sum of v over the 64 lanes, delivered in lane 63: four steps inside each row of 16
+// lanes (quad swaps, half-row and row mirrors), then the rows' totals handed on by
+// row_bcast.  Data-parallel-primitive moves only: nothing goes through LDS, unlike a
+// shuffle butterfly.  Fixed order, so the result is the same on every run.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float x) {  // 0 where the move has no source or the row is masked
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum_lane63(float v) {
+  v += dpp_move<0xB1, 0xf>(v);   // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E, 0xf>(v);   // quad_perm [2,3,0,1]
+  v += dpp_move<0x141, 0xf>(v);  // row_half_mirror
+  v += dpp_move<0x140, 0xf>(v);  // row_mirror: every lane holds its row's sum
+  v += dpp_move<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+  v += dpp_move<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+  return v;
+}
+
 // ---- critical-vertex queue of a wave ----------------------------------------
 // Critical vertices (c != 0) turn up a few lanes at a time.  Instead of running
 // the binning code with most lanes idle, a wave appends (value, c) to a small

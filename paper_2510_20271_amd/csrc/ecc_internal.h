@@ -75,6 +75,8 @@ hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, fl
                            const float* tau, int T, float lambda, const float* g, float* grad_X,
                            float* dtau, float* du, void* ws, hipStream_t st, bool tiltc = false);
 
+void launch_clear_f32(float* p, int64_t n, hipStream_t st);  // p[0..n) = 0 (fill kernel)
+
 // fused 2D soft path (strip sweep + sigmoid sinks)
 bool soft2d_supported(const Shape& s, int T);
 size_t soft2d_workspace_bytes(const Shape& s, int T);

@@ -283,6 +283,33 @@ __global__ void soft_bwd_reduce_kernel(const float* __restrict__ partial, int nt
 }
 
 // ---------------------------------------------------------------------------
+// grad_X of the fused paths is zero away from the critical vertices: cleared by a
+// fill kernel of its own (a captured graph may hold it, unlike a memset node)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void clear_f32_kernel(float4* __restrict__ p, int64_t n4, float* __restrict__ tail,
+                                                        int ntail) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0.f;
+}
+
+void launch_clear_f32(float* p, int64_t total, hipStream_t st) {
+  // p is only known to be 4-byte aligned: whole float4s from the first 16-byte boundary on,
+  // the few elements before and after by the first threads (two launches at most)
+  const uintptr_t a = reinterpret_cast<uintptr_t>(p);
+  int64_t lead = (int64_t)(((16 - (a & 15)) & 15) / 4);
+  if (lead > total) lead = total;
+  const int64_t n4 = (total - lead) / 4;
+  const int64_t rest = total - lead - n4 * 4;
+  int64_t nb = (n4 + 255) / 256;
+  nb = nb < 1 ? 1 : (nb > 4096 ? 4096 : nb);
+  if (lead)
+    hipLaunchKernelGGL(clear_f32_kernel, dim3(1), dim3(256), 0, st, (float4*)nullptr, (int64_t)0, p, (int)lead);
+  hipLaunchKernelGGL(clear_f32_kernel, dim3((unsigned)nb), dim3(256), 0, st, reinterpret_cast<float4*>(p + lead), n4,
+                     p + lead + n4 * 4, (int)rest);
+}
+
+// ---------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------
 static int64_t tiles_of(const Shape& s) { return (s.N + kTile - 1) / kTile; }

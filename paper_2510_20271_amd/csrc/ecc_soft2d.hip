@@ -10,9 +10,10 @@
 //     so T <= 256) and runs over the queue entries (LDS broadcast reads): the
 //     sums over p of Eq. 6 / Eq. 9 / Eq. 10 need no cross-lane reduction;
 //   - backward: the same pass also forms, per entry, the contraction of Eq. 8 with
-//     the upstream gradient as a fixed butterfly sum over the lanes (grad_X).
+//     the upstream gradient as a fixed-order sum over the lanes (grad_X).
 // grad_X is zero away from critical vertices; the sweep writes those zeros row
-// by row for the vertices it owns, before any entry of those rows is drained.
+// by row for the vertices it owns, before any entry of those rows is drained
+// (measured a little quicker than a fill kernel in front of the sweep).
 // Each wave writes its partial sums to the workspace; a second kernel adds them
 // in a fixed order in float64, so results are run-to-run identical.
 //
@@ -119,7 +120,7 @@ struct SoftBwdSink : SoftCommon {
 
   // One pass over entries x thresholds serves all three derivatives: lane l holds
   // sigma'(z) / lambda for its thresholds; the sums over p stay in the lane, the
-  // contraction with the upstream gradient (Eq. 8) is a fixed butterfly over lanes.
+  // contraction with the upstream gradient (Eq. 8) is a fixed-order sum over the lanes.
   __device__ __forceinline__ void consume(const Entry* buf, int n) {
     const int lane = threadIdx.x & (kWave - 1);
     for (int e = 0; e < n; ++e) {
@@ -142,9 +143,8 @@ struct SoftBwdSink : SoftCommon {
         }
       }
       if (gx) {  // wave-uniform
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) gd += __shfl_xor(gd, o);
-        if (lane == 0) gx[(int64_t)buf[e].row * W + buf[e].col] = -lambda * c * gd;
+        gd = wave_sum_lane63(gd);
+        if (lane == kWave - 1) gx[(int64_t)buf[e].row * W + buf[e].col] = -lambda * c * gd;
       }
     }
   }

@@ -7,7 +7,7 @@
 // in a small LDS stage, and then every lane runs over the staged entries for the
 // thresholds it owns (tau_l, tau_{l+64}, ...; T <= 256): the sums over p of
 // Eq. 6 / Eq. 9 / Eq. 10 need no cross-lane reduction, the contraction of Eq. 8
-// with the upstream gradient is a fixed butterfly over the lanes.  grad_X is
+// with the upstream gradient is a fixed-order sum over the lanes.  grad_X is
 // cleared by a fill kernel first and written at the critical vertices only.
 // Each wave leaves its partial sums in the workspace; a second kernel adds them
 // in a fixed order in float64, so results are run-to-run identical.
@@ -124,9 +124,8 @@ struct Soft3BwdSink : Soft3Common {
         }
       }
       if (gx) {  // wave-uniform
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) gd += __shfl_xor(gd, o);
-        if (lane == 0) gx[(int64_t)en.z * plane + en.inpl] = -lambda * en.c * gd;
+        gd = wave_sum_lane63(gd);
+        if (lane == kWave - 1) gx[(int64_t)en.z * plane + en.inpl] = -lambda * en.c * gd;
       }
     }
   }
@@ -324,13 +323,6 @@ __global__ __launch_bounds__(kRedWaves * kWave) void soft3d_bwd_reduce_kernel(
   }
 }
 
-__global__ __launch_bounds__(256) void soft3d_clear_kernel(float4* __restrict__ p, int64_t n4, float* __restrict__ tail,
-                                                           int ntail) {
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0.f;
-}
-
 static float kneg3d(float lambda) { return (float)(-(double)lambda * 1.4426950408889634); }
 
 bool soft3d_supported(const Shape& s, int T) {
@@ -363,21 +355,7 @@ void launch_soft3d_bwd(const float* grid, const Shape& s, const float* u, float 
                        hipStream_t st, bool tiltc) {
   const Plan3d pl = plan3d<float>(s);
   float* partial = (dtau || du) ? static_cast<float*>(ws) : nullptr;
-  if (grad_X) {  // zero away from the critical vertices
-    const int64_t total = s.N * s.batch;
-    // grad_X is only known to be 4-byte aligned: whole float4s from the first 16-byte boundary on
-    const uintptr_t a = reinterpret_cast<uintptr_t>(grad_X);
-    int64_t lead = (int64_t)(((16 - (a & 15)) & 15) / 4);
-    if (lead > total) lead = total;
-    const int64_t n4 = (total - lead) / 4;
-    const int64_t rest = total - lead - n4 * 4;
-    int64_t nb = (n4 + 255) / 256;
-    nb = nb < 1 ? 1 : (nb > 4096 ? 4096 : nb);
-    // the few elements before and after the aligned body: two tiny launches at most
-    if (lead) hipLaunchKernelGGL(soft3d_clear_kernel, dim3(1), dim3(256), 0, st, (float4*)nullptr, (int64_t)0, grad_X, (int)lead);
-    hipLaunchKernelGGL(soft3d_clear_kernel, dim3((unsigned)nb), dim3(256), 0, st,
-                       reinterpret_cast<float4*>(grad_X + lead), n4, grad_X + lead + n4 * 4, (int)rest);
-  }
+  if (grad_X) launch_clear_f32(grad_X, s.N * s.batch, st);  // zero away from the critical vertices
 #define ECC_GO(TC)                                                                                          \
   hipLaunchKernelGGL(soft3d_bwd_kernel<TC>, pl.grid, dim3(256), kSoft3Lds, st, grid, (int)s.D, (int)s.H,      \
                      (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg, u, alpha, tau, T,       \
