@@ -144,14 +144,16 @@ __device__ __forceinline__ void soft3_lds(int* smem, unsigned*& xch, s3::TubeQue
   stage = reinterpret_cast<Soft3Entry*>(smem + kXchInts + 4 * kQueueCap * 3) + wv * kWave;
 }
 
-// origin of a wave's unit: unit = ((seg * nstrip) + strip) * ngroup4 + group
-__host__ __device__ __forceinline__ void unit_origin(int unit, int nstrip, int ngroup, int planes_per_seg, int R,
-                                                     int& ox, int& oy, int& oz) {
-  const int ngroup4 = (ngroup + 3) & ~3;
-  const int group = unit % ngroup4, rest = unit / ngroup4;
-  ox = (rest % nstrip) * s3::kOut - 1;
+// origin of a wave's unit (the numbering of ecc_sweep3d.h)
+__host__ __device__ __forceinline__ void unit_origin(int unit, int D, int H, int W, long long batch,
+                                                     int planes_per_seg, int R, int& ox, int& oy, int& oz) {
+  const Tiling3 tl = make_tiling3(D, H, W, batch, R);
+  int seg, strip, group;
+  bool tail, active;
+  decode_unit3(tl, unit, seg, strip, group, tail, active);
+  ox = strip * s3::kOut - 1;
   oy = group * R;
-  oz = (rest / nstrip) * planes_per_seg;
+  oz = seg * planes_per_seg;
 }
 
 // partial[(item * units + unit) * T + j]
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(256) void soft3d_fwd_kernel(const float* __restrict
   for (int t = 0; t < kSoft3TL; ++t) queue.sink.acc[t] = 0.f;
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int ox, oy;
-  unit_origin(unit, nstrip, ngroup, planes_per_seg, kRows3d, ox, oy, queue.sink.oz);
+  unit_origin(unit, D, H, W, gridDim.y, planes_per_seg, kRows3d, ox, oy, queue.sink.oz);
   WaveRange range;
   const float* g = grid + (int64_t)blockIdx.y * N;
   if constexpr (TILTC) {
@@ -220,7 +222,7 @@ __global__ __launch_bounds__(256) void soft3d_bwd_kernel(const float* __restrict
   s.plane = (int64_t)H * W;
   s.lambda = lambda;
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  unit_origin(unit, nstrip, ngroup, planes_per_seg, kRows3d, s.ox, s.oy, s.oz);
+  unit_origin(unit, D, H, W, gridDim.y, planes_per_seg, kRows3d, s.ox, s.oy, s.oz);
   WaveRange range;
   const float* g = grid + (int64_t)blockIdx.y * N;
   if constexpr (TILTC) {
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(kRedWaves * kWave) void soft3d_fwd_reduce_kernel(co
 
 // dchi_dtau = lambda sum A0;  dchi_du = -alpha lambda sum (origin * A0 + A_xyz)
 __global__ __launch_bounds__(kRedWaves * kWave) void soft3d_bwd_reduce_kernel(
-    const float* __restrict__ partial, int units, int nstrip, int ngroup, int planes_per_seg, int T, float alpha,
+    const float* __restrict__ partial, int units, int D, int H, int W, int planes_per_seg, int T, float alpha,
     float lambda, float* __restrict__ dtau, float* __restrict__ du) {
   __shared__ double red[4][kRedWaves][kWave];
   const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
@@ -287,7 +289,7 @@ __global__ __launch_bounds__(kRedWaves * kWave) void soft3d_bwd_reduce_kernel(
   double s0 = 0.0, sx = 0.0, sy = 0.0, sz = 0.0;
   auto add = [&](int q, const float4& e) {
     int ox, oy, oz;
-    unit_origin(q, nstrip, ngroup, planes_per_seg, kRows3d, ox, oy, oz);
+    unit_origin(q, D, H, W, gridDim.y, planes_per_seg, kRows3d, ox, oy, oz);
     const double a0 = (double)e.x;
     s0 += a0;
     sx += (double)ox * a0 + (double)e.y;
@@ -365,7 +367,7 @@ void launch_soft3d_bwd(const float* grid, const Shape& s, const float* u, float 
 #undef ECC_GO
   if (partial) {
     hipLaunchKernelGGL(soft3d_bwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                       dim3(kRedWaves * kWave), 0, st, partial, (int)pl.grid.x * 4, pl.nstrip, pl.ngroup, pl.planes_per_seg, T,
+                       dim3(kRedWaves * kWave), 0, st, partial, (int)pl.grid.x * 4, (int)s.D, (int)s.H, (int)s.W, pl.planes_per_seg, T,
                        alpha, lambda, dtau, du);
   }
 }

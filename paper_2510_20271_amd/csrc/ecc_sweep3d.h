@@ -259,32 +259,47 @@ __device__ __forceinline__ void arc_starts(const unsigned (&m)[8], unsigned g, u
 // One tube: columns xs .. xs+63 (outputs xs+1 .. xs+62), output rows
 // yb .. yb+R-1, output planes z0 .. z1-1.  SAFE: some lane or row of the tube
 // lies outside the grid (those read as +inf).
+// A SAFE tube may be folded: when the strip is narrow (the ragged last strip of a
+// grid), its S = outputs + 2 columns fit into the wave F times, and fold f (lanes
+// f*S .. f*S+S-1) takes the same columns for the rows yb0 + f*R .. yb0 + f*R + R-1.
+// Lanes that meet at the seam of two folds are halo lanes on both sides, whose
+// outputs are dropped, so the folds do not interact.
 // TiltT: the field swept is X + t(p) (directional curves), NoTilt: X itself.
 template <typename T, int R, typename Sink, bool SAFE, bool SKIP_TOP, bool SKIP_BOTTOM, typename TiltT>
 __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item_elems, int D, int H,
-                                           int W, int xs, int yb, int z0, int z1,
+                                           int W, int xs, int yb0, int z0, int z1,
                                            TubeQueue<Sink>& queue, unsigned* xch, WaveRange& range,
-                                           const TiltT& tilt) {
+                                           const TiltT& tilt, int S = kWave, int F = 1) {
   constexpr bool skip_top = SKIP_TOP, skip_bottom = SKIP_BOTTOM;
   const int lane = threadIdx.x & (kWave - 1);
-  const int x = xs + lane;
-  const bool inb = !SAFE || (x >= 0 && x < W);
-  const bool out_lane = lane >= 1 && lane <= kOut && x >= 0 && x < W;
-  const unsigned voff = (SAFE ? (inb ? (unsigned)x : 0u) : (unsigned)lane) * (unsigned)sizeof(T);
+  const int fold = SAFE ? lane / S : 0;  // (S = 64, F = 1: one fold, as the tubes inside the grid)
+  const int xl = SAFE ? lane - fold * S : lane;
+  const int x = xs + xl;
+  const int yb = yb0 + fold * R;  // per lane in a folded tube
+  const bool inb = !SAFE || (fold < F && x >= 0 && x < W);
+  const bool out_lane = xl >= 1 && xl <= S - 2 && inb;
 
   // The buffer resource is rebuilt for every plane (base: row 0 of the plane,
   // column xs; column 0 for SAFE tubes), so only one plane has to stay below
   // 2^31 bytes.  Planes past the end of the item are not read (zero records).
   const int64_t plane = (int64_t)H * W;
   const T* const item_end = g + item_elems;
-  unsigned roff[R + 2];  // byte offset of tube row j inside a plane (clamped into the grid)
-  bool rok[R + 2];       // row j is inside the grid
+  // Tubes inside the grid: lane offset + the rows' offsets (wave-uniform).  SAFE tubes: the
+  // lane's own offset of tube row 1 (vb) and of row 0 (v0), rows 2.. by a wave-uniform step;
+  // a row or lane outside the grid reads some address inside the item (or beyond its end,
+  // which a buffer load answers with 0) and is replaced by the padding value afterwards.
+  const unsigned pitch = (unsigned)W * (unsigned)sizeof(T);
+  unsigned roff[R + 2];  // tubes inside the grid: byte offset of tube row j inside a plane
+  bool okj[R + 2];       // row j of this lane is inside the grid (and so is the lane)
 #pragma unroll
   for (int j = 0; j <= R + 1; ++j) {
     const int y = yb - 1 + j;
-    rok[j] = y >= 0 && y < H;
-    roff[j] = (unsigned)min(max(y, 0), H - 1) * (unsigned)W * (unsigned)sizeof(T);
+    okj[j] = inb && y >= 0 && y < H;
+    roff[j] = (unsigned)(yb0 - 1 + j) * pitch;  // (not used by SAFE tubes)
   }
+  const unsigned vb = SAFE ? (inb ? ((unsigned)yb * (unsigned)W + (unsigned)x) * (unsigned)sizeof(T) : 0u)
+                           : (unsigned)lane * (unsigned)sizeof(T);
+  const unsigned v0 = (SAFE && vb >= pitch) ? vb - pitch : 0u;
   const T* pnext = g + (int64_t)max(z0 - 1, 0) * plane + (SAFE ? 0 : xs);  // next plane to load
   // the last plane this segment needs: z1 (above its last output plane) or the grid's last one;
   // what the pipeline would fetch beyond it is that plane again (a cache hit, no memory traffic)
@@ -294,7 +309,10 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<T*>(pnext), 0, (int)(left > 0x7fffffff ? 0x7fffffff : (left > 0 ? left : 0)), 0x00020000);
 #pragma unroll
-    for (int j = 0; j <= R + 1; ++j) raw[j] = Load<T>::get(rsrc, voff, roff[j]);
+    for (int j = 0; j <= R + 1; ++j) {
+      if (SAFE) raw[j] = (j == 0) ? Load<T>::get(rsrc, v0, 0u) : Load<T>::get(rsrc, vb, (unsigned)(j - 1) * pitch);
+      else raw[j] = Load<T>::get(rsrc, vb, roff[j]);
+    }
     if (pnext < plast) pnext += plane;
   };
   // tilt of the vertex (x, row j of the tube, plane z): t = fl(fl(fl(a_x x) + fl(a_y y)) + fl(a_z z));
@@ -317,7 +335,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
       }
       else if (TiltT::kOn) f = add_rn(f, add_rn(txy[j], tz));
       else if (sizeof(T) == 4) f += 0.0f;  // -0 -> +0 so that equal values differ by +0
-      if (SAFE) f = (inb && rok[j]) ? f : (TiltT::kTop ? -INFINITY : INFINITY);
+      if (SAFE) f = okj[j] ? f : (TiltT::kTop ? -INFINITY : INFINITY);
       dst[j] = f;
     }
   };
@@ -374,7 +392,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 #pragma unroll
         for (int j = 1; j <= R; ++j) {
           const float v = TiltT::kNeg ? -p[j] : p[j];  // the range is that of the original values
-          if (SAFE) range.add_if(v, inb && rok[j]);
+          if (SAFE) range.add_if(v, okj[j]);
           else range.add(v);
         }
       }
@@ -483,7 +501,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
       t[5] = dn0;
       Slices sl;
       unsigned nz = count_pq(s, t, sl) & planes;
-      const bool row_ok = !SAFE || rok[j];
+      const bool row_ok = !SAFE || okj[j];
       if (!(out_lane && row_ok)) nz = 0u;
       const unsigned inpl = (unsigned)((yb - 1 + j) * W + x);
       while (ballot(nz != 0)) {
@@ -504,7 +522,60 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
 
 }  // namespace s3
 
-// Work unit of a wave: (z segment, row group, column strip) of one item;
+// How the tubes of one z segment are numbered.  The strips but the last are full (62
+// outputs) and have one unit per row group; the last strip is folded when it is
+// narrow (see sweep_tube): F row groups per unit.  Units are padded to multiples of
+// four per strip kind, so the four waves of a block are four consecutive row groups
+// of one strip.
+struct Tiling3 {
+  int nstrip, ngroup, ngroup4;  // strips, row groups, row groups padded to a multiple of 4
+  int S, F;                     // lanes per fold and folds of a last-strip unit
+  int ngroupT, full, units_seg; // units of the last strip, units of the full strips, units per segment
+};
+__host__ __device__ __forceinline__ Tiling3 make_tiling3(int D, int H, int W, long long batch, int R) {
+  Tiling3 t;
+  t.nstrip = (W + s3::kOut - 1) / s3::kOut;
+  t.ngroup = (H + R - 1) / R;
+  t.ngroup4 = (t.ngroup + 3) & ~3;
+  const int wt = W - s3::kOut * (t.nstrip - 1);  // outputs of the last strip, 1..62
+  t.S = kWave;
+  t.F = 1;
+  // Folding pays when the launch runs many rounds of waves over the chip (fewer waves, 6 % on
+  // 512^3); when every wave is resident at once it only makes the last strip's waves the
+  // slowest ones (7 % lost on a 256^3 volume of i.i.d. values), so small launches keep one
+  // row group per wave.
+  const bool many_rounds = (long long)t.nstrip * t.ngroup * batch * D >= 160000;  // about 1.3 rounds of 30-plane units
+  if (many_rounds && wt + 2 <= kWave / 2) {
+    t.S = wt + 2;
+    t.F = kWave / t.S;
+    if (t.F > 8) t.F = 8;
+    if (t.F > t.ngroup) t.F = t.ngroup;
+    if (t.F == 1) t.S = kWave;
+  }
+  t.ngroupT = (t.ngroup + t.F - 1) / t.F;
+  t.full = (t.nstrip - 1) * t.ngroup4;
+  t.units_seg = t.full + ((t.ngroupT + 3) & ~3);
+  return t;
+}
+// unit -> (segment, strip, first row group, is it a last-strip unit, has it any row)
+__host__ __device__ __forceinline__ void decode_unit3(const Tiling3& t, int unit, int& seg, int& strip, int& group,
+                                                      bool& tail, bool& active) {
+  seg = unit / t.units_seg;
+  const int r = unit - seg * t.units_seg;
+  tail = r >= t.full;
+  if (tail) {
+    strip = t.nstrip - 1;
+    const int gt = r - t.full;
+    group = gt * t.F;
+    active = gt < t.ngroupT;
+  } else {
+    strip = r / t.ngroup4;
+    group = r - strip * t.ngroup4;
+    active = group < t.ngroup;
+  }
+}
+
+// Work unit of a wave: (z segment, row group(s), column strip) of one item;
 // blockIdx.y is the item; the four waves of a block take consecutive row groups
 // of one strip, so their halo rows meet in the CU's vector cache and their halo
 // words are swapped through LDS.
@@ -513,25 +584,24 @@ __device__ __forceinline__ void sweep3d_wave(const T* __restrict__ g, int D, int
                                              int nstrip, int ngroup, int nseg, int planes_per_seg,
                                              s3::TubeQueue<Sink>& queue, unsigned* xch, WaveRange& range,
                                              const TiltT& tilt) {
-  // unit = ((seg * nstrip) + strip) * ngroup4 + group, group fastest
-  const int ngroup4 = (ngroup + 3) & ~3;
+  const Tiling3 tl = make_tiling3(D, H, W, gridDim.y, R);
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform
-  const int group = unit % ngroup4;
-  const int rest = unit / ngroup4;
-  const int strip = rest % nstrip;
-  const int seg = rest / nstrip;
+  int seg, strip, group;
+  bool tail, active;
+  decode_unit3(tl, unit, seg, strip, group, tail, active);
   const int z0 = seg * planes_per_seg;
   const int z1 = min(z0 + planes_per_seg, D);
-  if (group < ngroup && seg < nseg) {
+  if (active && seg < nseg) {
     const int xs = strip * s3::kOut - 1;
     const int yb = group * R;
     // the four waves of a block are four consecutive row groups of one strip and segment
     const bool skip_top = (unit & 3) != 0;
     const bool skip_bottom = (unit & 3) != 3 && group + 1 < ngroup;
-    const bool safe = (xs < 0) || (xs + kWave > W) || (yb == 0) || (yb + R + 1 > H);
+    const bool safe = tail || (xs < 0) || (xs + kWave > W) || (yb == 0) || (yb + R + 1 > H);
     // tubes touching the grid boundary compute their own halo words (one variant fewer)
     if (safe)
-      s3::sweep_tube<T, R, Sink, true, false, false, TiltT>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range, tilt);
+      s3::sweep_tube<T, R, Sink, true, false, false, TiltT>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range, tilt,
+                                                            tail ? tl.S : kWave, tail ? tl.F : 1);
     else if (skip_top && skip_bottom)
       s3::sweep_tube<T, R, Sink, false, true, true, TiltT>(g, N, D, H, W, xs, yb, z0, z1, queue, xch, range, tilt);
     else if (skip_top)
@@ -559,10 +629,10 @@ static Plan3d plan3d(const Shape& s) {
   constexpr int R = kRows3d;
   Plan3d p;
   const int D = (int)s.D, H = (int)s.H, W = (int)s.W;
-  p.nstrip = (W + s3::kOut - 1) / s3::kOut;
-  p.ngroup = (H + R - 1) / R;
-  const int ngroup4 = (p.ngroup + 3) & ~3;
-  const int64_t per_seg = (int64_t)p.nstrip * p.ngroup * s.batch;
+  const Tiling3 tl = make_tiling3(D, H, W, s.batch, R);
+  p.nstrip = tl.nstrip;
+  p.ngroup = tl.ngroup;
+  const int64_t per_seg = (int64_t)tl.units_seg * s.batch;
   // about 2.5 rounds of waves over the chip on 512^3 (60-plane segments); measured best
   // between the ragged last round of fewer, longer segments and the three extra planes
   // every segment reads
@@ -579,7 +649,7 @@ static Plan3d plan3d(const Shape& s) {
   if (planes > fit) planes = fit;
   p.planes_per_seg = (int)planes;
   p.nseg = (int)((D + p.planes_per_seg - 1) / p.planes_per_seg);
-  const int64_t units = (int64_t)p.nseg * p.nstrip * ngroup4;
+  const int64_t units = (int64_t)p.nseg * tl.units_seg;
   p.grid = dim3((unsigned)(units / 4), (unsigned)s.batch);
   return p;
 }
