@@ -348,13 +348,13 @@ bool soft2d_supported(const Shape& s, int T) {
 
 size_t soft2d_workspace_bytes(const Shape& s, int T) {
   if (!soft2d_supported(s, T)) return 0;
-  const Plan2d pl = plan2d<float>(s);
+  const Plan2d pl = plan2d<float>(s, true);
   return (size_t)256 + (size_t)s.batch * pl.nstrip * pl.nseg * (size_t)T * 4 * sizeof(float);
 }
 
 void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
                        int T, float lambda, float* chi, void* ws, hipStream_t st, bool tiltc) {
-  const Plan2d pl = plan2d<float>(s);
+  const Plan2d pl = plan2d<float>(s, true);
   float* partial = static_cast<float*>(ws);
   if (tiltc)
     hipLaunchKernelGGL(soft2d_fwd_kernel<true>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
@@ -369,7 +369,7 @@ void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float 
 void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
                        int T, float lambda, const float* gup, float* grad_X, float* dtau, float* du,
                        void* ws, hipStream_t st, bool tiltc) {
-  const Plan2d pl = plan2d<float>(s);
+  const Plan2d pl = plan2d<float>(s, true);
   float* partial = (dtau || du) ? static_cast<float*>(ws) : nullptr;
   if (tiltc)
     hipLaunchKernelGGL(soft2d_bwd_kernel<true>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,

@@ -33,6 +33,8 @@
 // wave copies each row as it becomes current (re-reading them from memory
 // would miss the L2 once per critical vertex, a 128-byte line for 4 bytes).
 #pragma once
+#include <algorithm>
+
 #include "ecc_device.h"
 #include "ecc_internal.h"
 
@@ -407,21 +409,36 @@ struct Plan2d {
   int nstrip, nseg, rows_per_seg;
   dim3 grid;
 };
+// sigmoid_sinks: the plan of the soft path, whose sinks do their work wave by wave and want
+// many short segments; the hard path's sweeps are measured best as below.
 template <typename T>
-static Plan2d plan2d(const Shape& s) {
+static Plan2d plan2d(const Shape& s, bool sigmoid_sinks = false) {
   Plan2d p;
   const int H = (int)s.H, W = (int)s.W;
   p.nstrip = (W + kStripOut - 1) / kStripOut;
-  // enough wave units to fill 256 CUs several times over, segments of >= 16 rows
-  // (measured on 16 x 4096^2: 7 rounds of waves over the chip beat 3 rounds of longer
-  // segments by 5 %: the ragged last round costs more than the extra warm-up rows)
-  const int64_t target = 32768;
-  int64_t nseg = (target + (int64_t)p.nstrip * s.batch - 1) / ((int64_t)p.nstrip * s.batch);
-  // at least 16 rows per segment (24 when that still leaves two rounds of waves: a
-  // segment reads five rows more than it puts out)
   const int64_t tubes = (int64_t)p.nstrip * s.batch;
-  const int64_t max_seg = tubes * ((H + 23) / 24) >= 8192 ? (H + 23) / 24 : (H + 15) / 16;
-  if (nseg > max_seg) nseg = max_seg;
+  int64_t nseg;
+  if (sigmoid_sinks) {
+    // enough wave units to fill 256 CUs several times over, segments of >= 16 rows (24 when
+    // that still leaves two rounds of waves: a segment reads five rows more than it puts out)
+    nseg = (32768 + tubes - 1) / tubes;
+    const int64_t max_seg = tubes * ((H + 23) / 24) >= 8192 ? (H + 23) / 24 : (H + 15) / 16;
+    if (nseg > max_seg) nseg = max_seg;
+  } else if (tubes * ((H + 15) / 16) <= 1024) {
+    // at most one wave per SIMD even with the shortest segments: the call is as long as one
+    // wave's march, so the segments are as short as they come
+    nseg = (H + 15) / 16;
+  } else {
+    // Measured (rows per segment against time): a batch of 16 x 4096^2 is flat from 24 to 64
+    // rows and loses beyond 96; one 4096^2 image gains 30 % from 24 -> 64, one 2048^2 image
+    // 20 % from 16 -> 32, batches of 256^2 ... 512^2 images 25-30 % from 16 -> 32 ... 64.  Aim
+    // at about 1536 waves, within 32 ... 64 rows per segment.
+    const int64_t want = std::max<int64_t>(1, 1536 / tubes);
+    int64_t rows = (H + want - 1) / want;
+    rows = (rows + kChunkRows - 1) / kChunkRows * kChunkRows;
+    rows = rows < 32 ? 32 : (rows > 64 ? 64 : rows);
+    nseg = (H + rows - 1) / rows;
+  }
   if (nseg < 1) nseg = 1;
   // whole chunks per segment; segment + prefetch must stay below 2^31 bytes
   int64_t rows = (H + nseg - 1) / nseg;
