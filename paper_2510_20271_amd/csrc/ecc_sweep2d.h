@@ -436,7 +436,11 @@ static Plan2d plan2d(const Shape& s, bool sigmoid_sinks = false) {
     const int64_t want = std::max<int64_t>(1, 1536 / tubes);
     int64_t rows = (H + want - 1) / want;
     rows = (rows + kChunkRows - 1) / kChunkRows * kChunkRows;
-    rows = rows < 32 ? 32 : (rows > 64 ? 64 : rows);
+    // plenty of tubes (a large batch of small images): up to 128 rows, but two segments per image at least
+    // (1024 x 224^2: 0.112 -> 0.085 ms with 2 x 112 rows; 2048 x 128^2 loses 17 % with one segment of 128)
+    int64_t longest = 64;
+    if (tubes >= 1024) longest = std::max<int64_t>(64, std::min<int64_t>(128, ((H + 1) / 2 + kChunkRows - 1) / kChunkRows * kChunkRows));
+    rows = rows < 32 ? 32 : (rows > longest ? longest : rows);
     nseg = (H + rows - 1) / rows;
   }
   if (nseg < 1) nseg = 1;
