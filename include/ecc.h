@@ -11,7 +11,14 @@
  *
  * Every entry point validates its arguments on the host BEFORE the first HIP
  * call and returns an ecc_status; ecc_last_error() gives a message for the
- * last failure on the calling thread.  Inputs must be finite (no NaN/Inf).
+ * last failure on the calling thread.
+ *
+ * Grid values must be finite.  This is NOT checked on the hot path (a test per
+ * vertex would cost the 3D sweep, which is bound by instruction issue, about
+ * 3 %): a NaN compares false with everything, so it ends up somewhere in the
+ * order and the curve is unspecified -- no fault, every access stays in bounds.
+ * A caller that cannot vouch for its data runs ecc_count_nonfinite() first (one
+ * read pass) and looks at the count when convenient.
  *
  * Complex convention (the paper's Background section, Eq. 1-3, leaves it
  * open; this library fixes it): grid points are the vertices of a cubical
@@ -52,9 +59,10 @@ typedef enum {
 
 typedef enum {
   ECC_OK = 0,
-  ECC_ERR_INVALID_ARG = -1, /* NULL pointer, bad ndim/dims/batch/bins/T/lambda/range/dtype */
+  ECC_ERR_INVALID_ARG = -1, /* NULL pointer, bad ndim/dims/batch/bins/T/lambda/dtype     */
   ECC_ERR_UNSUPPORTED = -2, /* valid request outside the built limits (see ECC_MAX_*)       */
   ECC_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than ecc_workspace_bytes()         */
+  ECC_ERR_RANGE = -4,       /* `range` argument: lo > hi, or lo / hi not finite             */
   ECC_ERR_DEVICE = -5       /* a HIP call failed; message holds hipGetErrorString           */
 } ecc_status;
 
@@ -79,7 +87,7 @@ size_t ecc_workspace_bytes(int ndim, const int64_t* dims /* host */, int64_t bat
  * The same for the hard curves with element type `dtype` (any ecc_dtype): adds the
  * room for the float32 copy of the grid that ECC_F16 .. ECC_I16 need.
  */
-size_t ecc_workspace_bytes_dtype(int ndim, const int64_t* dims /* host */, int64_t batch, int dtype,
+size_t ecc_workspace_bytes_dtype(int ndim, const int64_t* dims /* host */, int64_t batch, ecc_dtype dtype,
                                  int bins);
 
 /*
@@ -95,24 +103,33 @@ size_t ecc_workspace_bytes_dtype(int ndim, const int64_t* dims /* host */, int64
  *             range given (any dtype): t_b = float32(lo + (b+1)(hi-lo)/B)
  *               evaluated in float64, and t_{B-1} = float32(hi);
  *             NULL, integer dtype:  t_b = b   (one bin per level);
- *             NULL, floating dtype: lo, hi = min, max over the WHOLE batch
- *               (one extra read pass over the grid), then as above.
+ *             NULL, floating dtype: lo, hi = min, max over the WHOLE batch, then
+ *               as above.  (No extra read pass: the one sweep tracks the range
+ *               and lists the vertices with c != 0, which are binned afterwards;
+ *               a field so rough that more than one vertex in eight has c != 0
+ *               overflows the lists and is swept a second time.)
  *   curve   device out, int64 [batch][B]: curve[i][b] = ECC of item i at t_b.
  *           A point with X(p) > t_{B-1} is in no sublevel set and is dropped;
  *           a point with X(p) <= t_0 counts from bin 0.
  * The curve is exact (integer arithmetic end to end) and does not depend on
  * the tie-break.
  */
-int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype,
+int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype,
              int bins, const double* range, int64_t* curve, void* workspace,
              size_t workspace_bytes, void* hip_stream);
 
 /*
  * The coefficient map itself (Eq. 3): c_out[batch][N] int8, values in
  * [-3, 1] (2D) or [-5, 7] (3D).  Exposes the first step of ecc_hard and of
- * the soft path for inspection and tests.  Needs no workspace.
+ * the soft path for inspection and tests: shapes that the strip / tube sweeps
+ * of those paths take (rows of 8 elements or more) are computed by those very
+ * sweeps -- the map is cleared and the sweep writes c(p) at the vertices with
+ * c != 0 -- so the map shows, vertex by vertex, the stencil and the tie-break
+ * (equal values: the smaller C-order index first; -0 equals +0) that every
+ * other entry point runs.  Other shapes use a plain one-thread-per-vertex
+ * kernel.  Every element of c_out is written.  Needs no workspace.
  */
-int ecc_coeff(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype,
+int ecc_coeff(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype,
               int8_t* c_out, void* hip_stream);
 
 /*
@@ -187,7 +204,7 @@ int ecc_soft_bwd_tilted(const float* grid, int ndim, const int64_t* dims, int64_
  * outside the grid coming first, which is how it is computed.  Arguments,
  * thresholds, bins, output, workspace and errors: exactly as ecc_hard.
  */
-int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
+int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype, int bins,
                  const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
                  void* hip_stream);
 
@@ -212,7 +229,7 @@ int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch,
 #define ECC_TOPCELL 1
 #define ECC_SUBLEVEL 0
 #define ECC_SUPERLEVEL 1
-int ecc_hard_ex(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int construction,
+int ecc_hard_ex(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype, int construction,
                 int filtration, int bins, const double* range, int64_t* curve, void* workspace,
                 size_t workspace_bytes, void* hip_stream);
 
@@ -239,6 +256,35 @@ int ecc_hard_dir(const float* grid, int ndim, const int64_t* dims, int64_t batch
                  size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Number of grid elements that are NaN or +-Inf (the entry points above need
+ * finite values and do not check): *count (device, 8-byte aligned) receives
+ * the count over all n elements; 0 for the integer types.  One read pass on
+ * hip_stream; no workspace.  Any ecc_dtype.
+ */
+int ecc_count_nonfinite(const void* grid, int64_t n, ecc_dtype dtype, unsigned long long* count,
+                        void* hip_stream);
+
+/*
+ * Test aid (not part of the method): forces the fall-back kernels on shapes
+ * that would otherwise take the fast ones, so that tests can compare every
+ * path with the oracle on the same inputs.  `mask` is an OR of
+ *   ECC_FORCE_GENERIC     hard curves and ecc_coeff: the one-thread-per-vertex
+ *                         kernels for every shape;
+ *   ECC_FORCE_TWO_PASS    float grids without a range: a separate min / max
+ *                         pass over the grid, then the histogram-mode sweep,
+ *                         instead of the single pass that lists the critical
+ *                         vertices;
+ *   ECC_FORCE_SOFT_TILES  soft path: the tile kernels for every shape.
+ * 0 restores normal operation.  Returns the previous mask.  The setting is
+ * process-wide (one atomic word) and is read when a call is enqueued; results
+ * are the same on every path, only the kernels differ.
+ */
+#define ECC_FORCE_GENERIC 1u
+#define ECC_FORCE_TWO_PASS 2u
+#define ECC_FORCE_SOFT_TILES 4u
+unsigned ecc_debug_force(unsigned mask);
+
+/*
  * Measurement aid (not part of the method; Experiments section reports
  * "kernel execution times"): between ecc_profile_begin() and
  * ecc_profile_end() every ecc_hard call records a pair of HIP events around
@@ -246,8 +292,10 @@ int ecc_hard_dir(const float* grid, int ndim, const int64_t* dims, int64_t batch
  * path) on the call's own stream.  ecc_profile_end() waits for the recorded
  * events, stores the mean kernel duration in milliseconds and the number of
  * launches measured, destroys the events and switches recording off.
- * max_launches in 1..4096; launches beyond it are not recorded.  Host-side
- * state is process-global: do not use it from two threads at once.
+ * max_launches in 1..4096; launches beyond it are not recorded.  One
+ * recording at a time per process (a second ecc_profile_begin fails until
+ * ecc_profile_end); the state is guarded by a mutex, so calls from several
+ * threads are safe and all their sweeps land in the one recording.
  */
 int ecc_profile_begin(int max_launches);
 int ecc_profile_end(float* mean_ms /* host */, int* launches /* host */);

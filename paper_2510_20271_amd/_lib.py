@@ -47,6 +47,8 @@ SIGNATURES = {
     "ecc_hard_dir": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp, ctypes.c_int,
                                     ctypes.c_float, ctypes.c_int, ctypes.POINTER(ctypes.c_double), c_vp, c_vp,
                                     ctypes.c_size_t, c_vp]),
+    "ecc_count_nonfinite": (ctypes.c_int, [c_vp, c_i64, ctypes.c_int, c_vp, c_vp]),
+    "ecc_debug_force": (ctypes.c_uint, [ctypes.c_uint]),
     "ecc_profile_begin": (ctypes.c_int, [ctypes.c_int]),
     "ecc_profile_end": (ctypes.c_int, [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]),
 }

@@ -59,11 +59,35 @@ def ecc_workspace_bytes_dtype(item_shape, batch: int, dtype: int, bins: int) -> 
     return int(_lib.load().ecc_workspace_bytes_dtype(len(item_shape), _dims(item_shape), batch, dtype, bins))
 
 
+# Workspaces handed out when the caller passes none: one per (device, stream), grown on demand
+# and kept, so that repeated calls allocate nothing.  Calls on one stream run in order and may
+# share it; calls on different streams get different ones.
+_WS_CACHE = {}
+
+
+def _cached_workspace(need: int, device) -> torch.Tensor:
+    key = (torch.device(device).index, torch.cuda.current_stream().cuda_stream)
+    ws = _WS_CACHE.get(key)
+    if ws is None or ws.numel() < need:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+        _WS_CACHE[key] = ws
+    return ws
+
+
 def _workspace(item_shape, batch, n, device, workspace, dtype=ECC_F32):
-    need = ecc_workspace_bytes_dtype(item_shape, batch, dtype, n)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+        workspace = _cached_workspace(ecc_workspace_bytes_dtype(item_shape, batch, dtype, n), device)
     return workspace
+
+
+def _need_f32(grid, u, tau, ndim):
+    for name, t in (("grid", grid), ("u", u), ("tau", tau)):
+        if t.dtype != torch.float32:
+            raise ValueError(f"{name} must be float32, got {t.dtype}")
+    if grid.dim() != ndim + 1:
+        raise ValueError("grid must be [batch, *item_shape]")
+    if u.numel() != ndim:
+        raise ValueError(f"u must have {ndim} elements, got {u.numel()}")
 
 
 ECC_VERTEX, ECC_TOPCELL = 0, 1
@@ -138,8 +162,7 @@ def ecc_hard_dir(grid: torch.Tensor, ndim: int, u: torch.Tensor, alpha: float, b
     if curve is None:
         curve = torch.empty((ndir, batch, bins), dtype=torch.int64, device=grid.device)
     if workspace is None:
-        need = ecc_workspace_bytes_dir(item, batch, ndir, bins)
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=grid.device)
+        workspace = _cached_workspace(ecc_workspace_bytes_dir(item, batch, ndir, bins), grid.device)
     rng = None
     if range is not None:
         rng = (ctypes.c_double * 2)(float(range[0]), float(range[1]))
@@ -162,6 +185,7 @@ def ecc_coeff(grid: torch.Tensor, ndim: int, c_out=None):
 def ecc_soft_fwd(grid, ndim, u, alpha, tau, lam, chi=None, workspace=None, tilted_c=False):
     """tilted_c=True: c(p) of the tilted field X + alpha <u,p> (ecc_soft_fwd_tilted)."""
     _need_device(grid, u, tau, chi, workspace)
+    _need_f32(grid, u, tau, ndim)
     batch, item = grid.shape[0], tuple(grid.shape[1:])
     T = tau.numel()
     if chi is None:
@@ -174,17 +198,22 @@ def ecc_soft_fwd(grid, ndim, u, alpha, tau, lam, chi=None, workspace=None, tilte
 
 
 def ecc_soft_bwd(grid, ndim, u, alpha, tau, lam, grad_chi=None, grad_X=None, dchi_dtau=None,
-                 dchi_du=None, workspace=None, tilted_c=False):
-    """Returns (grad_X [batch,*item], dchi_dtau [batch,T], dchi_du [batch,T,ndim])."""
+                 dchi_du=None, workspace=None, tilted_c=False, skip=()):
+    """Returns (grad_X [batch,*item], dchi_dtau [batch,T], dchi_du [batch,T,ndim]).
+    skip: names among "grad_X", "dchi_dtau", "dchi_du" of outputs that are not wanted (the
+    library is handed NULL for them and None is returned in their place); not all three."""
     _need_device(grid, u, tau, grad_chi, grad_X, dchi_dtau, dchi_du, workspace)
+    _need_f32(grid, u, tau, ndim)
+    if grad_chi is not None and grad_chi.dtype != torch.float32:
+        raise ValueError("grad_chi must be float32")
     batch, item = grid.shape[0], tuple(grid.shape[1:])
     T = tau.numel()
     dev = grid.device
-    if grad_X is None:
+    if grad_X is None and "grad_X" not in skip:
         grad_X = torch.empty(grid.shape, dtype=torch.float32, device=dev)
-    if dchi_dtau is None:
+    if dchi_dtau is None and "dchi_dtau" not in skip:
         dchi_dtau = torch.empty((batch, T), dtype=torch.float32, device=dev)
-    if dchi_du is None:
+    if dchi_du is None and "dchi_du" not in skip:
         dchi_du = torch.empty((batch, T, ndim), dtype=torch.float32, device=dev)
     workspace = _workspace(item, batch, max(T, 1), dev, workspace)
     fn = _lib.load().ecc_soft_bwd_tilted if tilted_c else _lib.load().ecc_soft_bwd
@@ -192,6 +221,23 @@ def ecc_soft_bwd(grid, ndim, u, alpha, tau, lam, grad_chi=None, grad_X=None, dch
               _ptr(grad_chi), _ptr(grad_X), _ptr(dchi_dtau), _ptr(dchi_du), _ptr(workspace),
               workspace.numel(), _stream()))
     return grad_X, dchi_dtau, dchi_du
+
+
+def ecc_count_nonfinite(grid: torch.Tensor, count=None):
+    """Number of NaN / Inf elements of a device tensor, as a device int64 scalar tensor (no sync)."""
+    _need_device(grid, count)
+    if count is None:
+        count = torch.empty((), dtype=torch.int64, device=grid.device)
+    _check(_lib.load().ecc_count_nonfinite(_ptr(grid), grid.numel(), _DTYPES[grid.dtype], _ptr(count), _stream()))
+    return count
+
+
+ECC_FORCE_GENERIC, ECC_FORCE_TWO_PASS, ECC_FORCE_SOFT_TILES = 1, 2, 4
+
+
+def ecc_debug_force(mask: int) -> int:
+    """Test aid: force the fall-back kernels (OR of ECC_FORCE_*; 0 = normal).  Returns the previous mask."""
+    return int(_lib.load().ecc_debug_force(int(mask)))
 
 
 def ecc_profile_begin(max_launches: int = 256):

@@ -6,9 +6,13 @@
 #include <cstdarg>
 #include <cstdio>
 
+#include <atomic>
+
 #include "ecc_internal.h"
 
 namespace {
+
+std::atomic<unsigned> g_forced{0u};
 
 thread_local char g_err[512] = "";
 
@@ -84,6 +88,12 @@ int check_soft_common(const float* grid, const float* u, float alpha, const floa
   if (!(lambda > 0.0f) || !std::isfinite(lambda))
     return fail(ECC_ERR_INVALID_ARG, "lambda must be finite and > 0");
   if (!std::isfinite(alpha)) return fail(ECC_ERR_INVALID_ARG, "alpha must be finite");
+  if ((reinterpret_cast<uintptr_t>(grid) | reinterpret_cast<uintptr_t>(u) | reinterpret_cast<uintptr_t>(tau)) & 3)
+    return fail(ECC_ERR_INVALID_ARG, "grid / u / tau is not 4-byte aligned");
+  return ECC_OK;
+}
+int check_f32_out(const void* p, const char* name) {
+  if (reinterpret_cast<uintptr_t>(p) & 3) return fail(ECC_ERR_INVALID_ARG, "%s is not 4-byte aligned", name);
   return ECC_OK;
 }
 
@@ -97,7 +107,16 @@ int check_workspace(void* ws, size_t have, size_t need) {
 
 }  // namespace
 
+namespace ecc {
+unsigned forced_paths() { return g_forced.load(std::memory_order_relaxed); }
+}  // namespace ecc
+
 extern "C" {
+
+unsigned ecc_debug_force(unsigned mask) {
+  return g_forced.exchange(mask & (ECC_FORCE_GENERIC | ECC_FORCE_TWO_PASS | ECC_FORCE_SOFT_TILES),
+                           std::memory_order_relaxed);
+}
 
 const char* ecc_last_error(void) { return g_err; }
 
@@ -115,7 +134,7 @@ size_t ecc_workspace_bytes(int ndim, const int64_t* dims, int64_t batch, int bin
   return a > b ? a : b;
 }
 
-size_t ecc_workspace_bytes_dtype(int ndim, const int64_t* dims, int64_t batch, int dtype, int bins) {
+size_t ecc_workspace_bytes_dtype(int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype, int bins) {
   ecc::Shape s;
   if (make_shape(ndim, dims, batch, &s) != ECC_OK) return 0;
   if (!converted_dtype(dtype) && check_dtype(dtype) != ECC_OK) return 0;
@@ -140,7 +159,7 @@ static int hard_common(int conv, const char* who, const void* grid, int ndim, co
     lo = range[0];
     hi = range[1];
     if (!std::isfinite(lo) || !std::isfinite(hi) || lo > hi)
-      return fail(ECC_ERR_INVALID_ARG, "range must be finite with lo <= hi");
+      return fail(ECC_ERR_RANGE, "range must be finite with lo <= hi");
   }
   if (reinterpret_cast<uintptr_t>(grid) % dtype_size(dtype))
     return fail(ECC_ERR_INVALID_ARG, "grid is not aligned to its element size");
@@ -172,21 +191,21 @@ static int hard_common(int conv, const char* who, const void* grid, int ndim, co
                        who);
 }
 
-int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
+int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype, int bins,
              const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
              void* hip_stream) {
   return hard_common(0, "ecc_hard", grid, ndim, dims, batch, dtype, bins, range, curve, workspace, workspace_bytes,
                      hip_stream);
 }
 
-int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
+int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype, int bins,
                  const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
                  void* hip_stream) {
   return hard_common(ecc::kConvTop, "ecc_hard_top", grid, ndim, dims, batch, dtype, bins, range, curve, workspace, workspace_bytes,
                      hip_stream);
 }
 
-int ecc_hard_ex(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int construction,
+int ecc_hard_ex(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype, int construction,
                 int filtration, int bins, const double* range, int64_t* curve, void* workspace,
                 size_t workspace_bytes, void* hip_stream) {
   if (construction != ECC_VERTEX && construction != ECC_TOPCELL)
@@ -231,7 +250,7 @@ int ecc_hard_dir(const float* grid, int ndim, const int64_t* dims, int64_t batch
     lo = range[0];
     hi = range[1];
     if (!std::isfinite(lo) || !std::isfinite(hi) || lo > hi)
-      return fail(ECC_ERR_INVALID_ARG, "range must be finite with lo <= hi");
+      return fail(ECC_ERR_RANGE, "range must be finite with lo <= hi");
   }
   if (reinterpret_cast<uintptr_t>(grid) % 4 || reinterpret_cast<uintptr_t>(u) % 4)
     return fail(ECC_ERR_INVALID_ARG, "grid / u is not 4-byte aligned");
@@ -246,7 +265,7 @@ int ecc_hard_dir(const float* grid, int ndim, const int64_t* dims, int64_t batch
                        "ecc_hard_dir");
 }
 
-int ecc_coeff(const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype,
+int ecc_coeff(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype,
               int8_t* c_out, void* hip_stream) {
   ecc::Shape s;
   int rc = make_shape(ndim, dims, batch, &s);
@@ -269,6 +288,7 @@ static int soft_fwd_common(const char* who, bool tiltc, const float* grid, int n
   if (rc != ECC_OK) return rc;
   if ((rc = check_soft_common(grid, u, alpha, tau, T, lambda)) != ECC_OK) return rc;
   if (!chi) return fail(ECC_ERR_INVALID_ARG, "chi is NULL");
+  if ((rc = check_f32_out(chi, "chi")) != ECC_OK) return rc;
   if ((rc = check_workspace(workspace, workspace_bytes, ecc::soft_workspace_bytes(s, T))) != ECC_OK)
     return rc;
   return device_status(ecc::launch_soft_fwd(grid, s, u, alpha, tau, T, lambda, chi, workspace,
@@ -286,6 +306,9 @@ static int soft_bwd_common(const char* who, bool tiltc, const float* grid, int n
   if ((rc = check_soft_common(grid, u, alpha, tau, T, lambda)) != ECC_OK) return rc;
   if (!grad_X && !dchi_dtau && !dchi_du)
     return fail(ECC_ERR_INVALID_ARG, "all three outputs are NULL");
+  if ((rc = check_f32_out(grad_chi, "grad_chi")) != ECC_OK || (rc = check_f32_out(grad_X, "grad_X")) != ECC_OK ||
+      (rc = check_f32_out(dchi_dtau, "dchi_dtau")) != ECC_OK || (rc = check_f32_out(dchi_du, "dchi_du")) != ECC_OK)
+    return rc;
   if ((rc = check_workspace(workspace, workspace_bytes, ecc::soft_workspace_bytes(s, T))) != ECC_OK)
     return rc;
   return device_status(
@@ -322,6 +345,19 @@ int ecc_soft_bwd_tilted(const float* grid, int ndim, const int64_t* dims, int64_
                         size_t workspace_bytes, void* hip_stream) {
   return soft_bwd_common("ecc_soft_bwd_tilted", true, grid, ndim, dims, batch, u, alpha, tau, T, lambda,
                          grad_chi, grad_X, dchi_dtau, dchi_du, workspace, workspace_bytes, hip_stream);
+}
+
+int ecc_count_nonfinite(const void* grid, int64_t n, ecc_dtype dtype, unsigned long long* count,
+                        void* hip_stream) {
+  if (!converted_dtype(dtype) && check_dtype(dtype) != ECC_OK) return ECC_ERR_INVALID_ARG;
+  if (!grid) return fail(ECC_ERR_INVALID_ARG, "grid is NULL");
+  if (!count) return fail(ECC_ERR_INVALID_ARG, "count is NULL");
+  if (n < 1 || n > kMaxVertices) return fail(ECC_ERR_INVALID_ARG, "n must be in 1 .. 2^40, got %lld", (long long)n);
+  if (reinterpret_cast<uintptr_t>(grid) % dtype_size(dtype))
+    return fail(ECC_ERR_INVALID_ARG, "grid is not aligned to its element size");
+  if (reinterpret_cast<uintptr_t>(count) % 8) return fail(ECC_ERR_INVALID_ARG, "count is not 8-byte aligned");
+  return device_status(ecc::launch_count_nonfinite(grid, n, dtype, count, static_cast<hipStream_t>(hip_stream)),
+                       "ecc_count_nonfinite");
 }
 
 int ecc_profile_begin(int max_launches) {

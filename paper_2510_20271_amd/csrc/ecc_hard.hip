@@ -12,6 +12,8 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <atomic>
+#include <mutex>
 
 namespace ecc {
 
@@ -248,6 +250,8 @@ __global__ __launch_bounds__(kBlock) void coeff_kernel(const T* __restrict__ gri
 // sweep-kernel timing with HIP events on the caller's stream
 // ---------------------------------------------------------------------------
 namespace {
+std::mutex g_prof_mutex;
+std::atomic<bool> g_prof_on{false};
 struct Profile {
   bool on = false;
   int cap = 0, used = 0;
@@ -256,6 +260,7 @@ struct Profile {
 }  // namespace
 
 hipError_t profile_begin(int max_launches) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
   if (g_prof.on) return hipErrorInvalidValue;
   g_prof.ev = new hipEvent_t[2 * (size_t)max_launches];
   for (int i = 0; i < 2 * max_launches; ++i) {
@@ -270,16 +275,20 @@ hipError_t profile_begin(int max_launches) {
   g_prof.cap = max_launches;
   g_prof.used = 0;
   g_prof.on = true;
+  g_prof_on.store(true, std::memory_order_release);
   return hipSuccess;
 }
 
 void profile_mark(hipStream_t st, bool after) {
+  if (!g_prof_on.load(std::memory_order_acquire)) return;  // the usual case: nothing is being recorded
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
   if (!g_prof.on || g_prof.used >= g_prof.cap) return;
   (void)hipEventRecord(g_prof.ev[2 * g_prof.used + (after ? 1 : 0)], st);
   if (after) ++g_prof.used;
 }
 
 hipError_t profile_end(float* mean_ms, int* launches) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
   if (!g_prof.on) return hipErrorInvalidValue;
   hipError_t rc = hipSuccess;
   double sum = 0.0;
@@ -295,6 +304,7 @@ hipError_t profile_end(float* mean_ms, int* launches) {
   for (int i = 0; i < 2 * g_prof.cap; ++i) (void)hipEventDestroy(g_prof.ev[i]);
   delete[] g_prof.ev;
   g_prof = Profile();
+  g_prof_on.store(false, std::memory_order_release);
   return rc;
 }
 
@@ -368,10 +378,10 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
   const bool levels = !have_range && !is_float;
   const bool device_range = !have_range && is_float;
   const int64_t total = s.N * s.batch;
-  // ECC_FORCE_GENERIC=1 routes every shape through the plain one-thread-per-vertex sweep,
-  // ECC_TWO_PASS=1 keeps the separate range pass for float grids without a range
-  static const bool force_generic = getenv("ECC_FORCE_GENERIC") != nullptr;
-  static const bool two_pass = getenv("ECC_TWO_PASS") != nullptr;
+  // test aid (ecc_debug_force): every shape through the plain one-thread-per-vertex sweep, and / or
+  // the separate range pass for float grids without a range
+  const bool force_generic = (forced_paths() & kForceGeneric) != 0;
+  const bool two_pass = (forced_paths() & kForceTwoPass) != 0;
   // With the thresholds known up front, inputs of up to 2^16 vertices are quicker through
   // the one-thread-per-vertex sweep: a strip / tube wave marching alone is bound by its own
   // instruction latency (256^2 uint8: 11.7 against 19.5 us).
@@ -515,6 +525,41 @@ __global__ __launch_bounds__(kBlock) void convert_kernel(const S* __restrict__ s
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = to_f32<S>(src[i]);
 }
 
+// ---------------------------------------------------------------------------
+// NaN / Inf census (the sweeps need finite values and do not check)
+// ---------------------------------------------------------------------------
+__global__ void clear_u64_kernel(unsigned long long* p) { *p = 0ull; }
+
+// EXP: the exponent field's mask in the element's bit pattern (all ones: NaN or Inf)
+template <typename U, U EXP>
+__global__ __launch_bounds__(kBlock) void count_nonfinite_kernel(const U* __restrict__ bits, int64_t n,
+                                                                 unsigned long long* __restrict__ count) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  unsigned bad = 0;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) bad += (bits[i] & EXP) == EXP;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) bad += __shfl_xor(bad, o);
+  if ((threadIdx.x & (kWave - 1)) == 0 && bad) atomicAdd(count, (unsigned long long)bad);
+}
+
+hipError_t launch_count_nonfinite(const void* grid, int64_t n, int dtype, unsigned long long* count, hipStream_t st) {
+  hipLaunchKernelGGL(clear_u64_kernel, dim3(1), dim3(1), 0, st, count);
+  int64_t nb = (n + kBlock - 1) / kBlock;
+  nb = nb > 8192 ? 8192 : nb;
+#define ECC_GO(U, EXP)                                                                                     \
+  hipLaunchKernelGGL((count_nonfinite_kernel<U, EXP>), dim3((unsigned)nb), dim3(kBlock), 0, st,            \
+                     static_cast<const U*>(grid), n, count)
+  switch (dtype) {
+    case 2: ECC_GO(uint32_t, 0x7f800000u); break;             // float32
+    case 3: ECC_GO(uint16_t, (uint16_t)0x7c00u); break;       // float16
+    case 5: ECC_GO(uint64_t, 0x7ff0000000000000ull); break;   // float64
+    case 6: ECC_GO(uint16_t, (uint16_t)0x7f80u); break;       // bfloat16
+    default: break;                                           // integer types: nothing to count
+  }
+#undef ECC_GO
+  return hipGetLastError();
+}
+
 hipError_t launch_convert(const void* grid, int dtype, int64_t n, float* out, hipStream_t st) {
   int64_t nb = (n + kBlock - 1) / kBlock;
   nb = nb < 1 ? 1 : (nb > 16384 ? 16384 : nb);
@@ -531,7 +576,34 @@ hipError_t launch_convert(const void* grid, int dtype, int64_t n, float* out, hi
   return hipGetLastError();
 }
 
+// out[0..n) = 0, any alignment
+__global__ __launch_bounds__(kBlock) void clear_i8_kernel(int8_t* __restrict__ out, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t lead = min<int64_t>(n, (int64_t)((16 - (reinterpret_cast<uintptr_t>(out) & 15)) & 15));
+  const int64_t n16 = (n - lead) / 16;
+  uint4* body = reinterpret_cast<uint4*>(out + lead);
+  for (int64_t i = tid; i < n16; i += stride) body[i] = make_uint4(0u, 0u, 0u, 0u);
+  for (int64_t i = tid; i < lead; i += stride) out[i] = 0;
+  for (int64_t i = lead + n16 * 16 + tid; i < n; i += stride) out[i] = 0;
+}
+
+// Shapes the strip / tube sweeps take go through them (the map is cleared, the sweep writes the
+// critical vertices), so that the map shows the stencil every timed path runs; the rest, and
+// every shape under ECC_FORCE_GENERIC, through the one-thread-per-vertex kernel.
 hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st) {
+  const bool force_generic = (forced_paths() & kForceGeneric) != 0;
+  const bool fast2d = !force_generic && sweep2d_supported(s, 1);
+  const bool fast3d = !force_generic && !fast2d && sweep3d_supported(s, 1);
+  if (fast2d || fast3d) {
+    const int64_t total = s.N * s.batch;
+    int64_t nb = (total / 16 + kBlock - 1) / kBlock;
+    nb = nb < 1 ? 1 : (nb > 4096 ? 4096 : nb);
+    hipLaunchKernelGGL(clear_i8_kernel, dim3((unsigned)nb), dim3(kBlock), 0, st, c_out, total);
+    if (fast2d) launch_coeff2d(grid, s, dtype, c_out, st);
+    else launch_coeff3d(grid, s, dtype, c_out, st);
+    return hipGetLastError();
+  }
   dim3 g(blocks_for(s.N), (unsigned)s.batch);
 #define ECC_GO(T, ND)                                                                          \
   hipLaunchKernelGGL((coeff_kernel<T, ND>), g, dim3(kBlock), 0, st, static_cast<const T*>(grid), \

@@ -32,8 +32,17 @@ hipError_t launch_hard_dir(const float* grid, const Shape& sv, const float* u, f
 // element types beyond uint8 / uint16 / float32 (codes 3..7 of ecc_dtype): n elements rounded to float32
 hipError_t launch_convert(const void* grid, int dtype, int64_t n, float* out, hipStream_t st);
 hipError_t launch_coeff(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st);
+// *count = number of NaN / Inf among n elements of type `dtype` (any ecc_dtype code)
+hipError_t launch_count_nonfinite(const void* grid, int64_t n, int dtype, unsigned long long* count, hipStream_t st);
+// the coefficient map through the strip / tube sweep (the map must have been cleared)
+void launch_coeff2d(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st);
+void launch_coeff3d(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st);
 
-// fast sweeps (one wave per column strip, lane-mask stencil)
+// Paths forced by ecc_debug_force (bits ECC_FORCE_* of include/ecc.h); 0 in normal operation.
+constexpr unsigned kForceGeneric = 1u, kForceTwoPass = 2u, kForceSoftTiles = 4u;
+unsigned forced_paths();
+
+// fast sweeps (one wave per column strip / tube, bit-sliced stencil)
 struct HardHeader;
 // single-pass mode: per-item lists of critical vertices (value, c) in the workspace
 struct ListArgs {

@@ -320,15 +320,13 @@ size_t soft_workspace_bytes(const Shape& s, int T) {
   return std::max(a, std::max(b, c));
 }
 
-// ECC_SOFT_TILES=1 keeps the tile kernels of this file for every shape
+// test aid (ecc_debug_force): the tile kernels of this file for every shape
 static bool use_soft2d(const Shape& s, int T) {
-  static const bool tiles_only = getenv("ECC_SOFT_TILES") != nullptr;
-  return !tiles_only && soft2d_supported(s, T);
+  return !(forced_paths() & kForceSoftTiles) && soft2d_supported(s, T);
 }
 
 static bool use_soft3d(const Shape& s, int T) {
-  static const bool tiles_only = getenv("ECC_SOFT_TILES") != nullptr;
-  return !tiles_only && soft3d_supported(s, T);
+  return !(forced_paths() & kForceSoftTiles) && soft3d_supported(s, T);
 }
 
 static float kneg_of(float lambda) { return (float)(-(double)lambda * 1.4426950408889634); }

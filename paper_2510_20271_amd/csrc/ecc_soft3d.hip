@@ -144,18 +144,6 @@ __device__ __forceinline__ void soft3_lds(int* smem, unsigned*& xch, s3::TubeQue
   stage = reinterpret_cast<Soft3Entry*>(smem + kXchInts + 4 * kQueueCap * 3) + wv * kWave;
 }
 
-// origin of a wave's unit (the numbering of ecc_sweep3d.h)
-__host__ __device__ __forceinline__ void unit_origin(int unit, int D, int H, int W, long long batch,
-                                                     int planes_per_seg, int R, int& ox, int& oy, int& oz) {
-  const Tiling3 tl = make_tiling3(D, H, W, batch, R);
-  int seg, strip, group;
-  bool tail, active;
-  decode_unit3(tl, unit, seg, strip, group, tail, active);
-  ox = strip * s3::kOut - 1;
-  oy = group * R;
-  oz = seg * planes_per_seg;
-}
-
 // partial[(item * units + unit) * T + j]
 // TILTC: the sweep runs on the tilted field, so c(p) is that field's coefficient
 template <bool TILTC>
@@ -174,7 +162,7 @@ __global__ __launch_bounds__(256) void soft3d_fwd_kernel(const float* __restrict
   for (int t = 0; t < kSoft3TL; ++t) queue.sink.acc[t] = 0.f;
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int ox, oy;
-  unit_origin(unit, D, H, W, gridDim.y, planes_per_seg, kRows3d, ox, oy, queue.sink.oz);
+  unit_origin3(unit, D, H, W, gridDim.y, planes_per_seg, kRows3d, ox, oy, queue.sink.oz);
   WaveRange range;
   const float* g = grid + (int64_t)blockIdx.y * N;
   if constexpr (TILTC) {
@@ -222,7 +210,7 @@ __global__ __launch_bounds__(256) void soft3d_bwd_kernel(const float* __restrict
   s.plane = (int64_t)H * W;
   s.lambda = lambda;
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  unit_origin(unit, D, H, W, gridDim.y, planes_per_seg, kRows3d, s.ox, s.oy, s.oz);
+  unit_origin3(unit, D, H, W, gridDim.y, planes_per_seg, kRows3d, s.ox, s.oy, s.oz);
   WaveRange range;
   const float* g = grid + (int64_t)blockIdx.y * N;
   if constexpr (TILTC) {
@@ -289,7 +277,7 @@ __global__ __launch_bounds__(kRedWaves * kWave) void soft3d_bwd_reduce_kernel(
   double s0 = 0.0, sx = 0.0, sy = 0.0, sz = 0.0;
   auto add = [&](int q, const float4& e) {
     int ox, oy, oz;
-    unit_origin(q, D, H, W, gridDim.y, planes_per_seg, kRows3d, ox, oy, oz);
+    unit_origin3(q, D, H, W, gridDim.y, planes_per_seg, kRows3d, ox, oy, oz);
     const double a0 = (double)e.x;
     s0 += a0;
     sx += (double)ox * a0 + (double)e.y;

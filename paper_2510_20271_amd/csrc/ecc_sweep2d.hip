@@ -160,4 +160,54 @@ void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, in
   }
 }
 
+// Coefficient map through the strip sweep: the critical vertices' c(p) written to an int8
+// map that the caller has cleared (every other vertex has c = 0).  The same stencil, order
+// and tie-break as every other strip-sweep kernel, made visible vertex by vertex.
+struct CoeffSink2d {
+  typedef int4 Entry;  // (column, row, c, -)
+  static constexpr bool kTrackRange = false;
+  static constexpr bool kZeroFill = false;
+  int8_t* out;  // this item's map
+  int W;
+  static __device__ __forceinline__ Entry make(float, int c, int col, int row) { return make_int4(col, row, c, 0); }
+  __device__ __forceinline__ void consume(const Entry* buf, int n) {
+    const int lane = threadIdx.x & (kWave - 1);
+    if (lane >= n) return;
+    const Entry e = buf[lane];
+    out[(int64_t)e.y * W + e.x] = (int8_t)e.z;
+  }
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void coeff2d_kernel(const T* __restrict__ grid, int H, int W, int64_t N,
+                                                      int nstrip, int nseg, int rows_per_seg,
+                                                      int8_t* __restrict__ out) {
+  extern __shared__ int smem[];
+  const int wv = threadIdx.x >> 6;
+  float* ring = reinterpret_cast<float*>(smem) + wv * (kChunkRows * kWave * kNC);
+  int4* qbuf = reinterpret_cast<int4*>(smem + 4 * kChunkRows * kWave * kNC) + wv * kQueueCap;
+  WaveQueue<CoeffSink2d> queue;
+  queue.buf = qbuf;
+  queue.count = 0;
+  queue.sink.out = out + (int64_t)blockIdx.y * N;
+  queue.sink.W = W;
+  WaveRange range;
+  sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range, NoTilt());
+}
+
+template <typename T>
+static void launch_coeff2d_t(const void* grid, const Shape& s, int8_t* out, hipStream_t st) {
+  const Plan2d pl = plan2d<T>(s);
+  hipLaunchKernelGGL((coeff2d_kernel<T>), pl.grid, dim3(256), ring_bytes2d<int4>(), st, static_cast<const T*>(grid),
+                     (int)s.H, (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, out);
+}
+
+void launch_coeff2d(const void* grid, const Shape& s, int dtype, int8_t* out, hipStream_t st) {
+  switch (dtype) {
+    case 0: launch_coeff2d_t<uint8_t>(grid, s, out, st); break;
+    case 1: launch_coeff2d_t<uint16_t>(grid, s, out, st); break;
+    default: launch_coeff2d_t<float>(grid, s, out, st); break;
+  }
+}
+
 }  // namespace ecc

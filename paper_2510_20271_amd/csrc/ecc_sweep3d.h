@@ -575,6 +575,18 @@ __host__ __device__ __forceinline__ void decode_unit3(const Tiling3& t, int unit
   }
 }
 
+// origin of a wave's unit: first column of the tube (its halo column), first output row, first plane
+__host__ __device__ __forceinline__ void unit_origin3(int unit, int D, int H, int W, long long batch,
+                                                      int planes_per_seg, int R, int& ox, int& oy, int& oz) {
+  const Tiling3 tl = make_tiling3(D, H, W, batch, R);
+  int seg, strip, group;
+  bool tail, active;
+  decode_unit3(tl, unit, seg, strip, group, tail, active);
+  ox = strip * s3::kOut - 1;
+  oy = group * R;
+  oz = seg * planes_per_seg;
+}
+
 // Work unit of a wave: (z segment, row group(s), column strip) of one item;
 // blockIdx.y is the item; the four waves of a block take consecutive row groups
 // of one strip, so their halo rows meet in the CU's vector cache and their halo

@@ -157,4 +157,53 @@ void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, in
   }
 }
 
+// Coefficient map through the tube sweep: the critical vertices' c(p) written to an int8 map
+// that the caller has cleared.  The same stencil, order and tie-break as every other
+// tube-sweep kernel, made visible vertex by vertex.
+struct CoeffSink3d {
+  static constexpr bool kTrackRange = false;
+  int8_t* out;    // this item's map
+  int64_t plane;  // H * W
+  int oz;         // first plane of the wave's segment
+  __device__ __forceinline__ void take(int n, float, int c, unsigned inpl, unsigned zrel) {
+    const int lane = threadIdx.x & (kWave - 1);
+    if (lane < n) out[(int64_t)(oz + (int)zrel) * plane + inpl] = (int8_t)c;
+  }
+};
+
+template <typename T, int R>
+__global__ __launch_bounds__(256) void coeff3d_kernel(const T* __restrict__ grid, int D, int H, int W, int64_t N,
+                                                      int nstrip, int ngroup, int nseg, int planes_per_seg,
+                                                      int8_t* __restrict__ out) {
+  extern __shared__ int smem[];
+  unsigned* xch = reinterpret_cast<unsigned*>(smem);
+  s3::TubeQueue<CoeffSink3d> queue;
+  queue.buf = reinterpret_cast<uint2*>(smem + kXchInts) + (threadIdx.x >> 6) * kQueueCap;
+  queue.tbuf = reinterpret_cast<float*>(smem + kXchInts + 4 * kQueueCap * 2) + (threadIdx.x >> 6) * kQueueCap;
+  queue.count = 0;
+  queue.sink.out = out + (int64_t)blockIdx.y * N;
+  queue.sink.plane = (int64_t)H * W;
+  const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int ox, oy;
+  unit_origin3(unit, D, H, W, gridDim.y, planes_per_seg, R, ox, oy, queue.sink.oz);
+  WaveRange range;
+  sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg, queue, xch,
+                     range, NoTilt());
+}
+
+template <typename T>
+static void launch_coeff3d_t(const void* grid, const Shape& s, int8_t* out, hipStream_t st) {
+  const Plan3d pl = plan3d<T>(s);
+  hipLaunchKernelGGL((coeff3d_kernel<T, kRows3d>), pl.grid, dim3(256), kFixedLds3d, st, static_cast<const T*>(grid),
+                     (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg, out);
+}
+
+void launch_coeff3d(const void* grid, const Shape& s, int dtype, int8_t* out, hipStream_t st) {
+  switch (dtype) {
+    case 0: launch_coeff3d_t<uint8_t>(grid, s, out, st); break;
+    case 1: launch_coeff3d_t<uint16_t>(grid, s, out, st); break;
+    default: launch_coeff3d_t<float>(grid, s, out, st); break;
+  }
+}
+
 }  // namespace ecc

@@ -35,12 +35,17 @@ class SoftECCFunction(torch.autograd.Function):
     def backward(ctx, grad_chi):
         grid, u, tau = ctx.saved_tensors
         g = grad_chi.contiguous().float()
+        need_x, need_u, need_tau = ctx.needs_input_grad[:3]
+        if not (need_x or need_u or need_tau):
+            return None, None, None, None, None, None
+        # only the outputs autograd asks for are computed (with fixed inputs and learnable
+        # thresholds, the usual case, the image-sized grad_X is neither allocated nor written)
+        skip = [n for n, need in (("grad_X", need_x), ("dchi_du", need_u), ("dchi_dtau", need_tau)) if not need]
         grad_X, dtau, du = api.ecc_soft_bwd(grid, ctx.ndim, u, ctx.alpha, tau, ctx.lam, grad_chi=g,
-                                            tilted_c=ctx.tilted_c)
-        grad_grid = grad_X if ctx.needs_input_grad[0] else None
-        grad_u = torch.einsum("bj,bjd->d", g, du) if ctx.needs_input_grad[1] else None
-        grad_tau = (g * dtau).sum(0) if ctx.needs_input_grad[2] else None
-        return grad_grid, grad_u, grad_tau, None, None, None
+                                            tilted_c=ctx.tilted_c, skip=skip)
+        grad_u = torch.einsum("bj,bjd->d", g, du) if need_u else None
+        grad_tau = (g * dtau).sum(0) if need_tau else None
+        return grad_X, grad_u, grad_tau, None, None, None
 
 
 def soft_ecc(grid, u, tau, alpha: float, lam: float, tilted_c: bool = False):

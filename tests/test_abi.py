@@ -49,7 +49,7 @@ def test_workspace_bytes_host_only():
     assert big >= 32 * 128 * 128 * 16
 
 
-INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+INVALID, UNSUPPORTED, WORKSPACE, RANGE = -1, -2, -3, -4
 
 
 @pytest.mark.parametrize("kw,status,word", [
@@ -62,8 +62,9 @@ INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
     (dict(curve=None), INVALID, "curve"),
     (dict(bins=0), INVALID, "bins"),
     (dict(bins=1 << 20), UNSUPPORTED, "bins"),
-    (dict(range=(2.0, 1.0)), INVALID, "range"),
-    (dict(range=(float("nan"), 1.0)), INVALID, "range"),
+    (dict(range=(2.0, 1.0)), RANGE, "range"),
+    (dict(range=(float("nan"), 1.0)), RANGE, "range"),
+    (dict(range=(0.0, float("inf"))), RANGE, "range"),
     (dict(ws=None), WORKSPACE, "workspace"),
     (dict(ws_bytes=8), WORKSPACE, "workspace"),
     (dict(ws=ctypes.c_void_p(0x1004)), WORKSPACE, "aligned"),
@@ -132,6 +133,9 @@ def test_hard_rejects_null_dims():
     (dict(alpha=float("nan")), INVALID, "alpha"),
     (dict(out=None), INVALID, "NULL"),
     (dict(ws_bytes=16), WORKSPACE, "workspace"),
+    (dict(grid=ctypes.c_void_p(0x1002)), INVALID, "aligned"),
+    (dict(tau=ctypes.c_void_p(0x1001)), INVALID, "aligned"),
+    (dict(out=ctypes.c_void_p(0x1002)), INVALID, "aligned"),
 ])
 def test_soft_rejects_bad_arguments(kw, status, word):
     lib = _lib.load()
@@ -157,7 +161,7 @@ def test_soft_rejects_bad_arguments(kw, status, word):
     (dict(alpha=float("inf")), INVALID, "alpha"),
     (dict(bins=0), INVALID, "bins"),
     (dict(bins=1 << 20), UNSUPPORTED, "bins"),
-    (dict(range=(3.0, 1.0)), INVALID, "range"),
+    (dict(range=(3.0, 1.0)), RANGE, "range"),
     (dict(ws_bytes=8), WORKSPACE, "workspace"),
     (dict(u=ctypes.c_void_p(0x1002)), INVALID, "aligned"),
 ])
@@ -190,6 +194,21 @@ def test_coeff_rejects_bad_arguments():
     assert lib.ecc_coeff(None, 2, _dims(4, 4), 1, 0, FAKE, None) == INVALID
     assert lib.ecc_coeff(FAKE, 2, _dims(4, 4), 1, 0, None, None) == INVALID
     assert lib.ecc_coeff(FAKE, 5, _dims(4, 4), 1, 0, FAKE, None) == INVALID
+
+
+def test_count_nonfinite_and_debug_force_host_side():
+    lib = _lib.load()
+    assert lib.ecc_count_nonfinite(None, 16, 2, FAKE, None) == INVALID
+    assert lib.ecc_count_nonfinite(FAKE, 16, 2, None, None) == INVALID
+    assert lib.ecc_count_nonfinite(FAKE, 0, 2, FAKE, None) == INVALID
+    assert lib.ecc_count_nonfinite(FAKE, 16, 9, FAKE, None) == INVALID
+    assert lib.ecc_count_nonfinite(ctypes.c_void_p(0x1002), 16, 2, FAKE, None) == INVALID
+    assert lib.ecc_count_nonfinite(FAKE, 16, 2, ctypes.c_void_p(0x1004), None) == INVALID
+    # the switch of the fall-back paths: returns the previous mask, ignores unknown bits
+    assert lib.ecc_debug_force(3) == 0
+    assert lib.ecc_debug_force(0xff) == 3
+    assert lib.ecc_debug_force(0) == 7
+    assert lib.ecc_debug_force(0) == 0
 
 
 def test_product_package_never_imports_the_oracle():

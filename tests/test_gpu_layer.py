@@ -13,9 +13,7 @@ from tests.gpu_util import dev, host
 pytestmark = pytest.mark.gpu
 
 
-def _close(got, want, tol):
-    scale = max(np.abs(want).max(), 1e-30)
-    assert np.abs(got - want).max() <= tol * scale, (np.abs(got - want).max(), scale)
+from tests.test_gpu_soft import _close, _close_sum  # noqa: E402  (tolerances: see there)
 
 
 @pytest.mark.parametrize("shape", [(48, 60), (10, 20, 24)])
@@ -34,7 +32,7 @@ def test_autograd_gradients_match_the_oracle(shape):
     (chi * dev(gup)).sum().backward()
 
     want_chi = O.soft_fwd_batch(X, u, alpha, tau, lam)
-    _close(host(chi.detach()), want_chi, 1e-4)
+    _close_sum(host(chi.detach()), want_chi, 1e-4, "chi")
     gX = np.zeros(X.shape)
     g_tau = np.zeros(T)
     g_u = np.zeros(nd)
@@ -43,9 +41,9 @@ def test_autograd_gradients_match_the_oracle(shape):
         gX[b] = gx_b
         g_tau += gup[b] * dtau_b
         g_u += gup[b] @ du_b
-    _close(host(g.grad), gX, 1e-3)
-    _close(host(tt.grad), g_tau, 1e-3)
-    _close(host(ut.grad), g_u, 1e-3)
+    _close(host(g.grad), gX, 1e-3, "grad_X")
+    _close_sum(host(tt.grad), g_tau, 1e-3, "grad_tau")
+    _close_sum(host(ut.grad), g_u, 1e-3, "grad_u")
 
 
 def _setup():

@@ -1,8 +1,18 @@
 """GPU parity of the soft single-direction ECC (forward and derivatives)
 against the float64 CPU oracle, through the C ABI.
 
-Tolerance (per output array and batch item): max|gpu - oracle| <= tol *
-max|oracle|, tol = 1e-4 for chi and 1e-3 for each derivative array.
+The stated contract (per output array and batch item) is max|gpu - oracle| <= tol * max|oracle|
+with tol = 1e-4 for chi and 1e-3 for each derivative array.  The tests hold the kernels to what
+their float32 arithmetic delivers, a tenth of that (1e-5 / 1e-4), and add an element-wise check:
+|gpu_i - oracle_i| <= tol * max(|oracle_i|, floor * max|oracle|), i.e. the relative error of every
+element at the contract's tol, small elements measured against a floor.  For grad_X (one value per
+vertex, a sum over the thresholds only) the floor is 1e-3 of the largest element, which bounds the
+absolute error of every element by 1e-6 of the largest (a floor of 1e-4 would ask for 1e-7 of it,
+one float32 ulp of the largest element: a vertex whose threshold terms cancel misses that).  chi, dchi/dtau
+and dchi/du are sums over all vertices of signed float32 terms: such a sum is accurate relative to
+the sum of the terms' magnitudes (about 30 times the curve's own scale on these fields), not to its
+own value, which passes through zero along the curve (observed: 1.3e-6 of the largest element, at
+any element); their elements are measured against at least 5 % of the largest.
 """
 import numpy as np
 import pytest
@@ -16,11 +26,27 @@ from tests.gpu_util import dev, host
 pytestmark = pytest.mark.gpu
 
 
-def _close(got, ref, tol, what):
+TIGHT = 0.1   # norm-wise: a tenth of the contract's tolerance
+FLOOR = 1e-3      # element-wise: |oracle_i| is taken as at least FLOOR * max|oracle| ...
+SUM_FLOOR = 5e-2  # ... and at least this for the outputs that are sums over all vertices
+
+
+def _close_sum(got, ref, tol, what):
+    """chi, dchi/dtau, dchi/du: cancelling sums over all vertices."""
+    _close(got, ref, tol, what, floor=SUM_FLOOR)
+
+
+def _close(got, ref, tol, what, floor=FLOOR):
+    """tol is the contract's (1e-4 for chi, 1e-3 for a derivative array)."""
     got = np.asarray(got, dtype=np.float64)
-    scale = np.max(np.abs(ref))
-    err = np.max(np.abs(got - ref))
-    assert err <= tol * max(scale, 1e-30), f"{what}: err {err:.3e} scale {scale:.3e}"
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = max(float(np.max(np.abs(ref))), 1e-30)
+    err = np.abs(got - ref)
+    assert err.max() <= TIGHT * tol * scale, f"{what}: max err {err.max():.3e}, max|oracle| {scale:.3e}"
+    rel = err / np.maximum(np.abs(ref), floor * scale)
+    k = int(np.argmax(rel))
+    assert rel.max() <= tol, (f"{what}: element {k}: gpu {got.ravel()[k]:.6e} oracle {ref.ravel()[k]:.6e} "
+                              f"relative {rel.max():.3e} (max|oracle| {scale:.3e})")
 
 
 def _run_case(Xb, u, alpha, tau, lam, G):
@@ -32,10 +58,10 @@ def _run_case(Xb, u, alpha, tau, lam, G):
     ref_chi = O.soft_fwd_batch(Xb, u, alpha, tau, lam)
     rgx, rdt, rdu = O.soft_bwd_batch(Xb, u, alpha, tau, lam, G)
     for i in range(Xb.shape[0]):
-        _close(chi[i], ref_chi[i], 1e-4, f"chi[{i}]")
+        _close_sum(chi[i], ref_chi[i], 1e-4, f"chi[{i}]")
         _close(gx[i], rgx[i], 1e-3, f"grad_X[{i}]")
-        _close(dt[i], rdt[i], 1e-3, f"dchi_dtau[{i}]")
-        _close(du[i], rdu[i], 1e-3, f"dchi_du[{i}]")
+        _close_sum(dt[i], rdt[i], 1e-3, f"dchi_dtau[{i}]")
+        _close_sum(du[i], rdu[i], 1e-3, f"dchi_du[{i}]")
     return chi, gx, dt, du
 
 
@@ -90,6 +116,34 @@ def test_soft_large_lambda_matches_hard_curve():
     np.testing.assert_allclose(chi, hard, atol=1e-3)
 
 
+def test_count_nonfinite():
+    x = np.random.default_rng(0).standard_normal(100003).astype(np.float32)
+    assert int(api.ecc_count_nonfinite(dev(x))) == 0
+    x[[5, 77, 99999]] = [np.nan, np.inf, -np.inf]
+    assert int(api.ecc_count_nonfinite(dev(x))) == 3
+    assert int(api.ecc_count_nonfinite(dev(x.astype(np.float64)))) == 3
+    assert int(api.ecc_count_nonfinite(dev(x.astype(np.float16)))) == 3
+    assert int(api.ecc_count_nonfinite(dev(x).to(torch.bfloat16))) == 3
+    assert int(api.ecc_count_nonfinite(dev(np.arange(1000, dtype=np.int32)))) == 0
+
+
+def test_soft_skipped_outputs_and_binding_checks():
+    Xb = synth.grf_batch(2, (50, 60), 1.5, 5)
+    p = synth.soft_params_c5(Xb, T=16)
+    g, ud, td = dev(Xb), dev(p["u"]), dev(p["tau"])
+    full = api.ecc_soft_bwd(g, 2, ud, p["alpha"], td, p["lam"])
+    gx, dt, du = api.ecc_soft_bwd(g, 2, ud, p["alpha"], td, p["lam"], skip=("grad_X", "dchi_du"))
+    assert gx is None and du is None and torch.equal(dt, full[1])
+    gx, dt, du = api.ecc_soft_bwd(g, 2, ud, p["alpha"], td, p["lam"], skip=("dchi_dtau",))
+    assert dt is None and torch.equal(gx, full[0]) and torch.equal(du, full[2])
+    with pytest.raises(ValueError):
+        api.ecc_soft_fwd(g.double(), 2, ud, p["alpha"], td, p["lam"])
+    with pytest.raises(ValueError):
+        api.ecc_soft_fwd(g, 2, dev(np.zeros(3, np.float32)), p["alpha"], td, p["lam"])
+    with pytest.raises(ValueError):
+        api.ecc_soft_bwd(g, 2, ud, p["alpha"], td.double(), p["lam"])
+
+
 def test_soft_optional_outputs_and_determinism():
     Xb = synth.grf_batch(2, (50, 60), 1.5, 5)
     p = synth.soft_params_c5(Xb, T=16)
@@ -142,4 +196,4 @@ def test_soft_3d_outputs_optional_and_grad_x_unaligned():
                                   lib_dt.data_ptr(), None, ws.data_ptr(), ws.numel(),
                                   torch.cuda.current_stream().cuda_stream)
     assert rc == 0
-    _close(host(lib_dt)[0], ref[1][0], 1e-3, "dchi_dtau alone")
+    _close_sum(host(lib_dt)[0], ref[1][0], 1e-3, "dchi_dtau alone")

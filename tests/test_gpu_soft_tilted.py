@@ -12,7 +12,7 @@ from oracle import ecc_oracle as O
 from paper_2510_20271_amd import api, synth
 from paper_2510_20271_amd.layer import SoftECCLayer
 from tests.gpu_util import dev, host
-from tests.test_gpu_soft import _close
+from tests.test_gpu_soft import _close, _close_sum
 
 pytestmark = pytest.mark.gpu
 
@@ -29,10 +29,10 @@ def _run_tilted(Xb, u, alpha, tau, lam, G, expect_other_c=True):
         differs |= not np.array_equal(c, O.coeff(X))
         ref_chi = O.soft_fwd(X, u, alpha, tau, lam, c=c)
         rgx, rdt, rdu = O.soft_bwd(X, u, alpha, tau, lam, G[i], c=c)
-        _close(chi[i], ref_chi, 1e-4, f"chi[{i}]")
+        _close_sum(chi[i], ref_chi, 1e-4, f"chi[{i}]")
         _close(gx[i], rgx, 1e-3, f"grad_X[{i}]")
-        _close(dt[i], rdt, 1e-3, f"dchi_dtau[{i}]")
-        _close(du[i], rdu, 1e-3, f"dchi_du[{i}]")
+        _close_sum(dt[i], rdt, 1e-3, f"dchi_dtau[{i}]")
+        _close_sum(du[i], rdu, 1e-3, f"dchi_du[{i}]")
     assert differs or not expect_other_c  # the case tells the two coefficients apart
 
 
@@ -97,7 +97,7 @@ def test_layer_with_tilted_coefficient():
     tau = layer.tau.detach().cpu().numpy()
     for i in range(2):
         x = X[i].cpu().numpy()
-        _close(chi[i].detach().cpu().numpy(), O.soft_fwd(x, u, 0.05, tau, 10.0, c=O.coeff_tilted(x, u, 0.05)),
+        _close_sum(chi[i].detach().cpu().numpy(), O.soft_fwd(x, u, 0.05, tau, 10.0, c=O.coeff_tilted(x, u, 0.05)),
                1e-4, "layer chi")
     chi.sum().backward()
     assert layer.tau.grad is not None and torch.isfinite(layer.tau.grad).all()
