@@ -119,6 +119,26 @@ int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc
              size_t workspace_bytes, void* hip_stream);
 
 /*
+ * ecc_hard for callers that cannot allocate device memory and have no workspace
+ * to pass: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, thresholds, output and errors as ecc_hard,
+ * minus the workspace: the scratch space is a static device array inside the
+ * library, ECC_STATIC_SCRATCH_BYTES long, one copy per GPU, held until the
+ * process ends.  The call allocates and frees nothing (the array's address on
+ * the current device is looked up once, on the first call on that device).
+ * A request whose workspace (ecc_workspace_bytes_dtype) would not fit returns
+ * ECC_ERR_UNSUPPORTED -- roughly one byte of scratch per float32 vertex, so
+ * about 32 M vertices per call, e.g. two 4096^2 images or 256^3 volumes.
+ * Every call on a GPU uses that GPU's one array: calls that may overlap in time
+ * on one GPU (different streams, different threads) race and must not be made;
+ * calls on one stream are ordered and safe.  Nothing needs to be cleared
+ * between calls (each call resets what it uses).
+ */
+#define ECC_STATIC_SCRATCH_BYTES (32u << 20)
+int ecc_hard_static(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype,
+                    int bins, const double* range, int64_t* curve, void* hip_stream);
+
+/*
  * The coefficient map itself (Eq. 3): c_out[batch][N] int8, values in
  * [-3, 1] (2D) or [-5, 7] (3D).  Exposes the first step of ecc_hard and of
  * the soft path for inspection and tests: shapes that the strip / tube sweeps

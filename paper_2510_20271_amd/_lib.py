@@ -22,6 +22,8 @@ SIGNATURES = {
     "ecc_hard": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, ctypes.c_int,
                                 ctypes.c_int, ctypes.POINTER(ctypes.c_double), c_vp, c_vp,
                                 ctypes.c_size_t, c_vp]),
+    "ecc_hard_static": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, ctypes.c_int,
+                                       ctypes.c_int, ctypes.POINTER(ctypes.c_double), c_vp, c_vp]),
     "ecc_hard_top": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, ctypes.c_int,
                                     ctypes.c_int, ctypes.POINTER(ctypes.c_double), c_vp, c_vp,
                                     ctypes.c_size_t, c_vp]),

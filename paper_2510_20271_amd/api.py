@@ -119,6 +119,23 @@ def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, w
     return curve
 
 
+def ecc_hard_static(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None):
+    """ecc_hard on the library's static scratch (no workspace, no allocation inside the library);
+    pass `curve` to keep this binding from allocating the output."""
+    _need_device(grid, curve)
+    if grid.dim() != ndim + 1:
+        raise ValueError("grid must be [batch, *item_shape]")
+    batch, item = grid.shape[0], tuple(grid.shape[1:])
+    if curve is None:
+        curve = torch.empty((batch, bins), dtype=torch.int64, device=grid.device)
+    rng = None
+    if range is not None:
+        rng = (ctypes.c_double * 2)(float(range[0]), float(range[1]))
+    _check(_lib.load().ecc_hard_static(_ptr(grid), ndim, _dims(item), batch, _DTYPES[grid.dtype], bins, rng,
+                                       _ptr(curve), _stream()))
+    return curve
+
+
 def ecc_hard_ex(grid: torch.Tensor, ndim: int, construction: int, filtration: int, bins: int, range=None,
                 curve=None, workspace=None):
     """The entry point with construction (ECC_VERTEX / ECC_TOPCELL) and filtration

@@ -7,12 +7,22 @@
 #include <cstdio>
 
 #include <atomic>
+#include <mutex>
 
 #include "ecc_internal.h"
+
+// Scratch of ecc_hard_static: device memory that belongs to the library, one copy per GPU,
+// held until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; kernels are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[ECC_STATIC_SCRATCH_BYTES];
 
 namespace {
 
 std::atomic<unsigned> g_forced{0u};
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // address of `scratch` on each device, looked up once
 
 thread_local char g_err[512] = "";
 
@@ -142,9 +152,29 @@ size_t ecc_workspace_bytes_dtype(int ndim, const int64_t* dims, int64_t batch, e
   return base ? base + convert_bytes(s, dtype) : 0;
 }
 
+// The current device's copy of `scratch`: looked up with hipGetSymbolAddress on the first call
+// on that device (no allocation: the array is part of the loaded code object).
+static int static_scratch(const char* who, void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return device_status(e, who);
+  if (dev < 0 || dev >= kMaxDevices) return fail(ECC_ERR_UNSUPPORTED, "%s: device index %d beyond %d", who, dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return device_status(e, who);
+    if (!p) return fail(ECC_ERR_DEVICE, "%s: hipGetSymbolAddress returned NULL", who);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return ECC_OK;
+}
+
+// use_static: the workspace is the library's static scratch (workspace / workspace_bytes ignored)
 static int hard_common(int conv, const char* who, const void* grid, int ndim, const int64_t* dims, int64_t batch, int dtype, int bins,
              const double* range, int64_t* curve, void* workspace, size_t workspace_bytes,
-             void* hip_stream) {
+             void* hip_stream, bool use_static = false) {
   ecc::Shape s;
   int rc = make_shape(ndim, dims, batch, &s);
   if (rc != ECC_OK) return rc;
@@ -166,8 +196,15 @@ static int hard_common(int conv, const char* who, const void* grid, int ndim, co
   if (reinterpret_cast<uintptr_t>(curve) % 8)
     return fail(ECC_ERR_INVALID_ARG, "curve is not 8-byte aligned");
   const size_t base_bytes = ecc::hard_workspace_bytes(s, bins);
-  if ((rc = check_workspace(workspace, workspace_bytes, base_bytes + convert_bytes(s, dtype))) != ECC_OK)
+  if (use_static) {
+    const size_t need = base_bytes + convert_bytes(s, dtype);
+    if (need > (size_t)ECC_STATIC_SCRATCH_BYTES)
+      return fail(ECC_ERR_UNSUPPORTED, "%s: this call needs %zu bytes of scratch, the static buffer has %zu "
+                  "(use ecc_hard with a workspace)", who, need, (size_t)ECC_STATIC_SCRATCH_BYTES);
+    if ((rc = static_scratch(who, &workspace)) != ECC_OK) return rc;
+  } else if ((rc = check_workspace(workspace, workspace_bytes, base_bytes + convert_bytes(s, dtype))) != ECC_OK) {
     return rc;
+  }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (converted_dtype(dtype)) {
     // rounded to float32 behind the path's own workspace, then the float32 path; one bin per level
@@ -196,6 +233,12 @@ int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc
              void* hip_stream) {
   return hard_common(0, "ecc_hard", grid, ndim, dims, batch, dtype, bins, range, curve, workspace, workspace_bytes,
                      hip_stream);
+}
+
+int ecc_hard_static(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype, int bins,
+                    const double* range, int64_t* curve, void* hip_stream) {
+  return hard_common(0, "ecc_hard_static", grid, ndim, dims, batch, dtype, bins, range, curve, nullptr, 0, hip_stream,
+                     true);
 }
 
 int ecc_hard_top(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc_dtype dtype, int bins,

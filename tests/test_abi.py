@@ -196,6 +196,17 @@ def test_coeff_rejects_bad_arguments():
     assert lib.ecc_coeff(FAKE, 5, _dims(4, 4), 1, 0, FAKE, None) == INVALID
 
 
+def test_hard_static_rejects_on_the_host():
+    lib = _lib.load()
+    assert lib.ecc_hard_static(None, 2, _dims(4, 4), 1, 0, 8, None, FAKE, None) == INVALID
+    assert lib.ecc_hard_static(FAKE, 2, _dims(4, 4), 1, 0, 0, None, FAKE, None) == INVALID
+    assert lib.ecc_hard_static(FAKE, 2, _dims(4, 4), 1, 0, 8, (ctypes.c_double * 2)(2.0, 1.0), FAKE, None) == RANGE
+    # more scratch than the static buffer holds: refused before any HIP call
+    assert lib.ecc_workspace_bytes(2, _dims(8192, 8192), 1, 8) > 32 << 20
+    assert lib.ecc_hard_static(FAKE, 2, _dims(8192, 8192), 1, 2, 8, None, FAKE, None) == UNSUPPORTED
+    assert "scratch" in lib.ecc_last_error().decode()
+
+
 def test_count_nonfinite_and_debug_force_host_side():
     lib = _lib.load()
     assert lib.ecc_count_nonfinite(None, 16, 2, FAKE, None) == INVALID
