@@ -215,8 +215,10 @@ def main():
         torch.cuda.empty_cache()
 
     # ---------------- C1 / C3: integer levels, one bin per level ----------------
-    if args.only == "" and not args.quick:
+    if (args.only == "" and not args.quick) or args.only in ("c1", "c3"):
         for name, X, nd, bins in (("c1", synth.config_c1()[None], 2, 256), ("c3", synth.config_c3()[None], 3, 4096)):
+            if args.only and args.only != name:
+                continue
             if X.dtype == np.uint16:
                 gi = torch.from_numpy(X.view(np.int16)).cuda().view(torch.uint16)
             else:
@@ -236,6 +238,8 @@ def main():
                            "gvoxel_per_s": round(X.size / msi / 1e6, 2)}
             log(f"[bench] {name}: {msi * 1e3:.1f} us/step, sweep {swi * 1e3:.1f} us")
             del gi
+        if args.only in ("c1", "c3"):
+            return
 
     # ---------------- directional curves: 16 directions of one 4096^2 field --------
     if args.only in ("", "dir") and (not args.quick or args.only == "dir"):
@@ -283,6 +287,16 @@ def main():
             api.ecc_soft_fwd(g5, 2, u5, p["alpha"], tau5, p["lam"], chi=chi, workspace=ws5)
             api.ecc_soft_bwd(g5, 2, u5, p["alpha"], tau5, p["lam"], grad_chi=G5, grad_X=gx, dchi_dtau=dt_,
                              dchi_du=du_, workspace=ws5)
+        st5 = torch.empty(api.ecc_soft_state_bytes(X5.shape[1:], X5.shape[0]), dtype=torch.uint8, device="cuda")
+
+        def step5s():
+            api.ecc_soft_fwd_save(g5, 2, u5, p["alpha"], tau5, p["lam"], chi=chi, dchi_dtau=dt_, dchi_du=du_, state=st5,
+                                  workspace=ws5)
+            api.ecc_soft_bwd_saved(g5, 2, u5, p["alpha"], tau5, p["lam"], st5, grad_chi=G5, grad_X=gx, workspace=ws5)
+        ms5s = time_steps(step5s, args.steps, args.warmup)
+        ms5sf = time_steps(lambda: api.ecc_soft_fwd_save(g5, 2, u5, p["alpha"], tau5, p["lam"], chi=chi, dchi_dtau=dt_,
+                                                         dchi_du=du_, state=st5, workspace=ws5), args.steps, args.warmup)
+        log(f"[bench] C5 soft saved-state: fwd_save+bwd_saved {ms5s:.4f} ms, fwd_save {ms5sf:.4f} ms")
         ms5 = time_steps(step5, args.steps, args.warmup)
         ms5f = time_steps(lambda: api.ecc_soft_fwd(g5, 2, u5, p["alpha"], tau5, p["lam"], chi=chi, workspace=ws5),
                           args.steps, args.warmup)

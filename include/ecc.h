@@ -193,6 +193,41 @@ int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Forward pass that saves state for the backward pass (a training step needs
+ * both; Methods, "Learning Setup").  Every term of Eq. 6 and Eq. 8-10 carries
+ * the factor c(p), so only the vertices with c != 0 matter, and the forward
+ * sweep has to find them anyway: ecc_soft_fwd_save leaves them -- position,
+ * c(p) and y = X(p) + alpha <u,p> -- in `state`, and ecc_soft_bwd_saved forms
+ * grad_X (Eq. 8 contracted with grad_chi) from that list alone, without
+ * sweeping the grid again.  The sums over p of Eq. 9 and Eq. 10 share their
+ * sigmoids with Eq. 6, so the forward call returns them as well:
+ *   ecc_soft_fwd_save   chi as ecc_soft_fwd (bit for bit); dchi_dtau, dchi_du as
+ *                       ecc_soft_bwd (either may be NULL); fills `state`
+ *   ecc_soft_bwd_saved  grad_X as ecc_soft_bwd (every element written)
+ * tilted != 0: c(p) of the tilted field (as ecc_soft_fwd_tilted).
+ *   state  device memory, 256-byte aligned, ecc_soft_state_bytes() long, owned by
+ *          the caller.  It needs no initialisation.  What it holds depends on
+ *          grid, dims, batch, u, alpha and `tilted` only -- tau, lambda and
+ *          grad_chi may differ between the two calls -- and the caller must pass
+ *          the same grid (unchanged), u and alpha to ecc_soft_bwd_saved.  A state
+ *          written for another shape, and an item with so many vertices of c != 0
+ *          (more than one in eight of some unit of rows) that its list overflowed,
+ *          are noticed on the device: those items are swept again, as ecc_soft_bwd
+ *          would, so the result is right either way.
+ * Shapes outside the fused 2D kernels (3D grids, T > 256) keep no state: the two
+ * calls then run ecc_soft_fwd + ecc_soft_bwd's kernels.  workspace as ecc_soft_fwd.
+ */
+size_t ecc_soft_state_bytes(int ndim, const int64_t* dims /* host */, int64_t batch);
+int ecc_soft_fwd_save(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
+                      float alpha, const float* tau, int T, float lambda, int tilted, float* chi,
+                      float* dchi_dtau, float* dchi_du, void* state, size_t state_bytes, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+int ecc_soft_bwd_saved(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
+                       float alpha, const float* tau, int T, float lambda, int tilted, const float* grad_chi,
+                       float* grad_X, const void* state, size_t state_bytes, void* workspace,
+                       size_t workspace_bytes, void* hip_stream);
+
+/*
  * Soft ECC with the coefficient of the TILTED field: Eq. 6 and Eq. 8-10 exactly
  * as in ecc_soft_fwd / ecc_soft_bwd, except that c(p) is the coefficient (Eq. 3)
  * of Y(p) = X(p) + alpha <u,p> instead of the coefficient of X.  Y is formed in
@@ -307,9 +342,9 @@ unsigned ecc_debug_force(unsigned mask);
 /*
  * Measurement aid (not part of the method; Experiments section reports
  * "kernel execution times"): between ecc_profile_begin() and
- * ecc_profile_end() every ecc_hard call records a pair of HIP events around
- * its sweep kernel (the coefficient + histogram pass that dominates the
- * path) on the call's own stream.  ecc_profile_end() waits for the recorded
+ * ecc_profile_end() every hard or soft call records a pair of HIP events around
+ * its sweep kernel (the coefficient + histogram / sigmoid pass that dominates
+ * the path; for ecc_soft_bwd_saved the list kernel) on the call's own stream.  ecc_profile_end() waits for the recorded
  * events, stores the mean kernel duration in milliseconds and the number of
  * launches measured, destroys the events and switches recording off.
  * max_launches in 1..4096; launches beyond it are not recorded.  One

@@ -38,6 +38,13 @@ SIGNATURES = {
     "ecc_soft_bwd": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp,
                                     ctypes.c_float, c_vp, ctypes.c_int, ctypes.c_float, c_vp, c_vp,
                                     c_vp, c_vp, c_vp, ctypes.c_size_t, c_vp]),
+    "ecc_soft_state_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.POINTER(c_i64), c_i64]),
+    "ecc_soft_fwd_save": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp, ctypes.c_float,
+                                         c_vp, ctypes.c_int, ctypes.c_float, ctypes.c_int, c_vp, c_vp, c_vp, c_vp,
+                                         ctypes.c_size_t, c_vp, ctypes.c_size_t, c_vp]),
+    "ecc_soft_bwd_saved": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp, ctypes.c_float,
+                                          c_vp, ctypes.c_int, ctypes.c_float, ctypes.c_int, c_vp, c_vp, c_vp,
+                                          ctypes.c_size_t, c_vp, ctypes.c_size_t, c_vp]),
     "ecc_soft_fwd_tilted": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_i64), c_i64, c_vp,
                                            ctypes.c_float, c_vp, ctypes.c_int, ctypes.c_float, c_vp, c_vp,
                                            ctypes.c_size_t, c_vp]),

@@ -240,6 +240,53 @@ def ecc_soft_bwd(grid, ndim, u, alpha, tau, lam, grad_chi=None, grad_X=None, dch
     return grad_X, dchi_dtau, dchi_du
 
 
+def ecc_soft_state_bytes(item_shape, batch: int) -> int:
+    return int(_lib.load().ecc_soft_state_bytes(len(item_shape), _dims(item_shape), batch))
+
+
+def ecc_soft_fwd_save(grid, ndim, u, alpha, tau, lam, chi=None, dchi_dtau=None, dchi_du=None, state=None,
+                      workspace=None, tilted_c=False, want=("dchi_dtau", "dchi_du")):
+    """Forward pass that also returns the threshold / direction derivatives named in `want` and
+    leaves the critical vertices in `state` for ecc_soft_bwd_saved.
+    Returns (chi, dchi_dtau or None, dchi_du or None, state)."""
+    _need_device(grid, u, tau, chi, dchi_dtau, dchi_du, state, workspace)
+    _need_f32(grid, u, tau, ndim)
+    batch, item = grid.shape[0], tuple(grid.shape[1:])
+    T = tau.numel()
+    dev = grid.device
+    if chi is None:
+        chi = torch.empty((batch, T), dtype=torch.float32, device=dev)
+    if dchi_dtau is None and "dchi_dtau" in want:
+        dchi_dtau = torch.empty((batch, T), dtype=torch.float32, device=dev)
+    if dchi_du is None and "dchi_du" in want:
+        dchi_du = torch.empty((batch, T, ndim), dtype=torch.float32, device=dev)
+    if state is None:
+        state = torch.empty(max(ecc_soft_state_bytes(item, batch), 256), dtype=torch.uint8, device=dev)
+    workspace = _workspace(item, batch, max(T, 1), dev, workspace)
+    _check(_lib.load().ecc_soft_fwd_save(_ptr(grid), ndim, _dims(item), batch, _ptr(u), float(alpha), _ptr(tau), T,
+                                         float(lam), int(bool(tilted_c)), _ptr(chi), _ptr(dchi_dtau), _ptr(dchi_du),
+                                         _ptr(state), state.numel(), _ptr(workspace), workspace.numel(), _stream()))
+    return chi, dchi_dtau, dchi_du, state
+
+
+def ecc_soft_bwd_saved(grid, ndim, u, alpha, tau, lam, state, grad_chi=None, grad_X=None, workspace=None,
+                       tilted_c=False):
+    """grad_X [batch, *item] from the state an ecc_soft_fwd_save call on the same grid, u, alpha left."""
+    _need_device(grid, u, tau, grad_chi, grad_X, state, workspace)
+    _need_f32(grid, u, tau, ndim)
+    if grad_chi is not None and grad_chi.dtype != torch.float32:
+        raise ValueError("grad_chi must be float32")
+    batch, item = grid.shape[0], tuple(grid.shape[1:])
+    T = tau.numel()
+    if grad_X is None:
+        grad_X = torch.empty(grid.shape, dtype=torch.float32, device=grid.device)
+    workspace = _workspace(item, batch, max(T, 1), grid.device, workspace)
+    _check(_lib.load().ecc_soft_bwd_saved(_ptr(grid), ndim, _dims(item), batch, _ptr(u), float(alpha), _ptr(tau), T,
+                                          float(lam), int(bool(tilted_c)), _ptr(grad_chi), _ptr(grad_X), _ptr(state),
+                                          state.numel(), _ptr(workspace), workspace.numel(), _stream()))
+    return grad_X
+
+
 def ecc_count_nonfinite(grid: torch.Tensor, count=None):
     """Number of NaN / Inf elements of a device tensor, as a device int64 scalar tensor (no sync)."""
     _need_device(grid, count)

@@ -360,6 +360,53 @@ static int soft_bwd_common(const char* who, bool tiltc, const float* grid, int n
       who);
 }
 
+size_t ecc_soft_state_bytes(int ndim, const int64_t* dims, int64_t batch) {
+  ecc::Shape s;
+  if (make_shape(ndim, dims, batch, &s) != ECC_OK) return 0;
+  return ecc::soft_state_bytes(s);
+}
+
+int ecc_soft_fwd_save(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u, float alpha,
+                      const float* tau, int T, float lambda, int tilted, float* chi, float* dchi_dtau,
+                      float* dchi_du, void* state, size_t state_bytes, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  ecc::Shape s;
+  int rc = make_shape(ndim, dims, batch, &s);
+  if (rc != ECC_OK) return rc;
+  if ((rc = check_soft_common(grid, u, alpha, tau, T, lambda)) != ECC_OK) return rc;
+  if (!chi) return fail(ECC_ERR_INVALID_ARG, "chi is NULL");
+  if ((rc = check_f32_out(chi, "chi")) != ECC_OK || (rc = check_f32_out(dchi_dtau, "dchi_dtau")) != ECC_OK ||
+      (rc = check_f32_out(dchi_du, "dchi_du")) != ECC_OK)
+    return rc;
+  if (!state || state_bytes < ecc::soft_state_bytes(s) || (reinterpret_cast<uintptr_t>(state) & 255))
+    return fail(ECC_ERR_WORKSPACE, "state must be 256-byte aligned and hold ecc_soft_state_bytes() = %zu bytes",
+                ecc::soft_state_bytes(s));
+  if ((rc = check_workspace(workspace, workspace_bytes, ecc::soft_workspace_bytes(s, T))) != ECC_OK) return rc;
+  return device_status(ecc::launch_soft_fwd_save(grid, s, u, alpha, tau, T, lambda, chi, dchi_dtau, dchi_du, state,
+                                                 workspace, static_cast<hipStream_t>(hip_stream), tilted != 0),
+                       "ecc_soft_fwd_save");
+}
+
+int ecc_soft_bwd_saved(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u, float alpha,
+                       const float* tau, int T, float lambda, int tilted, const float* grad_chi, float* grad_X,
+                       const void* state, size_t state_bytes, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  ecc::Shape s;
+  int rc = make_shape(ndim, dims, batch, &s);
+  if (rc != ECC_OK) return rc;
+  if ((rc = check_soft_common(grid, u, alpha, tau, T, lambda)) != ECC_OK) return rc;
+  if (!grad_X) return fail(ECC_ERR_INVALID_ARG, "grad_X is NULL");
+  if ((rc = check_f32_out(grad_chi, "grad_chi")) != ECC_OK || (rc = check_f32_out(grad_X, "grad_X")) != ECC_OK)
+    return rc;
+  if (!state || state_bytes < ecc::soft_state_bytes(s) || (reinterpret_cast<uintptr_t>(state) & 255))
+    return fail(ECC_ERR_WORKSPACE, "state must be 256-byte aligned and hold ecc_soft_state_bytes() = %zu bytes",
+                ecc::soft_state_bytes(s));
+  if ((rc = check_workspace(workspace, workspace_bytes, ecc::soft_workspace_bytes(s, T))) != ECC_OK) return rc;
+  return device_status(ecc::launch_soft_bwd_saved(grid, s, u, alpha, tau, T, lambda, grad_chi, grad_X, state, workspace,
+                                                  static_cast<hipStream_t>(hip_stream), tilted != 0),
+                       "ecc_soft_bwd_saved");
+}
+
 int ecc_soft_fwd(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
                  float alpha, const float* tau, int T, float lambda, float* chi, void* workspace,
                  size_t workspace_bytes, void* hip_stream) {

@@ -86,6 +86,41 @@ hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, fl
 
 void launch_clear_f32(float* p, int64_t n, hipStream_t st);  // p[0..n) = 0 (fill kernel)
 
+// ---- soft path with state saved for the backward pass --------------------------------
+// The forward pass leaves the critical vertices it found -- (y = X(p) + alpha <u,p>, position,
+// c(p)) -- in a caller-owned state buffer, one list per wave unit of its sweep (filled in sweep
+// order without atomics, so the contents are the same on every run), with the per-unit counts
+// and a header naming the shape and plan.  The backward pass for grad_X then runs over those
+// lists alone: no second sweep of the grid.  Layout: header | overflow flags [batch] | counts
+// [batch][units] | entries [batch][units][cap].
+struct SavedEntry {
+  double y;  // X(p) + alpha <u,p>
+  int idx;   // linear index of p inside its item
+  int c;
+};
+struct SoftStateHeader {
+  unsigned magic;
+  int H, W, batch, nstrip, nseg, rows_per_seg, tiltc;
+  unsigned cap;  // entries per unit
+};
+constexpr unsigned kSoftStateMagic = 0x45434353u;
+size_t soft_state_bytes(const Shape& s);  // 256 when no shape-specific state is kept
+// chi always; dtau / du may be null.  state: soft_state_bytes(s) bytes.
+hipError_t launch_soft_fwd_save(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
+                                int T, float lambda, float* chi, float* dtau, float* du, void* state, void* ws,
+                                hipStream_t st, bool tiltc);
+hipError_t launch_soft_bwd_saved(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
+                                 int T, float lambda, const float* gup, float* grad_X, const void* state, void* ws,
+                                 hipStream_t st, bool tiltc);
+// fused 2D implementation of the two (shapes soft2d_supported takes)
+size_t soft2d_state_bytes(const Shape& s);
+void launch_soft2d_fwd_save(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
+                            float lambda, float* chi, float* dtau, float* du, void* state, void* ws, hipStream_t st,
+                            bool tiltc);
+void launch_soft2d_bwd_saved(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
+                             float lambda, const float* gup, float* grad_X, const void* state, hipStream_t st,
+                             bool tiltc);
+
 // fused 2D soft path (strip sweep + sigmoid sinks)
 bool soft2d_supported(const Shape& s, int T);
 size_t soft2d_workspace_bytes(const Shape& s, int T);

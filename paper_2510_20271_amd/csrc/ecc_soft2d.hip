@@ -17,8 +17,11 @@
 // Each wave writes its partial sums to the workspace; a second kernel adds them
 // in a fixed order in float64, so results are run-to-run identical.
 //
-// z = tau_j - X(p) - alpha <u,p> is formed in float64 and rounded once; exp2 and
-// the reciprocal run on the float32 transcendental unit.
+// y = X(p) + alpha <u,p> is formed in float64 and carried as two floats (yh + yl), so that
+// z = (tau_j - yh) - yl is the float64 difference to within an ulp of z; exp2 and the
+// reciprocal run on the float32 transcendental unit.  An entry whose y lies so far outside
+// [min tau, max tau] that every sigmoid is 0 or 1 to 2^-64 is not evaluated at all: it adds
+// c to every threshold (sigma = 1) or nothing, and nothing to the derivatives.
 #include "ecc_sweep2d.h"
 
 namespace ecc {
@@ -30,8 +33,19 @@ __device__ __forceinline__ float soft_exp_neg(float z, float kneg) {
   return __builtin_amdgcn_exp2f(fminf(kneg * z, 126.0f));
 }
 
+constexpr float kSatLog2 = 64.0f;  // |lambda z| log2(e) beyond which sigma is 0 or 1 and sigma' is 0
+
+// Saturation bounds for thresholds in [lo, hi]: with k = lambda log2(e) = -kneg, sigma(tau - y) differs from
+// 1 by less than 2^-64 for y <= lo - 64/k and from 0 for y >= hi + 64/k (a little margin covers
+// the rounding of yh); sigma' is below 2^-64 lambda in both cases.
+__device__ __forceinline__ void soft_sat_bounds(float lo, float hi, float kneg, float& sat_lo, float& sat_hi) {
+  const float w = (kSatLog2 + 2.0f) / -kneg;
+  sat_lo = lo - w - 1e-6f * fabsf(lo);
+  sat_hi = hi + w + 1e-6f * fabsf(hi);
+}
+
 struct SoftEntry {
-  double y;  // X(p) + alpha <u,p>
+  float yh, yl;  // X(p) + alpha <u,p> = yh + yl
   float c;
   int col, row;
   int pad;
@@ -41,10 +55,11 @@ struct SoftCommon {
   typedef SoftEntry Entry;
   static constexpr bool kTrackRange = false;
   double ux, uy, alpha;
-  double tj[kSoftTL];  // this lane's thresholds
+  float tj[kSoftTL];  // this lane's thresholds
   int T;
   int nt;  // threshold slots in use: ceil(T / 64)
   float kneg;
+  float sat_lo, sat_hi;  // y <= sat_lo: every sigma is 1;  y >= sat_hi: every sigma is 0 (to 2^-64)
   // The sweep ran on the tilted field (c of the tilted field): the value it hands over
   // is the tilted one in float32; X is read again so that y is formed as always.
   const float* xsrc;  // this item's grid, or null when the sweep ran on X itself
@@ -52,7 +67,9 @@ struct SoftCommon {
   __device__ __forceinline__ Entry make(float v, int c, int col, int row) const {
     Entry e;
     if (xsrc) v = xsrc[(int64_t)row * xW + col];  // wave-uniform condition
-    e.y = (double)v + alpha * (ux * (double)col + uy * (double)row);
+    const double y = (double)v + alpha * (ux * (double)col + uy * (double)row);
+    e.yh = (float)y;
+    e.yl = (float)(y - (double)e.yh);
     e.c = (float)c;
     e.col = col;
     e.row = row;
@@ -69,31 +86,65 @@ struct SoftCommon {
     xsrc = nullptr;
     xW = 0;
     const int lane = threadIdx.x & (kWave - 1);
+    float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
     for (int t = 0; t < kSoftTL; ++t) {
       const int j = lane + kWave * t;
-      tj[t] = j < T ? (double)tau[j] : 0.0;
+      tj[t] = j < T ? tau[j] : 0.0f;
+      if (j < T) {
+        lo = fminf(lo, tj[t]);
+        hi = fmaxf(hi, tj[t]);
+      }
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      lo = fminf(lo, __shfl_xor(lo, o));
+      hi = fmaxf(hi, __shfl_xor(hi, o));
+    }
+    soft_sat_bounds(lo, hi, kneg_, sat_lo, sat_hi);
   }
+  // Packs the entries of buf[0..n) that have to be evaluated to the front of buf (a wave's LDS
+  // reads and writes execute in order: every lane has read its entry before any lane overwrites
+  // one) and returns how many there are; *csat receives the sum of c over the dropped entries whose
+  // sigmoids are all 1 (dropped entries whose sigmoids are all 0 add nothing).
+  __device__ __forceinline__ int drop_saturated(Entry* buf, int n, float* csat) const {
+    const int lane = threadIdx.x & (kWave - 1);
+    Entry e = buf[lane < n ? lane : 0];
+    const bool in = lane < n;
+    const bool keep = in && e.yh > sat_lo && e.yh < sat_hi;
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(keep);
+    const int kept = __builtin_popcountll(m);
+    if (kept == n) return n;  // wave-uniform: nothing to drop
+    if (csat) {
+      const float ones = wave_sum_lane63((in && e.yh <= sat_lo) ? e.c : 0.0f);
+      *csat += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, ones), kWave - 1));
+    }
+    const int pos = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+    if (keep) buf[pos] = e;
+    return kept;
+  }
+  __device__ __forceinline__ float zarg(int t, float yh, float yl) const { return (tj[t] - yh) - yl; }
 };
 
 struct SoftFwdSink : SoftCommon {
   static constexpr bool kZeroFill = false;
   float acc[kSoftTL];
-  __device__ __forceinline__ void consume(const Entry* buf, int n) {
+  float csat;  // sum of c over the entries whose sigmoids are all 1 (wave-uniform)
+  __device__ __forceinline__ void consume(Entry* buf, int n) {
+    n = drop_saturated(buf, n, &csat);
     for (int e = 0; e < n; ++e) {
-      const double y = buf[e].y;
+      const float yh = buf[e].yh, yl = buf[e].yl;
       const float c = buf[e].c;
 #pragma unroll
       for (int t = 0; t < kSoftTL; ++t) {
         if (t < nt) {  // wave-uniform
-          const float z = (float)(tj[t] - y);
-          const float ex = soft_exp_neg(z, kneg);
+          const float ex = soft_exp_neg(zarg(t, yh, yl), kneg);
           acc[t] += c * __builtin_amdgcn_rcpf(1.0f + ex);
         }
       }
     }
   }
+  __device__ __forceinline__ float total(int t) const { return acc[t] + csat; }
 };
 
 struct SoftBwdSink : SoftCommon {
@@ -121,18 +172,18 @@ struct SoftBwdSink : SoftCommon {
   // One pass over entries x thresholds serves all three derivatives: lane l holds
   // sigma'(z) / lambda for its thresholds; the sums over p stay in the lane, the
   // contraction with the upstream gradient (Eq. 8) is a fixed-order sum over the lanes.
-  __device__ __forceinline__ void consume(const Entry* buf, int n) {
+  __device__ __forceinline__ void consume(Entry* buf, int n) {
     const int lane = threadIdx.x & (kWave - 1);
+    n = drop_saturated(buf, n, nullptr);  // sigma' < 2^-64 lambda at every threshold; grad_X stays 0 there
     for (int e = 0; e < n; ++e) {
-      const double y = buf[e].y;
+      const float yh = buf[e].yh, yl = buf[e].yl;
       const float c = buf[e].c;
       const float rx = (float)(buf[e].col - col0), ry = (float)(buf[e].row - row0);
       float gd = 0.0f;
 #pragma unroll
       for (int t = 0; t < kSoftTL; ++t) {
         if (t < nt) {  // wave-uniform
-          const float z = (float)(tj[t] - y);
-          const float ex = soft_exp_neg(z, kneg);
+          const float ex = soft_exp_neg(zarg(t, yh, yl), kneg);
           const float s = __builtin_amdgcn_rcpf(1.0f + ex);
           const float d = ex * s * s;  // sigma (1 - sigma)
           const float cd = c * d;
@@ -149,6 +200,50 @@ struct SoftBwdSink : SoftCommon {
     }
   }
 };
+
+// ---- state saved by the forward pass for the backward pass -----------------------------------
+// Header as ecc_internal.h describes it, followed by a generation number: every saving forward
+// pass raises it by one (its reduction kernel does, after the sweep), and a unit that runs out
+// of room writes the generation it belongs to into its item's overflow word.  An item's lists
+// are usable when the header matches the shape and that word is not the current generation --
+// so nothing in the state ever needs clearing, whatever it held before.
+struct StateView {
+  SoftStateHeader* hdr;
+  unsigned* gen;       // generation of the lists the state holds
+  unsigned* overflow;  // [batch]: generation in which a unit of the item last ran out of room
+  unsigned* counts;    // [batch][units]: critical vertices each unit found (may exceed cap)
+  SavedEntry* lists;   // [batch][units][cap]
+};
+static size_t align256(size_t n) { return (n + 255) / 256 * 256; }
+static unsigned state_cap(const Plan2d& pl) {
+  // room for one vertex in eight of a unit's rows x 248 columns (64 entries at least)
+  const unsigned v = (unsigned)pl.rows_per_seg * (unsigned)kStripOut / 8u;
+  return (v < 64u ? 64u : v);
+}
+static StateView state_view(void* state, const Shape& s, const Plan2d& pl) {
+  char* b = static_cast<char*>(state);
+  const size_t units = (size_t)pl.nstrip * pl.nseg;
+  StateView v;
+  v.hdr = reinterpret_cast<SoftStateHeader*>(b);
+  v.gen = reinterpret_cast<unsigned*>(b + 128);
+  v.overflow = reinterpret_cast<unsigned*>(b + 256);
+  v.counts = reinterpret_cast<unsigned*>(b + 256 + align256((size_t)s.batch * 4));
+  v.lists = reinterpret_cast<SavedEntry*>(b + 256 + align256((size_t)s.batch * 4) + align256((size_t)s.batch * units * 4));
+  return v;
+}
+size_t soft2d_state_bytes(const Shape& s) {
+  if (!soft2d_supported(s, 1)) return 256;
+  const Plan2d pl = plan2d<float>(s, true);
+  const size_t units = (size_t)pl.nstrip * pl.nseg;
+  return 256 + align256((size_t)s.batch * 4) + align256((size_t)s.batch * units * 4) +
+         (size_t)s.batch * units * state_cap(pl) * sizeof(SavedEntry);
+}
+__device__ __forceinline__ bool state_usable(const StateView& v, const SoftStateHeader& e, int item) {
+  const SoftStateHeader h = *v.hdr;
+  return h.magic == e.magic && h.H == e.H && h.W == e.W && h.batch == e.batch && h.nstrip == e.nstrip &&
+         h.nseg == e.nseg && h.rows_per_seg == e.rows_per_seg && h.tiltc == e.tiltc && h.cap == e.cap &&
+         v.overflow[item] != *v.gen;
+}
 
 // LDS: [4 waves] value rings, then [4 waves] queues of SoftEntry
 __device__ __forceinline__ void soft_lds(int* smem, float*& ring, SoftEntry*& qbuf) {
@@ -175,6 +270,7 @@ __global__ __launch_bounds__(256) void soft2d_fwd_kernel(const float* __restrict
   queue.sink.init(u, alpha, tau, T, kneg);
 #pragma unroll
   for (int t = 0; t < kSoftTL; ++t) queue.sink.acc[t] = 0.f;
+  queue.sink.csat = 0.f;
   WaveRange range;
   if constexpr (TILTC) {
     queue.sink.xsrc = grid + (int64_t)blockIdx.y * N;
@@ -193,7 +289,7 @@ __global__ __launch_bounds__(256) void soft2d_fwd_kernel(const float* __restrict
 #pragma unroll
     for (int t = 0; t < kSoftTL; ++t) {
       const int j = lane + kWave * t;
-      if (j < T) out[j] = queue.sink.acc[t];
+      if (j < T) out[j] = queue.sink.total(t);
     }
   }
 }
@@ -254,6 +350,105 @@ __global__ __launch_bounds__(256) void soft2d_bwd_kernel(const float* __restrict
         out[j * 4 + 1] = s.ax[t];
         out[j * 4 + 2] = s.ay[t];
       }
+    }
+  }
+}
+
+
+// Forward pass that saves its critical vertices: chi as SoftFwdSink, optionally the sums of
+// Eq. 9 / Eq. 10 in the same pass (they share the sigmoid), and every entry appended to the
+// unit's own list in the state buffer.
+template <bool DERIV>
+struct SoftSaveSink : SoftCommon {
+  static constexpr bool kZeroFill = false;
+  float acc[kSoftTL], a0[kSoftTL], ax[kSoftTL], ay[kSoftTL];
+  float csat;
+  int W, col0, row0;
+  SavedEntry* list;     // this unit's list
+  unsigned cap, saved;  // saved: entries seen so far (wave-uniform; may pass cap)
+  __device__ __forceinline__ void consume(Entry* buf, int n) {
+    const int lane = threadIdx.x & (kWave - 1);
+    if (lane < n && saved + (unsigned)lane < cap) {
+      const Entry e = buf[lane];
+      SavedEntry o;
+      o.y = (double)e.yh + (double)e.yl;
+      o.idx = e.row * W + e.col;
+      o.c = (int)e.c;
+      list[saved + lane] = o;
+    }
+    saved += (unsigned)n;
+    n = drop_saturated(buf, n, &csat);
+    for (int e = 0; e < n; ++e) {
+      const float yh = buf[e].yh, yl = buf[e].yl;
+      const float c = buf[e].c;
+      const float rx = (float)(buf[e].col - col0), ry = (float)(buf[e].row - row0);
+#pragma unroll
+      for (int t = 0; t < kSoftTL; ++t) {
+        if (t < nt) {  // wave-uniform
+          const float ex = soft_exp_neg(zarg(t, yh, yl), kneg);
+          const float sg = __builtin_amdgcn_rcpf(1.0f + ex);
+          acc[t] += c * sg;
+          if (DERIV) {
+            const float cd = c * (ex * sg * sg);  // c sigma (1 - sigma)
+            a0[t] += cd;
+            ax[t] += cd * rx;
+            ay[t] += cd * ry;
+          }
+        }
+      }
+    }
+  }
+};
+
+// partial[((item * units + unit) * T + j) * 4 + {0: chi, 1: A0, 2: Ax, 3: Ay}]
+template <bool TILTC, bool DERIV>
+__global__ __launch_bounds__(256) void soft2d_fwd_save_kernel(const float* __restrict__ grid, int H, int W, int64_t N,
+                                                              int nstrip, int nseg, int rows_per_seg,
+                                                              const float* __restrict__ u, float alpha,
+                                                              const float* __restrict__ tau, int T, float kneg,
+                                                              float* __restrict__ partial, StateView sv, unsigned cap) {
+  extern __shared__ int smem[];
+  float* ring;
+  SoftEntry* qbuf;
+  soft_lds(smem, ring, qbuf);
+  WaveQueue<SoftSaveSink<DERIV>> queue;
+  queue.buf = qbuf;
+  queue.count = 0;
+  SoftSaveSink<DERIV>& s = queue.sink;
+  s.init(u, alpha, tau, T, kneg);
+#pragma unroll
+  for (int t = 0; t < kSoftTL; ++t) s.acc[t] = s.a0[t] = s.ax[t] = s.ay[t] = 0.f;
+  s.csat = 0.f;
+  const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), units = nstrip * nseg;
+  s.W = W;
+  s.col0 = (unit % nstrip) * kStripOut - kNC;
+  s.row0 = (unit / nstrip) * rows_per_seg;
+  s.cap = cap;
+  s.saved = 0u;
+  s.list = sv.lists + ((size_t)blockIdx.y * units + (unit < units ? unit : 0)) * cap;
+  const unsigned next_gen = *sv.gen + 1u;  // (the reduction kernel that follows stores it)
+  WaveRange range;
+  if constexpr (TILTC) {
+    s.xsrc = grid + (int64_t)blockIdx.y * N;
+    s.xW = W;
+    const DirArgs da = {u, alpha, 1, 2};
+    sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                        load_tilt(da, 0));
+  } else {
+    sweep2d_wave<float>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
+                        NoTilt());
+  }
+  if (unit < units) {
+    const int lane = threadIdx.x & (kWave - 1);
+    if (lane == 0) {
+      sv.counts[(size_t)blockIdx.y * units + unit] = s.saved;
+      if (s.saved > cap) sv.overflow[blockIdx.y] = next_gen;
+    }
+    float4* out = reinterpret_cast<float4*>(partial) + ((int64_t)blockIdx.y * units + unit) * (int64_t)T;
+#pragma unroll
+    for (int t = 0; t < kSoftTL; ++t) {
+      const int j = lane + kWave * t;
+      if (j < T) out[j] = make_float4(s.acc[t] + s.csat, s.a0[t], s.ax[t], s.ay[t]);
     }
   }
 }
@@ -338,6 +533,216 @@ __global__ __launch_bounds__(kRedWaves * kWave) void soft2d_bwd_reduce_kernel(
   }
 }
 
+
+// Reduction of the saving forward pass: chi, dchi_dtau and dchi_du from one set of partial sums
+// (same fixed order as the two reductions above); block (0, 0) writes the header and raises the
+// state's generation.
+__global__ __launch_bounds__(kRedWaves * kWave) void soft2d_save_reduce_kernel(
+    const float* __restrict__ partial, int units, int nstrip, int rows_per_seg, int T, float alpha, float lambda,
+    float* __restrict__ chi, float* __restrict__ dtau, float* __restrict__ du, StateView sv, SoftStateHeader hdr) {
+  __shared__ double red[4][kRedWaves][kWave];
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+  const int j = blockIdx.x * kWave + lane;
+  const float4* p = reinterpret_cast<const float4*>(partial) + (int64_t)blockIdx.y * units * T + j;
+  double sc = 0.0, s0 = 0.0, sx = 0.0, sy = 0.0;
+  auto add = [&](int q, const float4& e) {
+    const double ox = (double)((q % nstrip) * kStripOut - kNC), oy = (double)((q / nstrip) * rows_per_seg);
+    const double a0 = (double)e.y;
+    sc += (double)e.x;
+    s0 += a0;
+    sx += ox * a0 + (double)e.z;
+    sy += oy * a0 + (double)e.w;
+  };
+  if (j < T) {
+    int q = wv;
+    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
+      float4 v[kRedUnroll];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
+#pragma unroll
+      for (int k = 0; k < kRedUnroll; ++k) add(q + k * kRedWaves, v[k]);
+    }
+    for (; q < units; q += kRedWaves) add(q, p[(int64_t)q * T]);
+  }
+  red[0][wv][lane] = sc;
+  red[1][wv][lane] = s0;
+  red[2][wv][lane] = sx;
+  red[3][wv][lane] = sy;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    *sv.hdr = hdr;
+    *sv.gen = *sv.gen + 1u;
+  }
+  __syncthreads();
+  if (wv == 0 && j < T) {
+    const int64_t k = (int64_t)blockIdx.y * T + j;
+    double r[4];
+    for (int c = 0; c < 4; ++c) {
+      r[c] = red[c][0][lane];
+      for (int w = 1; w < kRedWaves; ++w) r[c] += red[c][w][lane];
+    }
+    chi[k] = (float)r[0];
+    if (dtau) dtau[k] = (float)((double)lambda * r[1]);
+    if (du) {
+      du[k * 2 + 0] = (float)(-(double)alpha * (double)lambda * r[2]);
+      du[k * 2 + 1] = (float)(-(double)alpha * (double)lambda * r[3]);
+    }
+  }
+}
+
+// grad_X from the saved lists (Eq. 8 contracted with the upstream gradient).  A block takes one
+// unit of the forward sweep.  It clears the part of grad_X the unit owns (its rows x its 248
+// output columns), then goes through the unit's list 256 entries at a time: entries whose
+// sigmoids are all saturated are dropped (grad_X stays 0 there, see soft_sat_bounds), the others
+// are packed into an LDS stage and get eight lanes each -- every lane sums an eighth of the
+// thresholds, three lane swaps add the eight partial sums.  A unit's work is spread over four
+// waves because the lists are uneven: with a tilt, whole regions of the image are saturated and
+// the call lasts as long as its busiest unit.
+// An item whose lists cannot be used (header of another shape, a unit ran out of room) is
+// computed from the grid instead, vertex by vertex with the plain stencil: slow, but rare.
+constexpr int kSavedLanes = 8;  // lanes per entry
+struct StagedEntry {
+  float yh, yl, c;
+  int idx;
+};
+__device__ __forceinline__ float soft_dsig(float tau, float yh, float yl, float kneg) {  // sigma (1 - sigma)
+  const float ex = soft_exp_neg((tau - yh) - yl, kneg);
+  const float s = __builtin_amdgcn_rcpf(1.0f + ex);
+  return ex * s * s;
+}
+template <bool TILTC>
+__global__ __launch_bounds__(256) void soft2d_bwd_saved_kernel(const float* __restrict__ grid, int H, int W, int64_t N,
+                                                               int nstrip, int nseg, int rows_per_seg,
+                                                               const float* __restrict__ u, float alpha,
+                                                               const float* __restrict__ tau, int T, float kneg,
+                                                               float lambda, const float* __restrict__ gup,
+                                                               float* __restrict__ grad_X, StateView sv,
+                                                               SoftStateHeader expect) {
+  const int item = blockIdx.y, unit = blockIdx.x, units = nstrip * nseg;
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+  __shared__ float stau[kSoftTL * kWave];
+  __shared__ float sg[kSoftTL * kWave];
+  __shared__ StagedEntry stage[256];
+  __shared__ float sred[2][4];
+  __shared__ int skept[4];
+  // Everything the block needs from memory is requested up front, so that the call costs one
+  // round trip to memory and not four in a row: the state's header words, the unit's count and
+  // the first 256 entries of its list (or as many as the unit has room for, whatever the count says).
+  const bool usable = state_usable(sv, expect, item);
+  const unsigned cnt_raw = sv.counts[(size_t)item * units + unit];
+  const SavedEntry* list = sv.lists + ((size_t)item * units + unit) * expect.cap;
+  SavedEntry first = list[min((unsigned)threadIdx.x, expect.cap - 1u)];
+  float lo = INFINITY, hi = -INFINITY;
+  for (int j = threadIdx.x; j < T; j += 256) {
+    const float t = tau[j];
+    stau[j] = t;
+    sg[j] = gup ? gup[(int64_t)item * T + j] : 1.0f;
+    lo = fminf(lo, t);
+    hi = fmaxf(hi, t);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    lo = fminf(lo, __shfl_xor(lo, o));
+    hi = fmaxf(hi, __shfl_xor(hi, o));
+  }
+  if (lane == 0) {
+    sred[0][wv] = lo;
+    sred[1][wv] = hi;
+  }
+  float* gx = grad_X + (int64_t)item * N;
+  const int seg = unit / nstrip, strip = unit - seg * nstrip;
+  const int x0 = strip * kStripOut, x1 = min(x0 + kStripOut, W);
+  const int y0 = seg * rows_per_seg, y1 = min(y0 + rows_per_seg, H);
+  if (usable) {  // block-uniform
+    if (((reinterpret_cast<uintptr_t>(gx) | (uintptr_t)(W * 4) | (uintptr_t)(x0 * 4) | (uintptr_t)((x1 - x0) * 4)) & 15) == 0) {
+      const int w4 = (x1 - x0) / 4;  // 16-byte stores: rows, first column and width all fit
+      for (int y = y0 + wv; y < y1; y += 4)
+        if (lane < w4) reinterpret_cast<float4*>(gx + (int64_t)y * W + x0)[lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+      for (int y = y0 + wv; y < y1; y += 4)
+        for (int x = x0 + lane; x < x1; x += kWave) gx[(int64_t)y * W + x] = 0.0f;
+    }
+  }
+  __syncthreads();  // thresholds in LDS; the fill has reached memory before any entry is written
+  lo = fminf(fminf(sred[0][0], sred[0][1]), fminf(sred[0][2], sred[0][3]));
+  hi = fmaxf(fmaxf(sred[1][0], sred[1][1]), fmaxf(sred[1][2], sred[1][3]));
+  float sat_lo, sat_hi;
+  soft_sat_bounds(lo, hi, kneg, sat_lo, sat_hi);
+
+  if (!usable) {
+    const float* g = grid + (int64_t)item * N;
+    Tilt tilt;
+    if (TILTC) {
+      const DirArgs da = {u, alpha, 1, 2};
+      tilt = load_tilt(da, 0);
+    }
+    const double ux = (double)u[0], uy = (double)u[1];
+    for (int y = y0 + wv; y < y1; y += 4) {
+      for (int x = x0 + lane; x < x1; x += kWave) {
+        int c;
+        if (TILTC) c = coeff_tilted_at<2>(g, tilt, 1, H, W, 0, y, x);
+        else c = coeff_at<float, 2>(g, 1, H, W, 0, y, x);
+        float out = 0.0f;
+        if (c != 0) {
+          const double yv = (double)g[(int64_t)y * W + x] + (double)alpha * (ux * (double)x + uy * (double)y);
+          const float yh = (float)yv, yl = (float)(yv - (double)yh);
+          if (yh > sat_lo && yh < sat_hi) {
+            float gd = 0.0f;
+            for (int j = 0; j < T; ++j) gd += sg[j] * soft_dsig(stau[j], yh, yl, kneg);
+            out = -lambda * (float)c * gd;
+          }
+        }
+        gx[(int64_t)y * W + x] = out;
+      }
+    }
+    return;
+  }
+
+  // (<= cap when the forward pass wrote it: the item did not overflow; clamped all the same, and
+  // positions are checked below, so that a state that was never written cannot lead out of bounds)
+  const unsigned cnt = min(cnt_raw, expect.cap);
+  const int q = lane & (kSavedLanes - 1), slot = threadIdx.x / kSavedLanes;  // 32 entries per pass
+  for (unsigned e0 = 0; e0 < cnt; e0 += 256) {
+    bool keep = false;
+    StagedEntry mine;
+    if (e0 + threadIdx.x < cnt) {
+      const SavedEntry en = e0 == 0 ? first : list[e0 + threadIdx.x];
+      mine.yh = (float)en.y;
+      mine.yl = (float)(en.y - (double)mine.yh);
+      mine.c = (float)en.c;
+      mine.idx = en.idx;
+      keep = mine.yh > sat_lo && mine.yh < sat_hi;
+    }
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(keep);
+    if (lane == 0) skept[wv] = __builtin_popcountll(m);
+    __syncthreads();  // (also: the previous round's readers of the stage are done)
+    int base = 0, kept = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      if (w < wv) base += skept[w];
+      kept += skept[w];
+    }
+    const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+    if (keep) stage[pos] = mine;
+    __syncthreads();
+    for (int b = 0; b < kept; b += 256 / kSavedLanes) {
+      const bool on = b + slot < kept;
+      const StagedEntry en = stage[on ? b + slot : 0];
+      float g0 = 0.0f, g1 = 0.0f;  // two independent chains
+      int j = q;
+      for (; j + kSavedLanes < T; j += 2 * kSavedLanes) {
+        g0 += sg[j] * soft_dsig(stau[j], en.yh, en.yl, kneg);
+        g1 += sg[j + kSavedLanes] * soft_dsig(stau[j + kSavedLanes], en.yh, en.yl, kneg);
+      }
+      if (j < T) g0 += sg[j] * soft_dsig(stau[j], en.yh, en.yl, kneg);
+      float gd = g0 + g1;
+      gd += dpp_move<0xB1, 0xf>(gd);   // quad_perm [1,0,3,2]
+      gd += dpp_move<0x4E, 0xf>(gd);   // quad_perm [2,3,0,1]
+      gd += dpp_move<0x141, 0xf>(gd);  // row_half_mirror: the other quad of the eight
+      if (on && q == 0 && (unsigned)en.idx < (unsigned)N) gx[en.idx] = -lambda * en.c * gd;
+    }
+  }
+}
+
 static float kneg2d(float lambda) { return (float)(-(double)lambda * 1.4426950408889634); }
 constexpr size_t kSoftLds = ring_bytes2d<SoftEntry>();
 
@@ -356,12 +761,14 @@ void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float 
                        int T, float lambda, float* chi, void* ws, hipStream_t st, bool tiltc) {
   const Plan2d pl = plan2d<float>(s, true);
   float* partial = static_cast<float*>(ws);
+  profile_mark(st, false);
   if (tiltc)
     hipLaunchKernelGGL(soft2d_fwd_kernel<true>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
                        pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), partial);
   else
     hipLaunchKernelGGL(soft2d_fwd_kernel<false>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
                        pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), partial);
+  profile_mark(st, true);
   hipLaunchKernelGGL(soft2d_fwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
                      dim3(kRedWaves * kWave), 0, st, partial, pl.nstrip * pl.nseg, T, chi);
 }
@@ -371,6 +778,7 @@ void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float 
                        void* ws, hipStream_t st, bool tiltc) {
   const Plan2d pl = plan2d<float>(s, true);
   float* partial = (dtau || du) ? static_cast<float*>(ws) : nullptr;
+  profile_mark(st, false);
   if (tiltc)
     hipLaunchKernelGGL(soft2d_bwd_kernel<true>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
                        pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), lambda, gup,
@@ -379,11 +787,64 @@ void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float 
     hipLaunchKernelGGL(soft2d_bwd_kernel<false>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
                        pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), lambda, gup,
                        grad_X, partial);
+  profile_mark(st, true);
   if (partial) {
     hipLaunchKernelGGL(soft2d_bwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
                        dim3(kRedWaves * kWave), 0, st, partial, pl.nstrip * pl.nseg, pl.nstrip, pl.rows_per_seg, T, alpha,
                        lambda, dtau, du);
   }
+}
+
+static SoftStateHeader state_header(const Shape& s, const Plan2d& pl, bool tiltc) {
+  SoftStateHeader h;
+  h.magic = kSoftStateMagic;
+  h.H = (int)s.H;
+  h.W = (int)s.W;
+  h.batch = (int)s.batch;
+  h.nstrip = pl.nstrip;
+  h.nseg = pl.nseg;
+  h.rows_per_seg = pl.rows_per_seg;
+  h.tiltc = tiltc ? 1 : 0;
+  h.cap = state_cap(pl);
+  return h;
+}
+
+void launch_soft2d_fwd_save(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
+                            float lambda, float* chi, float* dtau, float* du, void* state, void* ws, hipStream_t st,
+                            bool tiltc) {
+  const Plan2d pl = plan2d<float>(s, true);
+  const StateView sv = state_view(state, s, pl);
+  const SoftStateHeader hdr = state_header(s, pl, tiltc);
+  float* partial = static_cast<float*>(ws);
+  const bool deriv = dtau || du;
+  profile_mark(st, false);
+#define ECC_GO(TC, DV)                                                                                        \
+  hipLaunchKernelGGL((soft2d_fwd_save_kernel<TC, DV>), pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, \
+                     s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), partial, sv, hdr.cap)
+  if (tiltc) { if (deriv) ECC_GO(true, true); else ECC_GO(true, false); }
+  else       { if (deriv) ECC_GO(false, true); else ECC_GO(false, false); }
+#undef ECC_GO
+  profile_mark(st, true);
+  hipLaunchKernelGGL(soft2d_save_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
+                     dim3(kRedWaves * kWave), 0, st, partial, pl.nstrip * pl.nseg, pl.nstrip, pl.rows_per_seg, T, alpha,
+                     lambda, chi, dtau, du, sv, hdr);
+}
+
+void launch_soft2d_bwd_saved(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
+                             float lambda, const float* gup, float* grad_X, const void* state, hipStream_t st,
+                             bool tiltc) {
+  const Plan2d pl = plan2d<float>(s, true);
+  const StateView sv = state_view(const_cast<void*>(state), s, pl);
+  const SoftStateHeader expect = state_header(s, pl, tiltc);
+  const dim3 g((unsigned)(pl.nstrip * pl.nseg), (unsigned)s.batch);
+  profile_mark(st, false);
+  if (tiltc)
+    hipLaunchKernelGGL(soft2d_bwd_saved_kernel<true>, g, dim3(256), 0, st, grid, (int)s.H, (int)s.W, s.N, pl.nstrip,
+                       pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), lambda, gup, grad_X, sv, expect);
+  else
+    hipLaunchKernelGGL(soft2d_bwd_saved_kernel<false>, g, dim3(256), 0, st, grid, (int)s.H, (int)s.W, s.N, pl.nstrip,
+                       pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), lambda, gup, grad_X, sv, expect);
+  profile_mark(st, true);
 }
 
 }  // namespace ecc

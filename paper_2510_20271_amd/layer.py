@@ -1,7 +1,8 @@
 """Differentiable ECC layer over the C ABI (the paper's "differentiable PyTorch layer").
 
-``SoftECCFunction`` is a ``torch.autograd.Function``: forward is ``ecc_soft_fwd`` (Eq. 6),
-backward is ``ecc_soft_bwd`` (Eq. 8-10, appendix on analytical derivatives).  The kernels
+``SoftECCFunction`` is a ``torch.autograd.Function``: forward is ``ecc_soft_fwd_save`` (Eq. 6, plus the
+sums of Eq. 9-10, which share its sigmoids, and the saved list of critical vertices), backward is
+``ecc_soft_bwd_saved`` (Eq. 8 over that list; appendix on analytical derivatives).  The kernels
 return d chi / d tau and d chi / d u uncontracted ([batch, T] and [batch, T, ndim]); the two
 small contractions with the upstream gradient that autograd needs are the only arithmetic
 done here.  ``SoftECCLayer`` holds the learnable thresholds and a direction kept on the unit
@@ -27,22 +28,29 @@ class SoftECCFunction(torch.autograd.Function):
         grid_c = grid.detach().contiguous().float()
         u_c = u.detach().contiguous().float()
         tau_c = tau.detach().contiguous().float()
-        ctx.save_for_backward(grid_c, u_c, tau_c)
         ctx.alpha, ctx.lam, ctx.ndim, ctx.tilted_c = float(alpha), float(lam), ndim, bool(tilted_c)
-        return api.ecc_soft_fwd(grid_c, ndim, u_c, alpha, tau_c, lam, tilted_c=ctx.tilted_c)
+        need_x, need_u, need_tau = ctx.needs_input_grad[:3]
+        if not (need_x or need_u or need_tau):
+            return api.ecc_soft_fwd(grid_c, ndim, u_c, alpha, tau_c, lam, tilted_c=ctx.tilted_c)
+        # The forward kernel shares its sigmoids with the sums of Eq. 9 / Eq. 10 and finds the vertices
+        # with c != 0 that Eq. 8 needs: it returns the former and saves the latter, so backward() neither
+        # sweeps the grid again nor, with fixed inputs and learnable thresholds (the usual case), runs a
+        # kernel at all.
+        want = [n for n, need in (("dchi_du", need_u), ("dchi_dtau", need_tau)) if need]
+        chi, dtau, du, state = api.ecc_soft_fwd_save(grid_c, ndim, u_c, alpha, tau_c, lam, tilted_c=ctx.tilted_c,
+                                                     want=want)
+        ctx.save_for_backward(grid_c, u_c, tau_c, state if need_x else None, dtau, du)
+        return chi
 
     @staticmethod
     def backward(ctx, grad_chi):
-        grid, u, tau = ctx.saved_tensors
+        grid, u, tau, state, dtau, du = ctx.saved_tensors
         g = grad_chi.contiguous().float()
         need_x, need_u, need_tau = ctx.needs_input_grad[:3]
-        if not (need_x or need_u or need_tau):
-            return None, None, None, None, None, None
-        # only the outputs autograd asks for are computed (with fixed inputs and learnable
-        # thresholds, the usual case, the image-sized grad_X is neither allocated nor written)
-        skip = [n for n, need in (("grad_X", need_x), ("dchi_du", need_u), ("dchi_dtau", need_tau)) if not need]
-        grad_X, dtau, du = api.ecc_soft_bwd(grid, ctx.ndim, u, ctx.alpha, tau, ctx.lam, grad_chi=g,
-                                            tilted_c=ctx.tilted_c, skip=skip)
+        grad_X = None
+        if need_x:
+            grad_X = api.ecc_soft_bwd_saved(grid, ctx.ndim, u, ctx.alpha, tau, ctx.lam, state, grad_chi=g,
+                                            tilted_c=ctx.tilted_c)
         grad_u = torch.einsum("bj,bjd->d", g, du) if need_u else None
         grad_tau = (g * dtau).sum(0) if need_tau else None
         return grad_X, grad_u, grad_tau, None, None, None
