@@ -1,19 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the ECC hot path on one MI355X.
 
-A step is one ecc_hard call (batch-global range, thresholds, coefficient sweep,
-histogram, merge, scan) over workload C2: a batch of 16 2D 4096x4096 float32
-smoothed Gaussian random fields, 1024 equal-width bins over the batch-global
-[min, max] computed on the device.  Inputs are resident in HBM before the
-timed region.  The same run also times, as extra fields of the one JSON line,
-the 3D 512^3 float32 volume (C4), the hard path with the range supplied, the
-two integer workloads (C1, C3), directional curves (16 directions over one
-4096^2 field, ecc_hard_dir), soft forward + backward over the 32 x 512^2
-batch (C5) and over one 256^3 volume, and the CPU oracle on the host cores (a baseline, not the target).
+A step is one ecc_hard call (batch-global range, thresholds, coefficient sweep, histogram,
+merge, scan) over workload C2: a batch of 16 2D 4096x4096 float32 smoothed Gaussian random
+fields, 1024 equal-width bins over the batch-global [min, max] found on the device.  Inputs are
+resident in HBM before the timed region.  The same run also times, as `extra` fields of the one
+JSON line, the other four workloads (C4 3D 512^3 float32, C1 256^2 uint8, C3 256^3 uint16, C5
+soft forward + backward), each with a roofline entry of its own and -- for the three that fit
+the 256 MB Infinity Cache -- a cold variant that rotates over copies totalling more than 256 MB;
+the hard path with the range supplied; directional curves; the grid sizes of the paper's
+Tables 1-2; and the CPU oracle on the host cores (a baseline, not the target).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--quick]
-    python bench.py --only c2|c2r|c4|c5|dir|calib   one workload (profiling runs)
-    python bench.py --sweep                         the grid sizes of the paper's Tables 1-2
+    python bench.py --only c1|c2|c2r|c3|c4|c4r|c5|dir|sizes|calib    one workload, no JSON (profiling runs)
+
+Counter-based figures (HBM traffic, VALU / LDS instruction counts) cannot be taken inside this
+process; they come from rocprofv3 runs of `bench.py --only <workload>` summarised by
+`python -m paper_2510_20271_amd.profile_summary` into profiles/counters.json, which this script
+reads (null when the file has no entry).
 """
 from __future__ import annotations
 
@@ -26,7 +30,9 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E peak
+VALU_PEAK_TLANEOPS = 39.32  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: vector lane-operations per second (x 1e12)
+CACHE_MB = 256              # Infinity Cache; cold variants rotate over more than this
 
 
 def log(*a):
@@ -45,6 +51,68 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e3  # ms per step
 
 
+def kernel_ms(api, fn, steps, warmup):
+    """(mean duration of the call's dominant kernel -- HIP events recorded by the library on the call's
+    stream --, wall time per call, launches measured) over the same `steps` calls."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    api.ecc_profile_begin(steps)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    k, n = api.ecc_profile_end()
+    return k, ms, n
+
+
+def load_counters():
+    path = os.path.join(ROOT, "profiles", "counters.json")
+    if os.path.exists(path):
+        return json.load(open(path)).get("kernels", {})
+    return {}
+
+
+def roofline_hbm(alg_bytes, k_ms, kernel, counters, note=None):
+    achieved = alg_bytes / (k_ms * 1e-3) / 1e9
+    c = counters or {}
+    traffic = None
+    if "fetch_bytes" in c and "write_bytes" in c:
+        traffic = int(c["fetch_bytes"] + c["write_bytes"])
+    r = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "kernel": kernel, "kernel_ms": round(k_ms, 4),
+         "algorithmic_bytes_per_launch": int(alg_bytes)}
+    if traffic is not None:
+        r["traffic_source"] = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/counters.json)"
+    if "SQ_INSTS_VALU" in c:
+        r["valu_lane_ops_per_launch"] = int(c["SQ_INSTS_VALU"] * 64)
+        r["valu_frac_of_peak"] = round(c["SQ_INSTS_VALU"] * 64 / (k_ms * 1e-3) / 1e12 / VALU_PEAK_TLANEOPS, 4)
+    if note:
+        r["note"] = note
+    return r
+
+
+def roofline_alu(k_ms, kernel, counters, alg_bytes, note):
+    """A kernel bound by vector instruction issue: achieved = lane-operations issued (SQ_INSTS_VALU x 64, from
+    the rocprofv3 run) per second of the kernel's duration measured here."""
+    c = counters or {}
+    if "SQ_INSTS_VALU" not in c:
+        return {"bound": "alu", "achieved": None, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s", "frac": None,
+                "traffic": None, "kernel": kernel, "kernel_ms": round(k_ms, 4), "note": note}
+    ach = c["SQ_INSTS_VALU"] * 64 / (k_ms * 1e-3) / 1e12
+    r = {"bound": "alu", "achieved": round(ach, 2), "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
+         "frac": round(ach / VALU_PEAK_TLANEOPS, 4),
+         "traffic": int(c["fetch_bytes"] + c["write_bytes"]) if "fetch_bytes" in c else None, "kernel": kernel,
+         "kernel_ms": round(k_ms, 4), "algorithmic_bytes_per_launch": int(alg_bytes),
+         "hbm_frac_by_algorithmic_bytes": round(alg_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "note": note}
+    for k in ("SQ_INSTS_LDS", "SQ_LDS_BANK_CONFLICT", "SQ_ACTIVE_INST_LDS"):
+        if k in c:
+            r[k] = int(c[k])
+    return r
+
+
 # "New" kernel times of the paper's Tables 1 and 2 (ms, one RTX A6000; dtype, bins and timing
 # method not stated there): context beside the sizes below, not a target.
 PAPER_MS = {(128, 128): 0.0165, (256, 256): 0.0174, (512, 512): 0.021, (1024, 1024): 0.032,
@@ -52,36 +120,36 @@ PAPER_MS = {(128, 128): 0.0165, (256, 256): 0.0174, (512, 512): 0.021, (1024, 10
             (256, 256, 256): 0.71, (512, 512, 512): 5.61, (1024, 1024, 1024): 48.47}
 
 
-def run_sweep(args, np, torch, api, synth):
-    """One float32 smoothed random field of each size of the paper's Tables 1-2, 1024 bins over
-    the range found on the device (the whole hot path per call).  The 1024^3 volume is the
-    periodic 512^3 field tiled 2x2x2 (the generator smooths with wrap-around, so the tiling is
-    seamless); exact duplicates across tiles are ties like any other."""
+def size_rows(args, np, torch, api, synth, field_2d=None, field_3d=None):
+    """One float32 smoothed random field of each size of the paper's Tables 1-2, 1024 bins over the range
+    found on the device (the whole hot path per call).  The generator smooths with wrap-around, so a
+    field tiles seamlessly: 8192^2 is a 4096^2 field tiled 2 x 2, 1024^3 a 512^3 field tiled 2 x 2 x 2
+    (exact duplicates across tiles are ties like any other)."""
     rows = []
     for shape in PAPER_MS:
         nd = len(shape)
-        if shape == (1024, 1024, 1024):
-            X = np.tile(synth.grf((512, 512, 512), 3.0, 4242), (2, 2, 2))
+        if shape == (8192, 8192):
+            X = np.tile(field_2d if field_2d is not None else synth.grf((4096, 4096), 4.0, 4242), (2, 2))
+        elif shape == (4096, 4096) and field_2d is not None:
+            X = field_2d
+        elif shape == (1024, 1024, 1024):
+            X = np.tile(field_3d if field_3d is not None else synth.grf((512, 512, 512), 3.0, 4242), (2, 2, 2))
+        elif shape == (512, 512, 512) and field_3d is not None:
+            X = field_3d
         else:
             X = synth.grf(shape, 4.0 if nd == 2 else 3.0, 4242)
-        g = torch.from_numpy(X[None]).cuda()
+        g = torch.from_numpy(np.ascontiguousarray(X)[None]).cuda()
         ws = torch.empty(api.ecc_workspace_bytes(shape, 1, 1024), dtype=torch.uint8, device="cuda")
         cv = torch.empty((1, 1024), dtype=torch.int64, device="cuda")
-        fn = lambda: api.ecc_hard(g, nd, 1024, curve=cv, workspace=ws)
-        ms = time_steps(fn, args.steps, args.warmup)
-        assert int(cv[0, -1]) == 1  # the full grid is contractible
+        ms = time_steps(lambda: api.ecc_hard(g, nd, 1024, curve=cv, workspace=ws), args.steps, args.warmup)
         n = int(np.prod(shape))
         rows.append({"shape": "x".join(map(str, shape)), "ms": round(ms, 4), "gvoxel_per_s": round(n / ms / 1e6, 1),
-                     "paper_ms_rtx_a6000": PAPER_MS[shape]})
-        log(f"[bench] sweep {rows[-1]['shape']:>14}: {ms:8.4f} ms  {rows[-1]['gvoxel_per_s']:8.1f} Gvoxel/s"
+                     "curve_ends_at_one": bool(int(cv[0, -1]) == 1), "paper_ms_rtx_a6000": PAPER_MS[shape]})
+        log(f"[bench] size {rows[-1]['shape']:>14}: {ms:8.4f} ms  {rows[-1]['gvoxel_per_s']:8.1f} Gvoxel/s"
             f"   (paper, RTX A6000: {PAPER_MS[shape]} ms)")
         del g, ws, cv, X
         torch.cuda.empty_cache()
-    print(json.dumps({"metric": "hard_ecc_size_sweep", "unit": "ms", "n_gpus": 1, "steps": args.steps,
-                      "warmup": args.warmup, "dtype": "f32", "data": "synthetic",
-                      "config": {"workload": "one float32 smoothed random field per size of the paper's "
-                                             "Tables 1-2, 1024 bins, range found on the device"},
-                      "rows": rows}))
+    return rows
 
 
 def main():
@@ -89,10 +157,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--quick", action="store_true", help="skip the extra workloads and the CPU baseline")
-    ap.add_argument("--sweep", action="store_true",
-                    help="time one grid of every size of the paper's Tables 1-2 instead (own JSON line)")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'c2', 'c2r' (range supplied), 'c4', 'c5', 'dir' or 'calib' (a plain 1 GiB copy), no JSON")
+    ap.add_argument("--quick", action="store_true", help="C2 only: skip the other workloads and the CPU baseline")
+    ap.add_argument("--only", default="", help="profiling aid: run one of c1, c2, c2r, c3, c4, c4r, c5, dir, sizes, "
+                                               "calib (a plain 1 GiB copy); no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path shards by batch item / "
@@ -106,7 +173,17 @@ def main():
     _lib.load()  # fails loudly when the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    if args.only == "calib":
+    only = args.only
+    full = only == "" and not args.quick
+    counters = load_counters()
+    BINS = 1024
+    extra = {}
+    rooflines = {}
+
+    def want(*names):
+        return full or only in names
+
+    if only == "calib":
         # counter calibration: a plain device copy of exactly 1 GiB read + 1 GiB written per launch
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
@@ -115,61 +192,45 @@ def main():
         torch.cuda.synchronize()
         log("[bench] calib: copied 1 GiB x %d" % args.steps)
         return
-    BINS = 1024
-    extra = {}
-    if args.sweep:
-        run_sweep(args, np, torch, api, synth)
-        return
+
+    def rotating(make_copy, one_bytes):
+        """Copies of an input totalling more than the Infinity Cache, for the cold variants."""
+        n = int(CACHE_MB * (1 << 20) * 1.05 // one_bytes) + 1
+        return [make_copy() for _ in range(n)]
 
     # ---------------- C2: the headline workload --------------------------------
-    if args.only in ("", "c2", "c2r"):
+    field_2d = None
+    if only in ("", "c2", "c2r"):
         t0 = time.perf_counter()
         X2 = synth.config_c2()
         log(f"[bench] generated C2 {X2.shape} in {time.perf_counter() - t0:.1f}s")
         g2 = torch.from_numpy(X2).cuda()
         ws2 = torch.empty(api.ecc_workspace_bytes(X2.shape[1:], X2.shape[0], BINS), dtype=torch.uint8, device="cuda")
         curve2 = torch.empty((X2.shape[0], BINS), dtype=torch.int64, device="cuda")
-        step = lambda: api.ecc_hard(g2, 2, BINS, curve=curve2, workspace=ws2)
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        api.ecc_profile_begin(args.steps)
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) / args.steps * 1e3
-        sweep_ms, nl = api.ecc_profile_end()
         nvox = X2.size
-        value = nvox / (ms * 1e-3) / 1e9
         alg_bytes = 4.0 * nvox  # one float32 read per vertex per sweep launch
-        achieved = alg_bytes / (sweep_ms * 1e-3) / 1e9
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-        if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get("c2_sweep_bytes_per_launch")
-        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                    "kernel": "sweep2d_list_kernel (coefficient sweep + range + critical-vertex lists)", "kernel_ms": round(sweep_ms, 4),
-                    "launches_timed": nl, "algorithmic_bytes_per_launch": alg_bytes}
-        log(f"[bench] C2: {ms:.3f} ms/step, {value:.1f} Gvoxel/s, sweep kernel {sweep_ms:.3f} ms")
-        if args.only == "c2":
-            return
-        if args.only == "c2r":  # profiling aid: the histogram-mode sweep (range supplied)
+        if only != "c2r":
+            sweep_ms, ms, nl = kernel_ms(api, lambda: api.ecc_hard(g2, 2, BINS, curve=curve2, workspace=ws2), args.steps,
+                                         args.warmup)
+            value = nvox / (ms * 1e-3) / 1e9
+            roofline = roofline_hbm(alg_bytes, sweep_ms, "sweep2d_list_kernel (coefficient sweep + range + "
+                                    "critical-vertex lists)", counters.get("c2"))
+            roofline["launches_timed"] = nl
+            roofline["whole_call_hbm_frac"] = round(alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            log(f"[bench] C2: {ms:.4f} ms/step, {value:.1f} Gvoxel/s, sweep kernel {sweep_ms:.4f} ms")
+        if full or only == "c2r":
             rng2 = (float(X2.min()), float(X2.max()))
-            ms_r = time_steps(lambda: api.ecc_hard(g2, 2, BINS, range=rng2, curve=curve2, workspace=ws2),
-                              args.steps, args.warmup)
-            log(f"[bench] C2, range supplied: {ms_r:.3f} ms/step")
-            return
-        if not args.quick:
-            rng2 = (float(X2.min()), float(X2.max()))
-            ms_r = time_steps(lambda: api.ecc_hard(g2, 2, BINS, range=rng2, curve=curve2, workspace=ws2),
-                              args.steps, args.warmup)
-            extra["c2_range_supplied"] = {"ms_per_step": round(ms_r, 4), "gvoxel_per_s": round(nvox / ms_r / 1e6, 1),
-                                          "hbm_frac_one_pass": round(alg_bytes / (ms_r * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            k_r, ms_r, _ = kernel_ms(api, lambda: api.ecc_hard(g2, 2, BINS, range=rng2, curve=curve2, workspace=ws2),
+                                     args.steps, args.warmup)
+            extra["c2_range_supplied"] = {"ms_per_step": round(ms_r, 4), "gvoxel_per_s": round(nvox / ms_r / 1e6, 1)}
+            rooflines["c2_range_supplied"] = roofline_hbm(alg_bytes, k_r, "sweep2d_kernel (histogram mode)",
+                                                          counters.get("c2r"))
+            log(f"[bench] C2, range supplied: {ms_r:.4f} ms/step, sweep kernel {k_r:.4f} ms")
+        if full:
             # CPU oracle on the same batch, as it stands
             from oracle import ecc_oracle as O
             from oracle import ecc_oracle_c as OC
+            api.ecc_hard(g2, 2, BINS, curve=curve2, workspace=ws2)
             nitem = X2.shape[0]  # the whole batch: a couple of seconds on the host cores
             t0 = time.perf_counter()
             lo, hi = X2.min(), X2.max()
@@ -178,84 +239,114 @@ def main():
             cpu = {"value": round(nitem * X2[0].size / dt / 1e9, 4), "unit": "Gvoxel/s", "cores": OC.threads(),
                    "kind": "oracle", "sample": f"the whole C2 batch, {nitem} items, thresholds from its min/max "
                    f"({dt:.1f} s of host time)"}
-            got = curve2[:nitem].cpu().numpy()
-            extra["c2_sample_matches_oracle"] = bool(np.array_equal(got, ref))
-        del g2, X2
+            extra["c2_matches_oracle"] = bool(np.array_equal(curve2.cpu().numpy(), ref))
+            # the same batch as float16
+            g2h = g2.half()
+            wsh = torch.empty(api.ecc_workspace_bytes_dtype(X2.shape[1:], X2.shape[0], api.ECC_F16, BINS),
+                              dtype=torch.uint8, device="cuda")
+            ms_h = time_steps(lambda: api.ecc_hard(g2h, 2, BINS, curve=curve2, workspace=wsh), args.steps, args.warmup)
+            extra["c2_float16"] = {"ms_per_step": round(ms_h, 4), "gvoxel_per_s": round(nvox / ms_h / 1e6, 1)}
+            log(f"[bench] C2 as float16: {ms_h:.4f} ms/step")
+            del g2h, wsh
+            field_2d = X2[0].copy()
+        if only in ("c2", "c2r"):
+            return
+        del g2, ws2, X2
         torch.cuda.empty_cache()
 
     # ---------------- C4: 3D 512^3 float32 -------------------------------------
-    if args.only in ("", "c4") and (not args.quick or args.only == "c4"):
+    field_3d = None
+    if want("c4", "c4r"):
         t0 = time.perf_counter()
         X4 = synth.config_c4()[None]
         log(f"[bench] generated C4 {X4.shape} in {time.perf_counter() - t0:.1f}s")
         g4 = torch.from_numpy(X4).cuda()
         ws4 = torch.empty(api.ecc_workspace_bytes(X4.shape[1:], 1, BINS), dtype=torch.uint8, device="cuda")
         curve4 = torch.empty((1, BINS), dtype=torch.int64, device="cuda")
-        step4 = lambda: api.ecc_hard(g4, 3, BINS, curve=curve4, workspace=ws4)
-        for _ in range(args.warmup):
-            step4()
-        torch.cuda.synchronize()
-        api.ecc_profile_begin(args.steps)
-        ms4 = time_steps(step4, args.steps, 0)
-        sweep4, _ = api.ecc_profile_end()
-        rng4 = (float(X4.min()), float(X4.max()))
-        ms4r = time_steps(lambda: api.ecc_hard(g4, 3, BINS, range=rng4, curve=curve4, workspace=ws4),
-                          args.steps, args.warmup)
         b4 = 4.0 * X4.size
-        extra["c4"] = {"workload": "C4: 3D 512^3 float32 GRF sigma=3, 1024 bins",
-                       "ms_per_step_auto_range": round(ms4, 4), "ms_per_step_range_supplied": round(ms4r, 4),
-                       "gvoxel_per_s_auto_range": round(X4.size / ms4 / 1e6, 1),
-                       "gvoxel_per_s_range_supplied": round(X4.size / ms4r / 1e6, 1),
-                       "sweep_kernel_ms": round(sweep4, 4),
-                       "sweep_hbm_frac": round(b4 / (sweep4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        log(f"[bench] C4: {ms4:.3f} ms/step (range supplied {ms4r:.3f}), sweep kernel {sweep4:.3f} ms")
-        if args.only == "c4":
+        c4 = {"workload": "C4: 3D 512^3 float32 GRF sigma=3, 1024 bins"}
+        if only != "c4r":
+            sweep4, ms4, _ = kernel_ms(api, lambda: api.ecc_hard(g4, 3, BINS, curve=curve4, workspace=ws4), args.steps,
+                                       args.warmup)
+            c4.update({"ms_per_step_auto_range": round(ms4, 4), "gvoxel_per_s_auto_range": round(X4.size / ms4 / 1e6, 1)})
+            rooflines["c4"] = roofline_hbm(b4, sweep4, "sweep3d_list_kernel (coefficient sweep + range + lists)",
+                                           counters.get("c4"), note="target of this build: frac >= 0.60; not met: the kernel "
+                                           "is bound by vector instruction issue before it is bound by memory (see "
+                                           "valu_frac_of_peak)")
+            rooflines["c4"]["whole_call_hbm_frac"] = round(b4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            log(f"[bench] C4: {ms4:.4f} ms/step, sweep kernel {sweep4:.4f} ms")
+        if full or only == "c4r":
+            rng4 = (float(X4.min()), float(X4.max()))
+            k4r, ms4r, _ = kernel_ms(api, lambda: api.ecc_hard(g4, 3, BINS, range=rng4, curve=curve4, workspace=ws4),
+                                     args.steps, args.warmup)
+            c4.update({"ms_per_step_range_supplied": round(ms4r, 4),
+                       "gvoxel_per_s_range_supplied": round(X4.size / ms4r / 1e6, 1)})
+            rooflines["c4_range_supplied"] = roofline_hbm(b4, k4r, "sweep3d_kernel (histogram mode)", counters.get("c4r"))
+            log(f"[bench] C4, range supplied: {ms4r:.4f} ms/step, sweep kernel {k4r:.4f} ms")
+        extra["c4"] = c4
+        if only in ("c4", "c4r"):
             return
-        del g4, X4
+        field_3d = X4[0]
+        del g4, ws4
         torch.cuda.empty_cache()
 
     # ---------------- C1 / C3: integer levels, one bin per level ----------------
-    if (args.only == "" and not args.quick) or args.only in ("c1", "c3"):
-        for name, X, nd, bins in (("c1", synth.config_c1()[None], 2, 256), ("c3", synth.config_c3()[None], 3, 4096)):
-            if args.only and args.only != name:
+    if want("c1", "c3"):
+        for name, nd, bins in (("c1", 2, 256), ("c3", 3, 4096)):
+            if only and only != name:
                 continue
+            X = (synth.config_c1() if name == "c1" else synth.config_c3())[None]
             if X.dtype == np.uint16:
                 gi = torch.from_numpy(X.view(np.int16)).cuda().view(torch.uint16)
             else:
                 gi = torch.from_numpy(X).cuda()
             wsi = torch.empty(api.ecc_workspace_bytes(X.shape[1:], 1, bins), dtype=torch.uint8, device="cuda")
             cvi = torch.empty((1, bins), dtype=torch.int64, device="cuda")
-            fn = lambda: api.ecc_hard(gi, nd, bins, curve=cvi, workspace=wsi)
-            for _ in range(args.warmup):
-                fn()
-            torch.cuda.synchronize()
-            api.ecc_profile_begin(args.steps)
-            msi = time_steps(fn, args.steps, 0)
-            swi, _ = api.ecc_profile_end()
+            swi, msi, _ = kernel_ms(api, lambda: api.ecc_hard(gi, nd, bins, curve=cvi, workspace=wsi), args.steps, args.warmup)
+            # cold: rotate over copies totalling more than the Infinity Cache
+            copies = rotating(lambda: gi.clone(), X.nbytes)
+            it = [0]
+
+            def cold():
+                it[0] = (it[0] + 1) % len(copies)
+                api.ecc_hard(copies[it[0]], nd, bins, curve=cvi, workspace=wsi)
+            ncold = max(args.steps, 2 * len(copies)) if name == "c3" else 512
+            swc, msc, _ = kernel_ms(api, cold, ncold, len(copies) if name == "c3" else 64)
             extra[name] = {"workload": {"c1": "C1: 2D 256^2 uint8 i.i.d., 256 levels (launch-latency bound, 3 launches)",
                                         "c3": "C3: 3D 256^3 uint16 i.i.d., 4096 levels"}[name],
                            "us_per_step": round(msi * 1e3, 2), "sweep_kernel_us": round(swi * 1e3, 2),
-                           "gvoxel_per_s": round(X.size / msi / 1e6, 2)}
-            log(f"[bench] {name}: {msi * 1e3:.1f} us/step, sweep {swi * 1e3:.1f} us")
-            del gi
-        if args.only in ("c1", "c3"):
+                           "gvoxel_per_s": round(X.size / msi / 1e6, 2),
+                           "cold_us_per_step": round(msc * 1e3, 2), "cold_sweep_kernel_us": round(swc * 1e3, 2),
+                           "cold_copies": len(copies)}
+            if name == "c3":
+                rooflines["c3"] = roofline_alu(swi, "sweep3d_kernel<uint16> (levels, LDS histogram)", counters.get("c3"),
+                                               X.nbytes, "2 bytes per vertex: HBM is idle by construction; the kernel is "
+                                               "bound by vector instruction issue (stencil, then a walk over the 60 % of "
+                                               "the vertices that are critical, each with one LDS histogram update)")
+                rooflines["c3"]["cold_kernel_ms"] = round(swc, 4)
+            else:
+                rooflines["c1"] = roofline_hbm(float(X.nbytes), swi, "sweep_generic_kernel<uint8> (one thread per vertex)",
+                                               counters.get("c1"), note="64 KiB input: the call is three dependent "
+                                               "launches of a few microseconds each; a fraction of HBM peak says nothing here")
+                rooflines["c1"]["cold_kernel_ms"] = round(swc, 4)
+                rooflines["c1"]["launches_per_call"] = 3
+            log(f"[bench] {name}: {msi * 1e3:.1f} us/step, sweep {swi * 1e3:.1f} us; cold {msc * 1e3:.1f} us/step, "
+                f"sweep {swc * 1e3:.1f} us ({len(copies)} copies)")
+            del gi, copies
+            torch.cuda.empty_cache()
+        if only in ("c1", "c3"):
             return
 
     # ---------------- directional curves: 16 directions of one 4096^2 field --------
-    if args.only in ("", "dir") and (not args.quick or args.only == "dir"):
-        Xd = synth.grf((4096, 4096), 4.0, 2002)[None]
+    if want("dir"):
+        Xd = (field_2d if field_2d is not None else synth.grf((4096, 4096), 4.0, 2002))[None]
         th = np.linspace(0.0, np.pi, 16, endpoint=False)
         Ud = np.stack([np.cos(th), np.sin(th)], 1).astype(np.float32)
         gd, ud = torch.from_numpy(Xd).cuda(), torch.from_numpy(Ud).cuda()
         wsd = torch.empty(api.ecc_workspace_bytes_dir(Xd.shape[1:], 1, 16, BINS), dtype=torch.uint8, device="cuda")
         cvd = torch.empty((16, 1, BINS), dtype=torch.int64, device="cuda")
-        fnd = lambda: api.ecc_hard_dir(gd, 2, ud, 1e-4, BINS, curve=cvd, workspace=wsd)
-        for _ in range(args.warmup):
-            fnd()
-        torch.cuda.synchronize()
-        api.ecc_profile_begin(args.steps)
-        msd = time_steps(fnd, args.steps, 0)
-        swd, _ = api.ecc_profile_end()
+        swd, msd, _ = kernel_ms(api, lambda: api.ecc_hard_dir(gd, 2, ud, 1e-4, BINS, curve=cvd, workspace=wsd), args.steps,
+                                args.warmup)
         extra["directional"] = {"workload": "16 directions x one 2D 4096^2 float32 GRF (alpha = 1e-4 per pixel), 1024 "
                                             "bins over the range of all tilted fields, found on the device",
                                 "ms_per_step": round(msd, 4), "sweep_kernel_ms": round(swd, 4),
@@ -263,62 +354,103 @@ def main():
                                 "note": "the field (64 MiB) is read once per direction; re-reads are served by "
                                         "the L2 / Infinity Cache, so vertices/s may pass the HBM roofline of a "
                                         "single read"}
-        log(f"[bench] directional: {msd:.3f} ms/step (16 x 4096^2), sweep kernel {swd:.3f} ms")
+        log(f"[bench] directional: {msd:.4f} ms/step (16 x 4096^2), sweep kernel {swd:.4f} ms")
         del gd, Xd
         torch.cuda.empty_cache()
-        if args.only == "dir":
+        if only == "dir":
             return
 
     # ---------------- C5: soft forward + backward -------------------------------
-    if args.only in ("", "c5") and (not args.quick or args.only == "c5"):
+    if want("c5"):
         X5 = synth.config_c5()
         p = synth.soft_params_c5(X5)
         T = len(p["tau"])
+        B5 = X5.shape[0]
         g5 = torch.from_numpy(X5).cuda()
         u5, tau5 = torch.from_numpy(p["u"]).cuda(), torch.from_numpy(p["tau"]).cuda()
-        G5 = torch.from_numpy(synth.upstream_grad(X5.shape[0], T)).cuda()
-        ws5 = torch.empty(api.ecc_workspace_bytes(X5.shape[1:], X5.shape[0], T), dtype=torch.uint8, device="cuda")
-        chi = torch.empty((X5.shape[0], T), dtype=torch.float32, device="cuda")
+        G5 = torch.from_numpy(synth.upstream_grad(B5, T)).cuda()
+        ws5 = torch.empty(api.ecc_workspace_bytes(X5.shape[1:], B5, T), dtype=torch.uint8, device="cuda")
+        st5 = torch.empty(api.ecc_soft_state_bytes(X5.shape[1:], B5), dtype=torch.uint8, device="cuda")
+        chi = torch.empty((B5, T), dtype=torch.float32, device="cuda")
         gx = torch.empty_like(g5)
         dt_ = torch.empty_like(chi)
-        du_ = torch.empty((X5.shape[0], T, 2), dtype=torch.float32, device="cuda")
+        du_ = torch.empty((B5, T, 2), dtype=torch.float32, device="cuda")
+        a5 = (2, u5, p["alpha"], tau5, p["lam"])
 
-        def step5():
-            api.ecc_soft_fwd(g5, 2, u5, p["alpha"], tau5, p["lam"], chi=chi, workspace=ws5)
-            api.ecc_soft_bwd(g5, 2, u5, p["alpha"], tau5, p["lam"], grad_chi=G5, grad_X=gx, dchi_dtau=dt_,
-                             dchi_du=du_, workspace=ws5)
-        st5 = torch.empty(api.ecc_soft_state_bytes(X5.shape[1:], X5.shape[0]), dtype=torch.uint8, device="cuda")
+        def fwd(g=g5):
+            api.ecc_soft_fwd(g, *a5, chi=chi, workspace=ws5)
 
-        def step5s():
-            api.ecc_soft_fwd_save(g5, 2, u5, p["alpha"], tau5, p["lam"], chi=chi, dchi_dtau=dt_, dchi_du=du_, state=st5,
-                                  workspace=ws5)
-            api.ecc_soft_bwd_saved(g5, 2, u5, p["alpha"], tau5, p["lam"], st5, grad_chi=G5, grad_X=gx, workspace=ws5)
-        ms5s = time_steps(step5s, args.steps, args.warmup)
-        ms5sf = time_steps(lambda: api.ecc_soft_fwd_save(g5, 2, u5, p["alpha"], tau5, p["lam"], chi=chi, dchi_dtau=dt_,
-                                                         dchi_du=du_, state=st5, workspace=ws5), args.steps, args.warmup)
-        log(f"[bench] C5 soft saved-state: fwd_save+bwd_saved {ms5s:.4f} ms, fwd_save {ms5sf:.4f} ms")
-        ms5 = time_steps(step5, args.steps, args.warmup)
-        ms5f = time_steps(lambda: api.ecc_soft_fwd(g5, 2, u5, p["alpha"], tau5, p["lam"], chi=chi, workspace=ws5),
-                          args.steps, args.warmup)
+        def bwd(g=g5):
+            api.ecc_soft_bwd(g, *a5, grad_chi=G5, grad_X=gx, dchi_dtau=dt_, dchi_du=du_, workspace=ws5)
+
+        def fwd_save(g=g5):
+            api.ecc_soft_fwd_save(g, *a5, chi=chi, dchi_dtau=dt_, dchi_du=du_, state=st5, workspace=ws5)
+
+        def bwd_saved(g=g5):
+            api.ecc_soft_bwd_saved(g, *a5, st5, grad_chi=G5, grad_X=gx, workspace=ws5)
+
+        k_f, ms_f, _ = kernel_ms(api, fwd, args.steps, args.warmup)
+        k_b, ms_b, _ = kernel_ms(api, bwd, args.steps, args.warmup)
+        k_fs, ms_fs, _ = kernel_ms(api, fwd_save, args.steps, args.warmup)
+        k_bs, ms_bs, _ = kernel_ms(api, bwd_saved, args.steps, args.warmup)
+        ms_pair = time_steps(lambda: (fwd(), bwd()), args.steps, args.warmup)
+        ms_saved = time_steps(lambda: (fwd_save(), bwd_saved()), args.steps, args.warmup)
+        # cold: rotate over copies of the batch totalling more than the Infinity Cache
+        copies = rotating(lambda: g5.clone(), X5.nbytes)
+        it = [0]
+
+        def cold_step():
+            it[0] = (it[0] + 1) % len(copies)
+            fwd_save(copies[it[0]])
+            bwd_saved(copies[it[0]])
+        ms_cold = time_steps(cold_step, max(args.steps, 2 * len(copies)), len(copies))
         K = int((api.ecc_coeff(g5, 2) != 0).sum().item())
-        extra["c5_soft"] = {"workload": "C5: soft fwd+bwd, 32 x 512^2 float32, T=128, lambda=20, alpha=0.01",
-                            "ms_fwd_plus_bwd": round(ms5, 4), "ms_fwd": round(ms5f, 4),
-                            "critical_vertices": K, "pairs_evaluated": K * T * 3,
-                            "dense_pairs": int(X5.size) * T}
-        log(f"[bench] C5 soft: fwd+bwd {ms5:.3f} ms, fwd {ms5f:.3f} ms, K={K}")
-        if args.only == "c5":
+        pairs = K * T  # (critical vertex, threshold) pairs: the sigmoids Eq. 6 / Eq. 8-10 need per pass
+        nb = float(X5.nbytes)
+        extra["c5_soft"] = {"workload": "C5: soft fwd+bwd, 32 x 512^2 float32, T=128, lambda=20, alpha=0.01; outputs chi, "
+                                        "dchi/dtau, dchi/du, grad_X",
+                            "ms_fwd_plus_bwd": round(ms_saved, 4),
+                            "ms_fwd_plus_bwd_cold": round(ms_cold, 4), "cold_copies": len(copies),
+                            "entry_points": "ecc_soft_fwd_save (chi, dchi/dtau, dchi/du, saved critical vertices) + "
+                                            "ecc_soft_bwd_saved (grad_X from the saved list)",
+                            "ms_fwd_save": round(ms_fs, 4), "ms_bwd_saved": round(ms_bs, 4),
+                            "stateless_pair": {"entry_points": "ecc_soft_fwd + ecc_soft_bwd (two sweeps of the grid)",
+                                               "ms_fwd_plus_bwd": round(ms_pair, 4), "ms_fwd": round(ms_f, 4),
+                                               "ms_bwd": round(ms_b, 4)},
+                            "critical_vertices": K, "pairs_per_pass": pairs, "dense_pairs": int(X5.size) * T,
+                            "pairs_note": "pairs_per_pass = critical vertices x thresholds, what Eq. 6 / Eq. 8-10 need; of "
+                                          "these, entries whose sigmoids are all 0 or 1 to 2^-64 are not evaluated (a tilt "
+                                          "of 0.01 per pixel against thresholds over the field's own range saturates most "
+                                          "of the image), so the rates below are upper bounds of the sigmoids evaluated",
+                            "gpairs_per_s_fwd_kernel": round(pairs / (k_f * 1e-3) / 1e9, 2),
+                            "gpairs_per_s_fwd_save_kernel": round(pairs / (k_fs * 1e-3) / 1e9, 2),
+                            "gpairs_per_s_bwd_kernel": round(pairs / (k_b * 1e-3) / 1e9, 2),
+                            "gpairs_per_s_bwd_saved_kernel": round(pairs / (k_bs * 1e-3) / 1e9, 2)}
+        note5 = ("bytes floor: the grid read once (forward), read + grad_X written (backward); the kernels are bound by "
+                 "launch latency and the march of 3072 short-lived waves, not by bandwidth")
+        rooflines["c5_fwd"] = roofline_hbm(nb, k_f, "soft2d_fwd_kernel", counters.get("c5_fwd"), note=note5)
+        rooflines["c5_bwd"] = roofline_hbm(2 * nb, k_b, "soft2d_bwd_kernel", counters.get("c5_bwd"), note=note5)
+        rooflines["c5_fwd_save"] = roofline_hbm(nb, k_fs, "soft2d_fwd_save_kernel", counters.get("c5_fwd_save"), note=note5)
+        rooflines["c5_bwd_saved"] = roofline_hbm(nb, k_bs, "soft2d_bwd_saved_kernel (grad_X written; the grid is not read)",
+                                                 counters.get("c5_bwd_saved"), note=note5)
+        log(f"[bench] C5 soft: fwd_save+bwd_saved {ms_saved:.4f} ms (cold {ms_cold:.4f}); fwd_save {ms_fs:.4f} (kernel "
+            f"{k_fs:.4f}), bwd_saved {ms_bs:.4f} (kernel {k_bs:.4f}); stateless fwd+bwd {ms_pair:.4f}: fwd {ms_f:.4f} "
+            f"(kernel {k_f:.4f}), bwd {ms_b:.4f} (kernel {k_b:.4f}); K={K}")
+        if only == "c5":
             return
-        if not args.quick:
+        if full:
             from oracle import ecc_oracle as O
             t0 = time.perf_counter()
             O.soft_fwd_batch(X5[:2], p["u"], p["alpha"], p["tau"], p["lam"])
             O.soft_bwd_batch(X5[:2], p["u"], p["alpha"], p["tau"], p["lam"], G5[:2].cpu().numpy())
             dt = time.perf_counter() - t0
-            extra["c5_soft"]["cpu_oracle_ms_full_batch_extrapolated"] = round(dt / 2 * X5.shape[0] * 1e3, 1)
+            extra["c5_soft"]["cpu_oracle_ms_full_batch_extrapolated"] = round(dt / 2 * B5 * 1e3, 1)
             extra["c5_soft"]["cpu_oracle_sample"] = "2 of 32 items, numpy float64"
+        del copies, g5
+        torch.cuda.empty_cache()
 
     # ---------------- soft forward + backward on a volume (fused 3D path) ---------
-    if args.only == "" and not args.quick:
+    if full:
         V = synth.grf((256, 256, 256), 3.0, 5151)[None]
         T3 = 64
         gv = torch.from_numpy(V).cuda()
@@ -334,9 +466,20 @@ def main():
         msv = time_steps(stepv, args.steps, args.warmup)
         extra["soft_3d"] = {"workload": "soft fwd+bwd, one 256^3 float32 GRF sigma=3, T=64, lambda=20, alpha=0.01",
                             "ms_fwd_plus_bwd": round(msv, 4)}
-        log(f"[bench] soft 3D 256^3: fwd+bwd {msv:.3f} ms")
+        log(f"[bench] soft 3D 256^3: fwd+bwd {msv:.4f} ms")
         del gv, gxv, wsv
+        torch.cuda.empty_cache()
 
+    # ---------------- the grid sizes of the paper's Tables 1-2 -------------------
+    if want("sizes"):
+        extra["size_sweep"] = {"workload": "one float32 smoothed random field per size of the paper's Tables 1-2, 1024 "
+                                           "bins, range found on the device (whole call); 8192^2 and 1024^3 are periodic "
+                                           "fields tiled 2x",
+                               "rows": size_rows(args, np, torch, api, synth, field_2d, field_3d)}
+        if only == "sizes":
+            return
+
+    extra["rooflines"] = rooflines
     line = {
         "metric": "hard_ecc_throughput", "value": round(value, 2), "unit": "Gvoxel/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
@@ -347,7 +490,7 @@ def main():
                                "vertices, which are binned afterwards)", "bins": BINS, "batch": 16},
         "roofline": roofline,
     }
-    if not args.quick:
+    if full:
         line["cpu_baseline"] = cpu
     line["extra"] = extra
     print(json.dumps(line), flush=True)
