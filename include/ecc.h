@@ -45,12 +45,15 @@ extern "C" {
 /*
  * Element types.  ECC_U8, ECC_U16 and ECC_F32 are read as they are by every
  * entry point.  The others are taken by the hard curves only (ecc_hard,
- * ecc_hard_top, ecc_hard_ex): the grid is first rounded to float32 (to nearest
- * even) into the workspace and the curve is that of the rounded grid.  Rounding
- * is monotone, so every set {p : fl32(X(p)) <= t} is a sublevel set of X and the
- * curve is exact for the float32 thresholds it is read at (float16, bfloat16 and
- * int16 convert without rounding at all); values beyond the float32 range are
- * not allowed.  They need the larger workspace of ecc_workspace_bytes_dtype.
+ * ecc_hard_static, ecc_hard_top, ecc_hard_ex).  ECC_F16, ECC_BF16 and ECC_I16
+ * widen to float32 without rounding and are loaded directly by the strip / tube
+ * sweeps (two bytes per vertex of memory traffic).  ECC_I32 and ECC_F64 -- and
+ * the two-byte types on the shapes the plain kernels take -- are first rounded
+ * to float32 (to nearest even) into the workspace, and the curve is that of the
+ * rounded grid: rounding is monotone, so every set {p : fl32(X(p)) <= t} is a
+ * sublevel set of X and the curve is exact for the float32 thresholds it is
+ * read at; values beyond the float32 range are not allowed.  All five need the
+ * larger workspace of ecc_workspace_bytes_dtype.
  */
 typedef enum {
   ECC_U8 = 0, ECC_U16 = 1, ECC_F32 = 2,

@@ -207,11 +207,11 @@ static int hard_common(int conv, const char* who, const void* grid, int ndim, co
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (converted_dtype(dtype)) {
-    // rounded to float32 behind the path's own workspace, then the float32 path; one bin per level
-    // (integer types without a range) is the equal-width table over (-1, B-1], or the lower edges
-    // of the one over [0, B) for superlevel sets
+    // room for a float32 copy behind the path's own workspace (the strip / tube sweeps read float16,
+    // bfloat16 and int16 directly and leave it unused); one bin per level (integer types without a
+    // range) is the equal-width table over (-1, B-1], or the lower edges of the one over [0, B) for
+    // superlevel sets
     float* f32 = reinterpret_cast<float*>(static_cast<char*>(workspace) + base_bytes);
-    if ((rc = device_status(ecc::launch_convert(grid, dtype, s.N * s.batch, f32, st), who)) != ECC_OK) return rc;
     bool have_range = range != nullptr;
     if (!have_range && integer_dtype(dtype)) {
       have_range = true;
@@ -219,8 +219,8 @@ static int hard_common(int conv, const char* who, const void* grid, int ndim, co
       lo = super ? 0.0 : -1.0;
       hi = super ? (double)bins : (double)bins - 1.0;
     }
-    return device_status(ecc::launch_hard(f32, s, ECC_F32, bins, have_range, lo, hi, curve, workspace, st, nullptr,
-                                          conv),
+    return device_status(ecc::launch_hard(grid, s, dtype, bins, have_range, lo, hi, curve, workspace, st, nullptr,
+                                          conv, f32),
                          who);
   }
   return device_status(ecc::launch_hard(grid, s, dtype, bins, range != nullptr, lo, hi, curve, workspace, st,

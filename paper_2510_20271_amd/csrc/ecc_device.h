@@ -164,6 +164,27 @@ __device__ __forceinline__ int bin_table(float x, const float* __restrict__ t, i
 
 template <typename T> __device__ __forceinline__ float as_float(T v) { return (float)v; }
 
+// Two-byte element types the strip / tube sweeps also load directly (all three widen to float32
+// without rounding, so the sweep runs on exactly the grid's values).
+struct Bf16 {
+  uint16_t bits;
+  __device__ __forceinline__ operator float() const { return __uint_as_float((unsigned)bits << 16); }
+};
+typedef _Float16 F16;
+// float32 view of a two-byte element given as the low 16 bits of `b`
+template <typename T> __device__ __forceinline__ float widen16(unsigned b);
+template <> __device__ __forceinline__ float widen16<uint16_t>(unsigned b) { return (float)(b & 0xffffu); }
+template <> __device__ __forceinline__ float widen16<int16_t>(unsigned b) { return (float)(int16_t)(uint16_t)b; }
+template <> __device__ __forceinline__ float widen16<F16>(unsigned b) {
+  return (float)__builtin_bit_cast(F16, (uint16_t)b);
+}
+template <> __device__ __forceinline__ float widen16<Bf16>(unsigned b) { return __uint_as_float(b << 16); }
+// element types that have a -0 (made +0 as the value is loaded, so that equal values differ by +0)
+template <typename T> struct HasNegZero { static constexpr bool value = false; };
+template <> struct HasNegZero<float> { static constexpr bool value = true; };
+template <> struct HasNegZero<F16> { static constexpr bool value = true; };
+template <> struct HasNegZero<Bf16> { static constexpr bool value = true; };
+
 // ---- tilted filtration (directional curves) ------------------------------------
 // The sweeps can add a linear function of the vertex's coordinates to the field as
 // they load it: Y(p) = X(p) + t(p), t = fl(fl(fl(a_x x) + fl(a_y y)) + fl(a_z z))

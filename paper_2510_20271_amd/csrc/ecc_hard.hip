@@ -368,13 +368,13 @@ static void launch_sweep_generic(const void* grid, const Shape& s, bool levels, 
 
 hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
                        double lo, double hi, int64_t* curve, void* ws, hipStream_t st, const DirArgs* dir,
-                       int conv) {
+                       int conv, float* f32_scratch) {
   const int super = (conv & kConvSuper) ? 1 : 0;
   HardHeader* hdr = static_cast<HardHeader*>(ws);
   char* wsb = static_cast<char*>(ws);
   float* table = reinterpret_cast<float*>(wsb + kTableOffset);
   unsigned long long* hist = reinterpret_cast<unsigned long long*>(curve);
-  const bool is_float = (dtype == 2);
+  const bool is_float = (dtype == 2 || dtype == 3 || dtype == 5 || dtype == 6);  // float32 / 16 / 64, bfloat16
   const bool levels = !have_range && !is_float;
   const bool device_range = !have_range && is_float;
   const int64_t total = s.N * s.batch;
@@ -389,6 +389,18 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
   // (a directional call comes here only for shapes the strip / tube sweeps take)
   const bool fast2d = (dir || (!force_generic && !tiny)) && sweep2d_supported(s, bins);
   const bool fast3d = (dir || (!force_generic && !tiny)) && !fast2d && sweep3d_supported(s, bins);
+  // Element types beyond uint8 / uint16 / float32.  The strip / tube sweeps load float16, bfloat16
+  // and int16 as they are (all three widen to float32 exactly); the other kernels, and int32 /
+  // float64 everywhere, get a float32 copy rounded to nearest even.
+  if (dtype >= 3) {
+    const bool native = (dtype == 3 || dtype == 6 || dtype == 7) && (fast2d || fast3d) && !(device_range && two_pass);
+    if (!native) {
+      hipError_t e = launch_convert(grid, dtype, total, f32_scratch, st);
+      if (e != hipSuccess) return e;
+      grid = f32_scratch;
+      dtype = 2;
+    }
+  }
   const int64_t hist_len = s.batch * bins;
   int prep_blocks = (int)((hist_len + kBlock - 1) / kBlock);
   prep_blocks = prep_blocks > 1024 ? 1024 : prep_blocks;
@@ -404,21 +416,20 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     la.lists = reinterpret_cast<float2*>(wsb + kTableOffset + table_bytes(bins) + counter_bytes(s));
     // no more sub-lists than blocks that append to them (a block uses one sub-list);
     // the room of the unused ones goes to the others
-    const unsigned blocks = fast2d ? sweep2d_list_blocks(s) : sweep3d_list_blocks(s);
+    const unsigned blocks = fast2d ? sweep2d_list_blocks(s, dtype) : sweep3d_list_blocks(s);
     la.nsub = list_nsub(s);
     la.cap = list_cap(s);
     while (la.nsub > 1 && la.nsub > blocks) {
       la.nsub /= 2;
       la.cap *= 2;
     }
-    const float* gf = static_cast<const float*>(grid);
     int64_t ib = (std::max<int64_t>(s.batch * la.nsub, hist_len) + 255) / 256;
     ib = ib > 1024 ? 1024 : ib;
     hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)ib), dim3(256), 0, st, hdr, la.counters,
                        (int)(s.batch * la.nsub), hist, hist_len);
     profile_mark(st, false);
-    if (fast2d) launch_sweep2d_list(gf, s, la, st, dir, conv);
-    else launch_sweep3d_list(gf, s, la, st, dir, conv);
+    if (fast2d) launch_sweep2d_list(grid, dtype, s, la, st, dir, conv);
+    else launch_sweep3d_list(grid, dtype, s, la, st, dir, conv);
     profile_mark(st, true);
     // few blocks per item merge into the global histogram (same-address atomics), but
     // enough of them in all to keep the list reads in flight
@@ -515,8 +526,7 @@ hipError_t launch_hard_dir(const float* grid, const Shape& sv, const float* u, f
 // further element types: rounded to float32 (to nearest even) into the workspace
 // ---------------------------------------------------------------------------
 template <typename S> __device__ __forceinline__ float to_f32(S v) { return (float)v; }
-struct Bf16 { uint16_t bits; };
-template <> __device__ __forceinline__ float to_f32<Bf16>(Bf16 v) { return __uint_as_float((unsigned)v.bits << 16); }
+template <> __device__ __forceinline__ float to_f32<Bf16>(Bf16 v) { return (float)v; }
 
 template <typename S>
 __global__ __launch_bounds__(kBlock) void convert_kernel(const S* __restrict__ src, int64_t n,

@@ -21,9 +21,10 @@ struct Shape {
 constexpr int kConvTop = 1, kConvSuper = 2;
 size_t hard_workspace_bytes(const Shape& s, int bins);
 struct DirArgs;  // directional launch (tilted field, blockIdx.y over directions x items); null: plain
+// dtype: any ecc_dtype code; f32_scratch: room for a float32 copy of the grid (codes 3..7 only)
 hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
                        double lo, double hi, int64_t* curve, void* ws, hipStream_t st,
-                       const DirArgs* dir = nullptr, int conv = 0);
+                       const DirArgs* dir = nullptr, int conv = 0, float* f32_scratch = nullptr);
 // directional curves; sv: the shape with batch = directions x items, batch: items per direction
 size_t hard_dir_workspace_bytes(const Shape& sv, int bins);
 hipError_t launch_hard_dir(const float* grid, const Shape& sv, const float* u, float alpha, int batch,
@@ -56,15 +57,15 @@ bool sweep2d_supported(const Shape& s, int bins);
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st, const unsigned* run_if, const DirArgs* dir = nullptr, int conv = 0);
-void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
+void launch_sweep2d_list(const void* grid, int dtype, const Shape& s, const ListArgs& la, hipStream_t st,
                          const DirArgs* dir = nullptr, int conv = 0);
-unsigned sweep2d_list_blocks(const Shape& s);  // blocks per item of that launch
+unsigned sweep2d_list_blocks(const Shape& s, int dtype);  // blocks per item of that launch
 
 bool sweep3d_supported(const Shape& s, int bins);
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st, const unsigned* run_if, const DirArgs* dir = nullptr, int conv = 0);
-void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
+void launch_sweep3d_list(const void* grid, int dtype, const Shape& s, const ListArgs& la, hipStream_t st,
                          const DirArgs* dir = nullptr, int conv = 0);
 unsigned sweep3d_list_blocks(const Shape& s);
 

@@ -88,14 +88,19 @@ template <> struct Raw4<float> {
   }
   __device__ __forceinline__ float get(int e) const { return __uint_as_float(v[e]); }
 };
-template <> struct Raw4<uint16_t> {
+// two-byte elements: one 8-byte load, widened to float32 element by element
+template <typename T> struct Raw4x16 {
   typedef __attribute__((ext_vector_type(2))) unsigned vec;
   vec v;
   __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
     v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
   }
-  __device__ __forceinline__ float get(int e) const { return (float)((v[e >> 1] >> (16 * (e & 1))) & 0xffffu); }
+  __device__ __forceinline__ float get(int e) const { return widen16<T>(v[e >> 1] >> (16 * (e & 1))); }
 };
+template <> struct Raw4<uint16_t> : Raw4x16<uint16_t> {};
+template <> struct Raw4<int16_t> : Raw4x16<int16_t> {};
+template <> struct Raw4<F16> : Raw4x16<F16> {};
+template <> struct Raw4<Bf16> : Raw4x16<Bf16> {};
 template <> struct Raw4<uint8_t> {
   unsigned v;
   __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
@@ -109,11 +114,15 @@ template <> struct Raw1<float> {
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
   }
 };
-template <> struct Raw1<uint16_t> {
+template <typename T> struct Raw1x16 {
   static __device__ __forceinline__ float get(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
-    return (float)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0);
+    return widen16<T>((unsigned)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0));
   }
 };
+template <> struct Raw1<uint16_t> : Raw1x16<uint16_t> {};
+template <> struct Raw1<int16_t> : Raw1x16<int16_t> {};
+template <> struct Raw1<F16> : Raw1x16<F16> {};
+template <> struct Raw1<Bf16> : Raw1x16<Bf16> {};
 template <> struct Raw1<uint8_t> {
   static __device__ __forceinline__ float get(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
     return (float)(uint8_t)__builtin_amdgcn_raw_buffer_load_b8(r, voff, soff, 0);
@@ -202,7 +211,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
       asm volatile("" : "+v"(f));
     }
     else if (Tilt::kOn) f = add_rn(f, add_rn(lx[e], mul_rn(tilt.ay, (float)y)));
-    else if (sizeof(T) == 4) f += 0.0f;
+    else if (HasNegZero<T>::value) f += 0.0f;
     if (EDGE) f = ok[e] ? f : (Tilt::kTop ? -INFINITY : INFINITY);
     return f;
   };

@@ -87,7 +87,8 @@ __global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__
 
 constexpr size_t kRingBytes2d = ring_bytes2d<float2>();
 
-template <typename T>
+// LV: the type also comes with one bin per level (uint8 / uint16 grids without a range)
+template <typename T, bool LV = false>
 static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
                        const float* table, unsigned long long* hist, hipStream_t st,
                        const unsigned* run_if, const DirArgs* dir, int conv) {
@@ -107,11 +108,13 @@ static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, 
       return;
     }
   }
-#define ECC_MODE(M)                       \
-  do {                                    \
-    if (levels) ECC_GO(true, false, M);   \
-    else if (tlds) ECC_GO(false, true, M); \
-    else ECC_GO(false, false, M);         \
+#define ECC_MODE(M)                                  \
+  do {                                               \
+    if constexpr (LV) {                              \
+      if (levels) { ECC_GO(true, false, M); break; } \
+    }                                                \
+    if (tlds) ECC_GO(false, true, M);                \
+    else ECC_GO(false, false, M);                    \
   } while (0)
   switch (mode_of_conv(conv)) {
     case kTopCells: ECC_MODE(kTopCells); break;
@@ -123,16 +126,20 @@ static void launch2d_t(const void* grid, const Shape& s, bool levels, int bins, 
 #undef ECC_GO
 }
 
-void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
-                         const DirArgs* dir, int conv) {
-  const Plan2d pl = plan2d<float>(s);
+template <typename T>
+static void launch2d_list_t(const void* grid, const Shape& s, const ListArgs& la, hipStream_t st, const DirArgs* dir,
+                            int conv) {
+  const Plan2d pl = plan2d<T>(s);
   const DirArgs none = {nullptr, 0.f, 1, 2};
+  const T* p = static_cast<const T*>(grid);
 #define ECC_LIST(M, DIR)                                                                                 \
-  hipLaunchKernelGGL((sweep2d_list_kernel<float, M>), pl.grid, dim3(256), kRingBytes2d, st, grid, (int)s.H, \
+  hipLaunchKernelGGL((sweep2d_list_kernel<T, M>), pl.grid, dim3(256), kRingBytes2d, st, p, (int)s.H, \
                      (int)s.W, s.N, pl.nstrip, pl.nseg, pl.rows_per_seg, la, DIR)
-  if (dir) {
-    ECC_LIST(kTilted, *dir);
-    return;
+  if constexpr (std::is_same<T, float>::value) {
+    if (dir) {
+      ECC_LIST(kTilted, *dir);
+      return;
+    }
   }
   switch (mode_of_conv(conv)) {
     case kTopCells: ECC_LIST(kTopCells, none); break;
@@ -143,7 +150,19 @@ void launch_sweep2d_list(const float* grid, const Shape& s, const ListArgs& la, 
 #undef ECC_LIST
 }
 
-unsigned sweep2d_list_blocks(const Shape& s) { return plan2d<float>(s).grid.x; }
+// dtype: float32, float16 or bfloat16 (the floating types whose range is found on the device)
+void launch_sweep2d_list(const void* grid, int dtype, const Shape& s, const ListArgs& la, hipStream_t st,
+                         const DirArgs* dir, int conv) {
+  switch (dtype) {
+    case 3: launch2d_list_t<F16>(grid, s, la, st, nullptr, conv); break;
+    case 6: launch2d_list_t<Bf16>(grid, s, la, st, nullptr, conv); break;
+    default: launch2d_list_t<float>(grid, s, la, st, dir, conv); break;
+  }
+}
+
+unsigned sweep2d_list_blocks(const Shape& s, int dtype) {
+  return dtype == 2 ? plan2d<float>(s).grid.x : plan2d<F16>(s).grid.x;
+}
 
 bool sweep2d_supported(const Shape& s, int bins) {
   // value ring (32 KiB) + queues (4 KiB) + histogram must fit the 64 KiB of LDS a block may ask for
@@ -154,8 +173,11 @@ void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, in
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st, const unsigned* run_if, const DirArgs* dir, int conv) {
   switch (dtype) {
-    case 0: launch2d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
-    case 1: launch2d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 0: launch2d_t<uint8_t, true>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 1: launch2d_t<uint16_t, true>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 3: launch2d_t<F16>(grid, s, false, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 6: launch2d_t<Bf16>(grid, s, false, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 7: launch2d_t<int16_t>(grid, s, false, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
     default: launch2d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir, conv); break;
   }
 }

@@ -93,11 +93,15 @@ template <> struct Load<float> {
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, v, s, 0));
   }
 };
-template <> struct Load<uint16_t> {
-  static __device__ __forceinline__ uint16_t get(__amdgpu_buffer_rsrc_t r, unsigned v, unsigned s) {
-    return (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, v, s, 0);
+template <typename T> struct Load16 {  // two-byte elements, kept as they are until they are converted
+  static __device__ __forceinline__ T get(__amdgpu_buffer_rsrc_t r, unsigned v, unsigned s) {
+    return __builtin_bit_cast(T, (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, v, s, 0));
   }
 };
+template <> struct Load<uint16_t> : Load16<uint16_t> {};
+template <> struct Load<int16_t> : Load16<int16_t> {};
+template <> struct Load<F16> : Load16<F16> {};
+template <> struct Load<Bf16> : Load16<Bf16> {};
 template <> struct Load<uint8_t> {
   static __device__ __forceinline__ uint8_t get(__amdgpu_buffer_rsrc_t r, unsigned v, unsigned s) {
     return (uint8_t)__builtin_amdgcn_raw_buffer_load_b8(r, v, s, 0);
@@ -334,7 +338,7 @@ __device__ __forceinline__ void sweep_tube(const T* __restrict__ g, int64_t item
         asm volatile("" : "+v"(f));  // opaque: a negated source operand downstream would make -0 of it
       }
       else if (TiltT::kOn) f = add_rn(f, add_rn(txy[j], tz));
-      else if (sizeof(T) == 4) f += 0.0f;  // -0 -> +0 so that equal values differ by +0
+      else if (HasNegZero<T>::value) f += 0.0f;  // -0 -> +0 so that equal values differ by +0
       if (SAFE) f = okj[j] ? f : (TiltT::kTop ? -INFINITY : INFINITY);
       dst[j] = f;
     }

@@ -80,7 +80,8 @@ __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__
   range.commit(la.hdr);
 }
 
-template <typename T>
+// LV: the type also comes with one bin per level (uint8 / uint16 grids without a range)
+template <typename T, bool LV = false>
 static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, const HardHeader* hdr,
                        const float* table, unsigned long long* hist, hipStream_t st,
                        const unsigned* run_if, const DirArgs* dir, int conv) {
@@ -101,11 +102,13 @@ static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, 
       return;
     }
   }
-#define ECC_MODE(M)                       \
-  do {                                    \
-    if (levels) ECC_GO(true, false, M);   \
-    else if (tlds) ECC_GO(false, true, M); \
-    else ECC_GO(false, false, M);         \
+#define ECC_MODE(M)                                  \
+  do {                                               \
+    if constexpr (LV) {                              \
+      if (levels) { ECC_GO(true, false, M); break; } \
+    }                                                \
+    if (tlds) ECC_GO(false, true, M);                \
+    else ECC_GO(false, false, M);                    \
   } while (0)
   switch (mode_of_conv(conv)) {
     case kTopCells: ECC_MODE(kTopCells); break;
@@ -117,17 +120,21 @@ static void launch3d_t(const void* grid, const Shape& s, bool levels, int bins, 
 #undef ECC_GO
 }
 
-void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, hipStream_t st,
-                         const DirArgs* dir, int conv) {
-  const Plan3d pl = plan3d<float>(s);
+template <typename T>
+static void launch3d_list_t(const void* grid, const Shape& s, const ListArgs& la, hipStream_t st, const DirArgs* dir,
+                            int conv) {
+  const Plan3d pl = plan3d<T>(s);
   const DirArgs none = {nullptr, 0.f, 1, 3};
+  const T* p = static_cast<const T*>(grid);
 #define ECC_LIST(M, DIR)                                                                                  \
-  hipLaunchKernelGGL((sweep3d_list_kernel<float, kRows3d, M>), pl.grid, dim3(256), kFixedLds3d, st, grid,   \
+  hipLaunchKernelGGL((sweep3d_list_kernel<T, kRows3d, M>), pl.grid, dim3(256), kFixedLds3d, st, p,   \
                      (int)s.D, (int)s.H, (int)s.W, s.N, pl.nstrip, pl.ngroup, pl.nseg, pl.planes_per_seg, la, \
                      DIR)
-  if (dir) {
-    ECC_LIST(kTilted, *dir);
-    return;
+  if constexpr (std::is_same<T, float>::value) {
+    if (dir) {
+      ECC_LIST(kTilted, *dir);
+      return;
+    }
   }
   switch (mode_of_conv(conv)) {
     case kTopCells: ECC_LIST(kTopCells, none); break;
@@ -136,6 +143,16 @@ void launch_sweep3d_list(const float* grid, const Shape& s, const ListArgs& la, 
     default: ECC_LIST(kPlain, none); break;
   }
 #undef ECC_LIST
+}
+
+// dtype: float32, float16 or bfloat16 (the floating types whose range is found on the device)
+void launch_sweep3d_list(const void* grid, int dtype, const Shape& s, const ListArgs& la, hipStream_t st,
+                         const DirArgs* dir, int conv) {
+  switch (dtype) {
+    case 3: launch3d_list_t<F16>(grid, s, la, st, nullptr, conv); break;
+    case 6: launch3d_list_t<Bf16>(grid, s, la, st, nullptr, conv); break;
+    default: launch3d_list_t<float>(grid, s, la, st, dir, conv); break;
+  }
 }
 
 unsigned sweep3d_list_blocks(const Shape& s) { return plan3d<float>(s).grid.x; }
@@ -151,8 +168,11 @@ void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, in
                     const HardHeader* hdr, const float* table, unsigned long long* hist,
                     hipStream_t st, const unsigned* run_if, const DirArgs* dir, int conv) {
   switch (dtype) {
-    case 0: launch3d_t<uint8_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
-    case 1: launch3d_t<uint16_t>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 0: launch3d_t<uint8_t, true>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 1: launch3d_t<uint16_t, true>(grid, s, levels, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 3: launch3d_t<F16>(grid, s, false, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 6: launch3d_t<Bf16>(grid, s, false, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
+    case 7: launch3d_t<int16_t>(grid, s, false, bins, hdr, table, hist, st, run_if, nullptr, conv); break;
     default: launch3d_t<float>(grid, s, levels, bins, hdr, table, hist, st, run_if, dir, conv); break;
   }
 }
