@@ -158,16 +158,40 @@ __global__ __launch_bounds__(kBlock) void sweep_generic_kernel(
 // block (0, 0) also leaves it, with the factor of the bin guess, in the
 // workspace for the histogram-mode sweep that runs if a list overflowed.
 // lower != 0: superlevel curves (lower bin edges, bin = last threshold <= value).
-__global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, float* __restrict__ table, int bins,
+// Few, large blocks: every block ends by adding its histogram to the global one, and atomics on
+// one address queue up behind each other (256 blocks per item cost 10 us there, 32 cost one).
+constexpr int kBinBlock = 1024;
+__global__ __launch_bounds__(kBinBlock) void binlist_kernel(ListArgs la, float* __restrict__ table, int bins,
                                                          unsigned long long* __restrict__ hist, int lower) {
   extern __shared__ int lhist[];
   float* ltable = reinterpret_cast<float*>(lhist + bins);
+  // Wave w of block x (16 waves) takes the sub-lists 16x + w, 16x + w + 16 gridDim.x, ... of item y.  What it
+  // needs from memory is requested in as few dependent steps as possible: the fill counts of all
+  // its sub-lists at once (lane k holds the k-th), then the first 256 entries of its first
+  // sub-list, both before the header is looked at and the table is built.
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+  const unsigned sl0 = blockIdx.x * (kBinBlock / kWave) + wv, step = gridDim.x * (kBinBlock / kWave);
+  unsigned mycount = 0;
+  {
+    const unsigned sl = sl0 + (unsigned)lane * step;
+    if (sl < la.nsub) mycount = min(la.counters[blockIdx.y * la.nsub + sl], la.cap);
+  }
+  const unsigned n0 = sl0 < la.nsub ? (unsigned)__builtin_amdgcn_readlane((int)mycount, 0) : 0u;
+  float2 e0[4];
+  {
+    const float2* list = la.lists + (size_t)(blockIdx.y * la.nsub + (sl0 < la.nsub ? sl0 : 0u)) * la.cap;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const unsigned i = q * kWave + lane;
+      e0[q] = i < n0 ? list[i] : make_float2(0.f, 0.f);
+    }
+  }
   const double lo_d = (double)key_float(la.hdr->min_key), hi_d = (double)key_float(la.hdr->max_key);
   const float lo = __double2float_rn(lo_d), scale = bin_scale(bins, lo_d, hi_d);
   const bool first = blockIdx.x == 0 && blockIdx.y == 0;
   const bool overflow = la.hdr->overflow != 0u;  // the two-pass sweep that follows does the work
   if (overflow && !first) return;
-  for (int b = threadIdx.x; b < bins; b += kBlock) {
+  for (int b = threadIdx.x; b < bins; b += kBinBlock) {
     const float t = lower ? threshold_lower_at(b, bins, lo_d, hi_d) : threshold_at(b, bins, lo_d, hi_d);
     ltable[b] = t;
     lhist[b] = 0;
@@ -178,22 +202,43 @@ __global__ __launch_bounds__(kBlock) void binlist_kernel(ListArgs la, float* __r
     la.hdr->scale = scale;
   }
   if (overflow) return;
-  __syncthreads();
-  // block x of item y takes the sub-lists x, x + gridDim.x, ...
-  for (unsigned sl = blockIdx.x; sl < la.nsub; sl += gridDim.x) {
-    const unsigned sub = blockIdx.y * la.nsub + sl;
-    const float2* list = la.lists + (size_t)sub * la.cap;
-    const unsigned n = min(la.counters[sub], la.cap);
-    for (unsigned i = threadIdx.x; i < n; i += kBlock) {
-      const float2 e = list[i];
-      const int b = lower ? bin_super_from_table(e.x, ltable, bins, lo, scale)
-                          : bin_from_table(e.x, ltable, bins, lo, scale);
-      if (b < bins) atomicAdd(&lhist[b], __float_as_int(e.y));
+  __syncthreads();  // histogram cleared, table built
+  auto bin_four = [&](const float2 (&e)[4], unsigned i0, unsigned n) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (i0 + q * kWave + lane < n) {
+        const int b = lower ? bin_super_from_table(e[q].x, ltable, bins, lo, scale)
+                            : bin_from_table(e[q].x, ltable, bins, lo, scale);
+        if (b < bins) atomicAdd(&lhist[b], __float_as_int(e[q].y));
+      }
+    }
+  };
+  for (unsigned sl = sl0, k = 0; sl < la.nsub; sl += step, ++k) {
+    unsigned n;
+    if (k < (unsigned)kWave) {
+      n = (unsigned)__builtin_amdgcn_readlane((int)mycount, (int)k);
+    } else {  // (more than 64 sub-lists per wave: small launches only)
+      n = min(la.counters[blockIdx.y * la.nsub + sl], la.cap);
+    }
+    const float2* list = la.lists + (size_t)(blockIdx.y * la.nsub + sl) * la.cap;
+    unsigned i0 = 0;
+    if (k == 0) {
+      bin_four(e0, 0, n);
+      i0 = 4 * kWave;
+    }
+    for (; i0 < n; i0 += 4 * kWave) {
+      float2 e[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const unsigned i = i0 + q * kWave + lane;
+        e[q] = i < n ? list[i] : make_float2(0.f, 0.f);
+      }
+      bin_four(e, i0, n);
     }
   }
   __syncthreads();
   unsigned long long* out = hist + (int64_t)blockIdx.y * bins;
-  for (int b = threadIdx.x; b < bins; b += kBlock) {
+  for (int b = threadIdx.x; b < bins; b += kBinBlock) {
     const int v = lhist[b];
     if (v != 0) atomicAdd(&out[b], (unsigned long long)(long long)v);
   }
@@ -431,12 +476,12 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     if (fast2d) launch_sweep2d_list(grid, dtype, s, la, st, dir, conv);
     else launch_sweep3d_list(grid, dtype, s, la, st, dir, conv);
     profile_mark(st, true);
-    // few blocks per item merge into the global histogram (same-address atomics), but
-    // enough of them in all to keep the list reads in flight
-    int64_t nblk = 1024 / s.batch;
-    nblk = nblk < 32 ? 32 : (nblk > 256 ? 256 : nblk);
-    if (nblk > (int64_t)la.nsub) nblk = la.nsub;
-    hipLaunchKernelGGL(binlist_kernel, dim3((unsigned)nblk, (unsigned)s.batch), dim3(kBlock),
+    // a wave per sub-list, but no more than about 512 blocks in all and 32 to 64 per item (every block
+    // ends with one atomic per non-empty bin on the item's histogram)
+    int64_t nblk = ((int64_t)la.nsub + kBinBlock / kWave - 1) / (kBinBlock / kWave);
+    const int64_t most = std::min<int64_t>(64, std::max<int64_t>(32, 512 / s.batch));
+    nblk = nblk > most ? most : (nblk < 1 ? 1 : nblk);
+    hipLaunchKernelGGL(binlist_kernel, dim3((unsigned)nblk, (unsigned)s.batch), dim3(kBinBlock),
                        (size_t)bins * 2 * sizeof(int), st, la, table, bins, hist, super);
     if (fast2d) launch_sweep2d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir, conv);
     else launch_sweep3d(grid, s, dtype, false, bins, hdr, table, hist, st, &hdr->overflow, dir, conv);
