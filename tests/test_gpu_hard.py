@@ -224,3 +224,29 @@ def test_config_c4_full():
     t = O.thresholds_equal_width(X.min(), X.max(), 1024)
     np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, t))
     assert got[0, -1] == 1
+
+
+# ---- the largest sizes of the paper's Tables 1-2, as the benchmark's size sweep builds them ----
+
+
+def test_table_size_8192_squared():
+    X = np.tile(synth.grf((4096, 4096), 4.0, 4242), (2, 2))[None]   # periodic field: the tiling is seamless
+    got = host(api.ecc_hard(dev(X), 2, 1024))
+    t = O.thresholds_equal_width(X.min(), X.max(), 1024)
+    np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, t))
+    assert got[0, -1] == 1
+
+
+def test_table_size_1024_cubed():
+    # 4 GiB of float32: element offsets pass 2^31, the sweep runs in many z segments
+    X = np.tile(synth.grf((512, 512, 512), 3.0, 4242), (2, 2, 2))[None]
+    lo, hi = float(X.min()), float(X.max())
+    g = dev(X)
+    got = host(api.ecc_hard(g, 3, 1024))
+    got_r = host(api.ecc_hard(g, 3, 1024, range=(lo, hi)))
+    del g
+    torch.cuda.empty_cache()
+    want = OC.ecc_hard_batch(X, O.thresholds_equal_width(lo, hi, 1024))
+    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(got_r, want)
+    assert got[0, -1] == 1
