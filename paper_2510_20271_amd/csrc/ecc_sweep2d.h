@@ -163,11 +163,22 @@ template <typename T> struct RowRegs<T, true> {
 //
 // Tilt: the field swept is Y(p) = X(p) + t(p) with t = fl(fl(a_x x) + fl(a_y y)),
 // every operation a float32 one in this order (directional curves; NoTilt: Y = X).
-template <typename T, typename Sink, bool EDGE, typename Tilt>
+//
+// Lanes lane_lo .. lane_hi put out their vertices; the others are halo lanes.  A strip inside the
+// grid has one halo lane on each side (1 .. 62).  A strip that starts at the grid's first column
+// (open_left) or ends at its last one (open_right) has no neighbour lane there: the vertices beyond
+// the grid are "never before p" (always, for the top-cell order), and the words that would come
+// from the missing lane are set to say so once per chunk.
+// OPEN: the strip may be such a first / last strip (compiled apart, so that the strips inside the
+// grid carry none of this).
+template <typename T, typename Sink, bool EDGE, typename Tilt, bool OPEN = false>
 __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t item_elems, int H, int W,
                                             int c0, int y0, int y1, WaveQueue<Sink>& queue,
                                             float* ring /* [kChunkRows][64][kNC] */, WaveRange& range,
-                                            const Tilt& tilt) {
+                                            const Tilt& tilt, int lane_lo_ = 1, int lane_hi_ = kWave - 2,
+                                            bool open_left_ = false, bool open_right_ = false) {
+  const int lane_lo = OPEN ? lane_lo_ : 1, lane_hi = OPEN ? lane_hi_ : kWave - 2;
+  const bool open_left = OPEN && open_left_, open_right = OPEN && open_right_;
   const int lane = threadIdx.x & (kWave - 1);
   bool ok[kNC];         // column inside the grid
   unsigned voff[kNC];   // byte offset of the column inside a row (clamped into the row)
@@ -177,7 +188,10 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     ok[e] = x >= 0 && x < W;
     voff[e] = (unsigned)min(max(x, 0), W - 1) * (unsigned)sizeof(T);
   }
-  const bool out_lane = lane >= 1 && lane <= kWave - 2;
+  const bool out_lane = lane >= lane_lo && lane <= lane_hi;
+  // what a relation towards a vertex beyond the grid reads: never before p, or always (top-cell order)
+  constexpr unsigned kBeyond = Tilt::kTop ? 0xffffffffu : 0u;
+  const bool first_lane = open_left && lane == 0, last_lane = open_right && lane == kWave - 1;
   const unsigned voff4 = (unsigned)(kNC * lane) * (unsigned)sizeof(T);  // interior strips: from column c0
 
   // the resource starts at the first streamed row (and at column c0 for interior strips)
@@ -271,6 +285,10 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
 #pragma unroll
       for (int e = 0; e < kNC; ++e) range.add_if(original(cur[e]), ok[e]);
     }
+    if (Sink::kTrackRange && !EDGE) {  // the grid's first / last column (wave-uniform conditions)
+      if (open_left) range.add_if(original(cur[0]), first_lane);
+      if (open_right) range.add_if(original(cur[kNC - 1]), last_lane);
+    }
     float dE, dNE, dNW;
     lane_edge_differences(cur[0], cur[kNC - 1], nxt[0], nxt[kNC - 1], dE, dNE, dNW);
 #pragma unroll
@@ -292,11 +310,21 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     next_row();
   };
 
+  // relations of the strip's outermost columns towards vertices beyond the grid (the lane that would
+  // supply the other operand does not exist: the differences pushed there mean nothing)
+  auto beyond_the_grid = [&]() {
+    if (open_left) wNW[0] = first_lane ? kBeyond : wNW[0];
+    if (open_right) {
+      wE[kNC - 1] = last_lane ? kBeyond : wE[kNC - 1];
+      wNE[kNC - 1] = last_lane ? kBeyond : wNE[kNC - 1];
+    }
+  };
   unsigned oN[kNC], oNE[kNC], oNW[kNC];  // bit 0: the row above the first output row
 #pragma unroll
   for (int e = 0; e < kNC; ++e) oN[e] = oNE[e] = oNW[e] = Tilt::kTop ? 0 : 1;  // (reversed order: always before p)
   if (y0 > 0) {
     step();  // warm-up on row y0-1
+    beyond_the_grid();
 #pragma unroll
     for (int e = 0; e < kNC; ++e) {
       oN[e] = wN[e];
@@ -316,6 +344,7 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
       for (int q = 0; q < kPF; ++q) step();
     }
     for (; k < n; ++k) step();
+    beyond_the_grid();
     if constexpr (Sink::kZeroFill) {  // the sink's per-vertex output is 0 except at critical vertices
       for (int j = 0; j < n; ++j) queue.sink.template zero_row<EDGE>(r + j, c0 + kNC * lane, ok, out_lane);
     }
@@ -352,15 +381,22 @@ __device__ __forceinline__ void sweep_strip(const T* __restrict__ g, int64_t ite
     // words of the columns just left / right of this lane's four
     const unsigned E_left = word_from_left(E[kNC - 1]);
     const unsigned pNEE_left = word_from_left(pNE[kNC - 1] | E[kNC - 1]);
-    const unsigned pNW_right = word_from_right(pNW[0]);
+    unsigned pNW_right = word_from_right(pNW[0]);
+    // [p before its neighbour] towards a neighbour beyond the grid, where no lane supplies the word
+    unsigned E_left_ = E_left, pNEE_left_ = pNEE_left;
+    if (open_left) {
+      E_left_ = first_lane ? ~kBeyond : E_left;
+      pNEE_left_ = first_lane ? ~kBeyond : pNEE_left;
+    }
+    if (open_right) pNW_right = last_lane ? ~kBeyond : pNW_right;
     // A chunk uses the top kChunkRows (8) bits of a word, so the four columns of a
     // lane are packed into one word (column e in byte 3-e) and walked in one loop.
     static_assert(kChunkRows * kNC <= 32, "four columns of a chunk must fit one word");
     unsigned pE = 0, pNn = 0, pW = 0, pS = 0, nz = 0;
 #pragma unroll
     for (int e = 0; e < kNC; ++e) {
-      const unsigned El = e > 0 ? E[e - 1] : E_left;                              // [p before its -x neighbour]
-      const unsigned pNEEl = e > 0 ? (pNE[e - 1] | E[e - 1]) : pNEE_left;         // SW or W relation, complemented
+      const unsigned El = e > 0 ? E[e - 1] : E_left_;                             // [p before its -x neighbour]
+      const unsigned pNEEl = e > 0 ? (pNE[e - 1] | E[e - 1]) : pNEE_left_;        // SW or W relation, complemented
       const unsigned pNWr = e + 1 < kNC ? pNW[e + 1] : pNW_right;                 // SE relation, complemented
       const unsigned sE = E[e] & (pNWr | pN[e]);
       const unsigned sN = N[e] & ~(NE[e] & E[e]);
@@ -401,16 +437,35 @@ __device__ __forceinline__ void sweep2d_wave(const T* __restrict__ g, int H, int
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform
   if (unit < nstrip * nseg) {
     const int seg = unit / nstrip, strip = unit - seg * nstrip;
-    const int c0 = strip * kStripOut - kNC;
     const int y0 = seg * rows_per_seg;
     const int y1 = min(y0 + rows_per_seg, H);
-    // 4-element loads need every column in the grid and 4-element alignment of the rows
-    const bool edge = (c0 < 0) || (c0 + kNC * kWave > W) || (W % kNC != 0) ||
-                      ((reinterpret_cast<uintptr_t>(g) & (kNC * sizeof(T) - 1)) != 0);
-    if (edge)
-      sweep_strip<T, Sink, true>(g, N, H, W, c0, y0, y1, queue, ring, range, tilt);
-    else
-      sweep_strip<T, Sink, false>(g, N, H, W, c0, y0, y1, queue, ring, range, tilt);
+    // Strip s puts out the columns [248 s, 248 s + 248).  One aligned 4-element load per lane and row
+    // needs all 256 columns of the wave inside the grid and 4-element alignment of the rows; then
+    // the strip inside the grid starts four columns early (a halo lane on each side), the first
+    // strip starts at column 0 (its first lane puts out, two halo lanes at the end) and the last
+    // strip ends at column W - 1 (its last lane puts out, the lanes before its first column are halo).
+    const bool wide = (W % kNC == 0) && W >= kNC * kWave &&
+                      ((reinterpret_cast<uintptr_t>(g) & (kNC * sizeof(T) - 1)) == 0);
+    if (wide) {
+      int c0 = strip * kStripOut - kNC, lo = 1, hi = kWave - 2;
+      const bool left = strip == 0, right = strip == nstrip - 1;  // (W >= 256: at least two strips)
+      if (left) {
+        c0 = 0;
+        lo = 0;
+        hi = kWave - 3;
+      }
+      if (right) {
+        c0 = W - kNC * kWave;
+        lo = (strip * kStripOut - c0) / kNC;
+        hi = kWave - 1;
+      }
+      if (left || right)
+        sweep_strip<T, Sink, false, Tilt, true>(g, N, H, W, c0, y0, y1, queue, ring, range, tilt, lo, hi, left, right);
+      else
+        sweep_strip<T, Sink, false>(g, N, H, W, c0, y0, y1, queue, ring, range, tilt);
+    } else {
+      sweep_strip<T, Sink, true>(g, N, H, W, strip * kStripOut - kNC, y0, y1, queue, ring, range, tilt);
+    }
   }
 }
 

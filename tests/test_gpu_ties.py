@@ -45,7 +45,9 @@ def _quantised(shape, seed, steps=8.0, sigma=2.0):
 # 2D: several strips of 248 columns (aligned interior strips need W % 4 == 0), several 8-row
 # chunks and segments, ragged last strip / chunk; 3D: several strips of 62 columns, row groups
 # of 4 with a ragged last one, more than one 30-plane chunk and more than one segment
-SHAPES = [(70, 1024), (33, 1000), (129, 503), (300, 250), (16, 249), (1, 600), (600, 8),
+# (widths 256, 260, 500, 512: the first and the last strip start / end at the grid's own edge)
+SHAPES = [(70, 1024), (33, 1000), (129, 503), (300, 250), (16, 249), (1, 600), (600, 8), (40, 256), (24, 260),
+          (18, 500), (20, 512),
           (70, 70, 130), (35, 9, 200), (2, 131, 64), (64, 6, 63), (31, 5, 8)]
 
 
