@@ -94,11 +94,8 @@ ECC_VERTEX, ECC_TOPCELL = 0, 1
 ECC_SUBLEVEL, ECC_SUPERLEVEL = 0, 1
 
 
-def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, workspace=None, top=False,
-             superlevel=False):
-    """grid: [batch, (D,) H, W] device tensor (uint8 / uint16 / float32).
-    Returns the int64 curve [batch, bins].  top=True: top-cell construction (ecc_hard_top);
-    superlevel=True: superlevel sets read at the lower bin edges (ecc_hard_ex)."""
+def _hard_args(grid, ndim, bins, range, curve, workspace):
+    """Marshalling shared by the hard entry points: (head, tail, curve) of the C call's arguments."""
     _need_device(grid, curve, workspace)
     if grid.dim() != ndim + 1:
         raise ValueError("grid must be [batch, *item_shape]")
@@ -111,6 +108,15 @@ def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, w
         rng = (ctypes.c_double * 2)(float(range[0]), float(range[1]))
     head = (_ptr(grid), ndim, _dims(item), batch, _DTYPES[grid.dtype])
     tail = (bins, rng, _ptr(curve), _ptr(workspace), workspace.numel(), _stream())
+    return head, tail, curve
+
+
+def ecc_hard(grid: torch.Tensor, ndim: int, bins: int, range=None, curve=None, workspace=None, top=False,
+             superlevel=False):
+    """grid: [batch, (D,) H, W] device tensor (uint8 / uint16 / float32; float16 / bfloat16 / int16 / int32 /
+    float64 for the hard curves).  Returns the int64 curve [batch, bins].  top=True: top-cell construction
+    (ecc_hard_top); superlevel=True: superlevel sets read at the lower bin edges (ecc_hard_ex)."""
+    head, tail, curve = _hard_args(grid, ndim, bins, range, curve, workspace)
     if superlevel:
         _check(_lib.load().ecc_hard_ex(*head, ECC_TOPCELL if top else ECC_VERTEX, ECC_SUPERLEVEL, *tail))
     else:
@@ -140,19 +146,8 @@ def ecc_hard_ex(grid: torch.Tensor, ndim: int, construction: int, filtration: in
                 curve=None, workspace=None):
     """The entry point with construction (ECC_VERTEX / ECC_TOPCELL) and filtration
     (ECC_SUBLEVEL / ECC_SUPERLEVEL) as arguments; every combination goes through ecc_hard_ex."""
-    _need_device(grid, curve, workspace)
-    if grid.dim() != ndim + 1:
-        raise ValueError("grid must be [batch, *item_shape]")
-    batch, item = grid.shape[0], tuple(grid.shape[1:])
-    if curve is None:
-        curve = torch.empty((batch, bins), dtype=torch.int64, device=grid.device)
-    workspace = _workspace(item, batch, max(bins, 1), grid.device, workspace, _DTYPES[grid.dtype])
-    rng = None
-    if range is not None:
-        rng = (ctypes.c_double * 2)(float(range[0]), float(range[1]))
-    _check(_lib.load().ecc_hard_ex(_ptr(grid), ndim, _dims(item), batch, _DTYPES[grid.dtype], int(construction),
-                                   int(filtration), bins, rng, _ptr(curve), _ptr(workspace), workspace.numel(),
-                                   _stream()))
+    head, tail, curve = _hard_args(grid, ndim, bins, range, curve, workspace)
+    _check(_lib.load().ecc_hard_ex(*head, int(construction), int(filtration), *tail))
     return curve
 
 
