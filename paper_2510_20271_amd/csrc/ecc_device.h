@@ -298,6 +298,23 @@ __device__ __forceinline__ float wave_sum_lane63(float v) {
   return v;
 }
 
+// ---- sigmoid pieces shared by the fused soft kernels (Eq. 6, Eq. 8-10) ------
+__device__ __forceinline__ float soft_exp_neg(float z, float kneg) {
+  // exp(-lambda z) = 2^(kneg z); clamped so the result stays finite
+  return __builtin_amdgcn_exp2f(fminf(kneg * z, 126.0f));
+}
+
+constexpr float kSatLog2 = 64.0f;  // |lambda z| log2(e) beyond which sigma is 0 or 1 and sigma' is 0
+
+// Saturation bounds for thresholds in [lo, hi]: with k = lambda log2(e) = -kneg, sigma(tau - y) differs from
+// 1 by less than 2^-64 for y <= lo - 64/k and from 0 for y >= hi + 64/k (a little margin covers
+// the rounding of yh); sigma' is below 2^-64 lambda in both cases.
+__device__ __forceinline__ void soft_sat_bounds(float lo, float hi, float kneg, float& sat_lo, float& sat_hi) {
+  const float w = (kSatLog2 + 2.0f) / -kneg;
+  sat_lo = lo - w - 1e-6f * fabsf(lo);
+  sat_hi = hi + w + 1e-6f * fabsf(hi);
+}
+
 // ---- critical-vertex queue of a wave ----------------------------------------
 // Critical vertices (c != 0) turn up a few lanes at a time.  Instead of running
 // the binning code with most lanes idle, a wave appends (value, c) to a small

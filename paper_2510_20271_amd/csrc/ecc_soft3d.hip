@@ -3,8 +3,11 @@
 //
 // As in 2D, only the critical vertices (c != 0) carry a term.  The tube sweep
 // finds them and queues (position, c); when 64 are drained together each lane
-// fetches one value, forms y = X(p) + alpha <u,p> in float64 and parks the entry
-// in a small LDS stage, and then every lane runs over the staged entries for the
+// fetches one value, forms y = X(p) + alpha <u,p> in float64, carries it on as two
+// floats (yh + yl, so that (tau_j - yh) - yl is the float64 difference to an ulp) and
+// parks the entry in a small LDS stage -- unless y lies so far outside [min tau, max tau]
+// that every sigmoid is 0 or 1 to 2^-64: such an entry adds c or nothing to every
+// threshold and is not evaluated.  Then every lane runs over the staged entries for the
 // thresholds it owns (tau_l, tau_{l+64}, ...; T <= 256): the sums over p of
 // Eq. 6 / Eq. 9 / Eq. 10 need no cross-lane reduction, the contraction of Eq. 8
 // with the upstream gradient is a fixed-order sum over the lanes.  grad_X is
@@ -19,13 +22,8 @@ namespace ecc {
 
 constexpr int kSoft3TL = 4;  // thresholds per lane
 
-__device__ __forceinline__ float soft3_exp_neg(float z, float kneg) {
-  // exp(-lambda z) = 2^(kneg z); clamped so the result stays finite
-  return __builtin_amdgcn_exp2f(fminf(kneg * z, 126.0f));
-}
-
 struct Soft3Entry {
-  double y;  // X(p) + alpha <u,p>
+  float yh, yl;  // X(p) + alpha <u,p> = yh + yl
   float c;
   int x, yy, z;
   unsigned inpl;  // yy * W + x
@@ -35,9 +33,10 @@ struct Soft3Entry {
 struct Soft3Common {
   static constexpr bool kTrackRange = false;
   double ux, uy, uz, alpha;
-  double tj[kSoft3TL];  // this lane's thresholds
-  int nt;               // threshold slots in use: ceil(T / 64)
+  float tj[kSoft3TL];  // this lane's thresholds
+  int nt;              // threshold slots in use: ceil(T / 64)
   float kneg;
+  float sat_lo, sat_hi;  // y <= sat_lo: every sigma is 1;  y >= sat_hi: every sigma is 0 (to 2^-64)
   int W;
   int oz;             // first plane of the wave's segment
   Soft3Entry* stage;  // wave-private LDS, 64 entries
@@ -52,46 +51,71 @@ struct Soft3Common {
     W = W_;
     stage = stage_;
     const int lane = threadIdx.x & (kWave - 1);
+    float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
     for (int t = 0; t < kSoft3TL; ++t) {
       const int j = lane + kWave * t;
-      tj[t] = j < T ? (double)tau[j] : 0.0;
+      tj[t] = j < T ? tau[j] : 0.0f;
+      if (j < T) {
+        lo = fminf(lo, tj[t]);
+        hi = fmaxf(hi, tj[t]);
+      }
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      lo = fminf(lo, __shfl_xor(lo, o));
+      hi = fmaxf(hi, __shfl_xor(hi, o));
+    }
+    soft_sat_bounds(lo, hi, kneg_, sat_lo, sat_hi);
   }
-  // lane i < n parks its entry
-  __device__ __forceinline__ void park(int n, float v, int c, unsigned inpl, unsigned zrel) const {
+  // Lane i < n forms its entry; the entries that have to be evaluated are packed into the stage
+  // and counted (the return value).  A dropped entry whose sigmoids are all 1 adds its c to
+  // *csat, one whose sigmoids are all 0 adds nothing; neither has a derivative above 2^-64 lambda.
+  __device__ __forceinline__ int park(int n, float v, int c, unsigned inpl, unsigned zrel, float* csat) const {
     const int lane = threadIdx.x & (kWave - 1);
-    if (lane < n) {
-      Soft3Entry e;
-      e.yy = (int)(inpl / (unsigned)W);
-      e.x = (int)(inpl - (unsigned)e.yy * (unsigned)W);
-      e.z = oz + (int)zrel;
-      e.y = (double)v + alpha * ((ux * (double)e.x + uy * (double)e.yy) + uz * (double)e.z);
-      e.c = (float)c;
-      e.inpl = inpl;
-      e.pad = 0;
-      stage[lane] = e;
+    const bool in = lane < n;
+    Soft3Entry e;
+    e.yy = (int)(inpl / (unsigned)W);
+    e.x = (int)(inpl - (unsigned)e.yy * (unsigned)W);
+    e.z = oz + (int)zrel;
+    const double y = (double)v + alpha * ((ux * (double)e.x + uy * (double)e.yy) + uz * (double)e.z);
+    e.yh = (float)y;
+    e.yl = (float)(y - (double)e.yh);
+    e.c = (float)c;
+    e.inpl = inpl;
+    e.pad = 0;
+    const bool keep = in && e.yh > sat_lo && e.yh < sat_hi;
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(keep);
+    const int kept = __builtin_popcountll(m);
+    if (kept != n && csat) {  // wave-uniform
+      const float ones = wave_sum_lane63((in && e.yh <= sat_lo) ? e.c : 0.0f);
+      *csat += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, ones), kWave - 1));
     }
+    const int pos = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+    if (keep) stage[pos] = e;
+    return kept;
   }
+  __device__ __forceinline__ float zarg(int t, float yh, float yl) const { return (tj[t] - yh) - yl; }
 };
 
 struct Soft3FwdSink : Soft3Common {
   float acc[kSoft3TL];
+  float csat;  // sum of c over the entries whose sigmoids are all 1 (wave-uniform)
   __device__ __forceinline__ void take(int n, float v, int c, unsigned inpl, unsigned zrel) {
-    park(n, v, c, inpl, zrel);
+    n = park(n, v, c, inpl, zrel, &csat);
     for (int e = 0; e < n; ++e) {
-      const double y = stage[e].y;
+      const float yh = stage[e].yh, yl = stage[e].yl;
       const float cf = stage[e].c;
 #pragma unroll
       for (int t = 0; t < kSoft3TL; ++t) {
         if (t < nt) {  // wave-uniform
-          const float z = (float)(tj[t] - y);
-          const float ex = soft3_exp_neg(z, kneg);
+          const float ex = soft_exp_neg(zarg(t, yh, yl), kneg);
           acc[t] += cf * __builtin_amdgcn_rcpf(1.0f + ex);
         }
       }
     }
   }
+  __device__ __forceinline__ float total(int t) const { return acc[t] + csat; }
 };
 
 struct Soft3BwdSink : Soft3Common {
@@ -102,7 +126,7 @@ struct Soft3BwdSink : Soft3Common {
   int ox, oy;          // origin of the wave's unit (with oz): coordinates are summed relative to it
   float lambda;
   __device__ __forceinline__ void take(int n, float v, int c, unsigned inpl, unsigned zrel) {
-    park(n, v, c, inpl, zrel);
+    n = park(n, v, c, inpl, zrel, nullptr);  // grad_X stays 0 at a saturated vertex
     const int lane = threadIdx.x & (kWave - 1);
     for (int e = 0; e < n; ++e) {
       const Soft3Entry en = stage[e];
@@ -111,8 +135,7 @@ struct Soft3BwdSink : Soft3Common {
 #pragma unroll
       for (int t = 0; t < kSoft3TL; ++t) {
         if (t < nt) {  // wave-uniform
-          const float z = (float)(tj[t] - en.y);
-          const float ex = soft3_exp_neg(z, kneg);
+          const float ex = soft_exp_neg(zarg(t, en.yh, en.yl), kneg);
           const float s = __builtin_amdgcn_rcpf(1.0f + ex);
           const float d = ex * s * s;  // sigma (1 - sigma)
           const float cd = en.c * d;
@@ -160,6 +183,7 @@ __global__ __launch_bounds__(256) void soft3d_fwd_kernel(const float* __restrict
   queue.sink.init(u, alpha, tau, T, kneg, W, stage);
 #pragma unroll
   for (int t = 0; t < kSoft3TL; ++t) queue.sink.acc[t] = 0.f;
+  queue.sink.csat = 0.f;
   const int unit = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int ox, oy;
   unit_origin3(unit, D, H, W, gridDim.y, planes_per_seg, kRows3d, ox, oy, queue.sink.oz);
@@ -180,7 +204,7 @@ __global__ __launch_bounds__(256) void soft3d_fwd_kernel(const float* __restrict
 #pragma unroll
   for (int t = 0; t < kSoft3TL; ++t) {
     const int j = lane + kWave * t;
-    if (j < T) out[j] = queue.sink.acc[t];
+    if (j < T) out[j] = queue.sink.total(t);
   }
 }
 
@@ -233,84 +257,128 @@ __global__ __launch_bounds__(256) void soft3d_bwd_kernel(const float* __restrict
   }
 }
 
-// Reduction over units: block (x = group of 64 thresholds, y = item) of 16 waves; wave w
-// adds units w, w+16, ... in order (eight loads in flight at a time: a lone volume has
-// thousands of units and one block per 64 thresholds), then wave 0 adds the 16 sums in order.
-constexpr int kRedWaves = 16, kRedUnroll = 8;
+// Reduction over units, in float64 and in a fixed order (run-to-run identical).  A lone volume has
+// thousands of units, so the sum is split: block (x = group of 64 thresholds, y = item, z = slice)
+// of 16 waves adds the units of its slice -- wave w takes units begin + w, begin + w + 16, ... in
+// order, then wave 0 adds the 16 sums in order -- and, when there is more than one slice, leaves
+// the slice's sums in `mid`, which the final kernel adds in slice order.
+constexpr int kRedWaves = 16, kRedSlices = 64;
 
-__global__ __launch_bounds__(kRedWaves * kWave) void soft3d_fwd_reduce_kernel(const float* __restrict__ partial,
-                                                                              int units, int T,
-                                                                              float* __restrict__ chi) {
-  __shared__ double red[kRedWaves][kWave];
-  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
-  const int j = blockIdx.x * kWave + lane;
-  const float* p = partial + (int64_t)blockIdx.y * units * T + j;
-  double s = 0.0;
-  if (j < T) {
-    int q = wv;
-    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
-      float v[kRedUnroll];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) s += (double)v[k];
-    }
-    for (; q < units; q += kRedWaves) s += (double)p[(int64_t)q * T];
-  }
-  red[wv][lane] = s;
-  __syncthreads();
-  if (wv == 0 && j < T) {
-    double r = red[0][lane];
-    for (int w = 1; w < kRedWaves; ++w) r += red[w][lane];
-    chi[(int64_t)blockIdx.y * T + j] = (float)r;
+// NV = 1: forward (chi);  NV = 4: backward (A0 and the coordinate-weighted sums, relative to each
+// unit's origin on the way in, absolute on the way out)
+template <int NV>
+struct RedSums {
+  double v[NV];
+};
+
+template <int NV>
+__device__ __forceinline__ void soft3d_finish(const RedSums<NV>& r, int64_t k, float alpha, float lambda, float* o0,
+                                              float* o1) {
+  if constexpr (NV == 1) {
+    o0[k] = (float)r.v[0];  // chi
+  } else {
+    // dchi_dtau = lambda sum A0;  dchi_du = -alpha lambda sum (origin * A0 + A_xyz)
+    if (o0) o0[k] = (float)((double)lambda * r.v[0]);
+    if (o1)
+      for (int c = 0; c < 3; ++c) o1[k * 3 + c] = (float)(-(double)alpha * (double)lambda * r.v[1 + c]);
   }
 }
 
-// dchi_dtau = lambda sum A0;  dchi_du = -alpha lambda sum (origin * A0 + A_xyz)
-__global__ __launch_bounds__(kRedWaves * kWave) void soft3d_bwd_reduce_kernel(
-    const float* __restrict__ partial, int units, int D, int H, int W, int planes_per_seg, int T, float alpha,
-    float lambda, float* __restrict__ dtau, float* __restrict__ du) {
-  __shared__ double red[4][kRedWaves][kWave];
+template <int NV>
+__global__ __launch_bounds__(kRedWaves * kWave) void soft3d_reduce_kernel(const float* __restrict__ partial, int units,
+                                                                          int per_slice, int D, int H, int W,
+                                                                          int planes_per_seg, int nitems, int T,
+                                                                          float alpha, float lambda,
+                                                                          double* __restrict__ mid,
+                                                                          float* __restrict__ o0,
+                                                                          float* __restrict__ o1) {
+  __shared__ double red[NV][kRedWaves][kWave];
   const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
   const int j = blockIdx.x * kWave + lane;
-  const float4* p = reinterpret_cast<const float4*>(partial) + (int64_t)blockIdx.y * units * T + j;
-  double s0 = 0.0, sx = 0.0, sy = 0.0, sz = 0.0;
-  auto add = [&](int q, const float4& e) {
-    int ox, oy, oz;
-    unit_origin3(q, D, H, W, gridDim.y, planes_per_seg, kRows3d, ox, oy, oz);
-    const double a0 = (double)e.x;
-    s0 += a0;
-    sx += (double)ox * a0 + (double)e.y;
-    sy += (double)oy * a0 + (double)e.z;
-    sz += (double)oz * a0 + (double)e.w;
-  };
+  const int item = blockIdx.y, slice = blockIdx.z;
+  const int begin = slice * per_slice, end = min(units, begin + per_slice);
+  RedSums<NV> s;
+  for (int c = 0; c < NV; ++c) s.v[c] = 0.0;
   if (j < T) {
-    int q = wv;
-    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
-      float4 v[kRedUnroll];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) add(q + k * kRedWaves, v[k]);
+    for (int q = begin + wv; q < end; q += kRedWaves) {
+      if constexpr (NV == 1) {
+        s.v[0] += (double)partial[((int64_t)item * units + q) * T + j];
+      } else {
+        const float4 e = reinterpret_cast<const float4*>(partial)[((int64_t)item * units + q) * T + j];
+        int ox, oy, oz;
+        unit_origin3(q, D, H, W, nitems, planes_per_seg, kRows3d, ox, oy, oz);
+        const double a0 = (double)e.x;
+        s.v[0] += a0;
+        s.v[1] += (double)ox * a0 + (double)e.y;
+        s.v[2] += (double)oy * a0 + (double)e.z;
+        s.v[3] += (double)oz * a0 + (double)e.w;
+      }
     }
-    for (; q < units; q += kRedWaves) add(q, p[(int64_t)q * T]);
   }
-  red[0][wv][lane] = s0;
-  red[1][wv][lane] = sx;
-  red[2][wv][lane] = sy;
-  red[3][wv][lane] = sz;
+  for (int c = 0; c < NV; ++c) red[c][wv][lane] = s.v[c];
   __syncthreads();
   if (wv == 0 && j < T) {
-    const int64_t k = (int64_t)blockIdx.y * T + j;
-    double r[4];
-    for (int c = 0; c < 4; ++c) {
-      r[c] = red[c][0][lane];
-      for (int w = 1; w < kRedWaves; ++w) r[c] += red[c][w][lane];
+    RedSums<NV> r;
+    for (int c = 0; c < NV; ++c) {
+      r.v[c] = red[c][0][lane];
+      for (int w = 1; w < kRedWaves; ++w) r.v[c] += red[c][w][lane];
     }
-    if (dtau) dtau[k] = (float)((double)lambda * r[0]);
-    if (du)
-      for (int c = 0; c < 3; ++c) du[k * 3 + c] = (float)(-(double)alpha * (double)lambda * r[1 + c]);
+    if (gridDim.z == 1) {
+      soft3d_finish<NV>(r, (int64_t)item * T + j, alpha, lambda, o0, o1);
+    } else {
+      for (int c = 0; c < NV; ++c) mid[(((int64_t)item * gridDim.z + slice) * T + j) * NV + c] = r.v[c];
+    }
   }
+}
+
+// wave w adds slices w, w + 16, ... in order, wave 0 adds the 16 sums in order
+template <int NV>
+__global__ __launch_bounds__(kRedWaves * kWave) void soft3d_reduce_final_kernel(const double* __restrict__ mid,
+                                                                                int slices, int T, float alpha,
+                                                                                float lambda, float* __restrict__ o0,
+                                                                                float* __restrict__ o1) {
+  __shared__ double red[NV][kRedWaves][kWave];
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+  const int j = blockIdx.x * kWave + lane, item = blockIdx.y;
+  RedSums<NV> s;
+  for (int c = 0; c < NV; ++c) s.v[c] = 0.0;
+  if (j < T)
+    for (int sl = wv; sl < slices; sl += kRedWaves)
+      for (int c = 0; c < NV; ++c) s.v[c] += mid[(((int64_t)item * slices + sl) * T + j) * NV + c];
+  for (int c = 0; c < NV; ++c) red[c][wv][lane] = s.v[c];
+  __syncthreads();
+  if (wv == 0 && j < T) {
+    RedSums<NV> r;
+    for (int c = 0; c < NV; ++c) {
+      r.v[c] = red[c][0][lane];
+      for (int w = 1; w < kRedWaves; ++w) r.v[c] += red[c][w][lane];
+    }
+    soft3d_finish<NV>(r, (int64_t)item * T + j, alpha, lambda, o0, o1);
+  }
+}
+
+// slices a reduction over `units` is split into, and units per slice
+static void red_split(int units, int& slices, int& per_slice) {
+  slices = units / (4 * kRedWaves);
+  slices = slices < 1 ? 1 : (slices > kRedSlices ? kRedSlices : slices);
+  per_slice = (units + slices - 1) / slices;
+  slices = (units + per_slice - 1) / per_slice;
+}
+
+template <int NV>
+static void launch_soft3d_reduce(const float* partial, double* mid, const Shape& s, const Plan3d& pl, int T, float alpha,
+                                 float lambda, float* o0, float* o1, hipStream_t st) {
+  const int units = (int)pl.grid.x * 4;
+  int slices, per;
+  red_split(units, slices, per);
+  const unsigned tg = (unsigned)((T + kWave - 1) / kWave);
+  hipLaunchKernelGGL(soft3d_reduce_kernel<NV>, dim3(tg, (unsigned)s.batch, (unsigned)slices), dim3(kRedWaves * kWave), 0,
+                     st, partial, units, per, (int)s.D, (int)s.H, (int)s.W, pl.planes_per_seg, (int)s.batch, T, alpha,
+                     lambda, mid, o0, o1);
+  if (slices > 1)
+    hipLaunchKernelGGL(soft3d_reduce_final_kernel<NV>, dim3(tg, (unsigned)s.batch), dim3(kRedWaves * kWave), 0, st, mid,
+                       slices, T,
+                       alpha, lambda, o0, o1);
 }
 
 static float kneg3d(float lambda) { return (float)(-(double)lambda * 1.4426950408889634); }
@@ -319,10 +387,16 @@ bool soft3d_supported(const Shape& s, int T) {
   return s.ndim == 3 && T <= kSoft3TL * kWave && sweep3d_supported(s, 1);
 }
 
+// per-unit partial sums (float4 per unit and threshold in the backward pass), a multiple of 256 bytes
+static size_t soft3d_partial_bytes(const Shape& s, const Plan3d& pl, int T) {
+  const size_t n = (size_t)s.batch * pl.grid.x * 4 * (size_t)T * 4 * sizeof(float);
+  return (n + 255) / 256 * 256;
+}
+
 size_t soft3d_workspace_bytes(const Shape& s, int T) {
   if (!soft3d_supported(s, T)) return 0;
   const Plan3d pl = plan3d<float>(s);
-  return (size_t)256 + (size_t)s.batch * pl.grid.x * 4 * (size_t)T * 4 * sizeof(float);
+  return (size_t)256 + soft3d_partial_bytes(s, pl, T) + (size_t)s.batch * kRedSlices * (size_t)T * 4 * sizeof(double);
 }
 
 void launch_soft3d_fwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
@@ -336,8 +410,8 @@ void launch_soft3d_fwd(const float* grid, const Shape& s, const float* u, float 
   if (tiltc) ECC_GO(true);
   else ECC_GO(false);
 #undef ECC_GO
-  hipLaunchKernelGGL(soft3d_fwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                     dim3(kRedWaves * kWave), 0, st, partial, (int)pl.grid.x * 4, T, chi);
+  double* mid = reinterpret_cast<double*>(static_cast<char*>(ws) + soft3d_partial_bytes(s, pl, T));
+  launch_soft3d_reduce<1>(partial, mid, s, pl, T, alpha, lambda, chi, nullptr, st);
 }
 
 void launch_soft3d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
@@ -354,9 +428,8 @@ void launch_soft3d_bwd(const float* grid, const Shape& s, const float* u, float 
   else ECC_GO(false);
 #undef ECC_GO
   if (partial) {
-    hipLaunchKernelGGL(soft3d_bwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                       dim3(kRedWaves * kWave), 0, st, partial, (int)pl.grid.x * 4, (int)s.D, (int)s.H, (int)s.W, pl.planes_per_seg, T,
-                       alpha, lambda, dtau, du);
+    double* mid = reinterpret_cast<double*>(static_cast<char*>(ws) + soft3d_partial_bytes(s, pl, T));
+    launch_soft3d_reduce<4>(partial, mid, s, pl, T, alpha, lambda, dtau, du, st);
   }
 }
 

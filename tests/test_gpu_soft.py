@@ -104,6 +104,32 @@ def test_soft_extreme_arguments_stay_finite():
     np.testing.assert_allclose(chi[0, [0, -1]], [0.0, 1.0], atol=1e-6)
 
 
+@pytest.mark.parametrize("shape", [(120, 700), (40, 70, 130)])
+@pytest.mark.parametrize("alpha", [0.0, 0.02])
+def test_soft_thresholds_in_a_narrow_band(shape, alpha):
+    # lambda = 200 and thresholds within +-0.2: most vertices lie more than 64 / (lambda log2 e) = 0.22
+    # below or above every threshold (sigma is 1 or 0 there to 2^-64); the kernels do not evaluate
+    # them, the float64 oracle does
+    nd, B, T = len(shape), 2, 70
+    Xb = np.stack([synth.grf(shape, 1.5, 140 + i) for i in range(B)])
+    Xb = (Xb / Xb.std()).astype(np.float32)
+    tau = np.linspace(-0.2, 0.2, T).astype(np.float32)
+    u = np.array([np.cos(0.3), np.sin(0.3)] if nd == 2 else [0.48, -0.6, 0.64], np.float32)
+    G = np.random.default_rng(5).standard_normal((B, T)).astype(np.float32)
+    assert np.mean(Xb < -0.5) > 0.2 and np.mean(Xb > 0.5) > 0.2
+    _run_case(Xb, u, np.float32(alpha), tau, np.float32(200.0), G)
+    if nd == 2:
+        g, ud, td = dev(Xb), dev(u), dev(tau)
+        chi, dt, du, state = api.ecc_soft_fwd_save(g, 2, ud, np.float32(alpha), td, np.float32(200.0))
+        gx = api.ecc_soft_bwd_saved(g, 2, ud, np.float32(alpha), td, np.float32(200.0), state, grad_chi=dev(G))
+        ref = api.ecc_soft_bwd(g, 2, ud, np.float32(alpha), td, np.float32(200.0), grad_chi=dev(G))
+        assert torch.equal(chi, api.ecc_soft_fwd(g, 2, ud, np.float32(alpha), td, np.float32(200.0)))
+        for i in range(B):
+            _close(host(gx)[i], host(ref[0])[i], 1e-3, "grad_X from the saved state")
+            _close_sum(host(dt)[i], host(ref[1])[i], 1e-3, "dchi_dtau")
+            _close_sum(host(du)[i], host(ref[2])[i], 1e-3, "dchi_du")
+
+
 def test_soft_large_lambda_matches_hard_curve():
     X = synth.grf((60, 70), 2.0, 21)
     vals = np.unique(X)
