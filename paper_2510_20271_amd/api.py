@@ -291,7 +291,7 @@ def ecc_count_nonfinite(grid: torch.Tensor, count=None):
     return count
 
 
-ECC_FORCE_GENERIC, ECC_FORCE_TWO_PASS, ECC_FORCE_SOFT_TILES = 1, 2, 4
+ECC_FORCE_GENERIC, ECC_FORCE_TWO_PASS, ECC_FORCE_SOFT_TILES, ECC_FORCE_NO_SMALL = 1, 2, 4, 8
 
 
 def ecc_debug_force(mask: int) -> int:

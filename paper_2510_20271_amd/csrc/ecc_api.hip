@@ -124,7 +124,7 @@ unsigned forced_paths() { return g_forced.load(std::memory_order_relaxed); }
 extern "C" {
 
 unsigned ecc_debug_force(unsigned mask) {
-  return g_forced.exchange(mask & (ECC_FORCE_GENERIC | ECC_FORCE_TWO_PASS | ECC_FORCE_SOFT_TILES),
+  return g_forced.exchange(mask & (ECC_FORCE_GENERIC | ECC_FORCE_TWO_PASS | ECC_FORCE_SOFT_TILES | ECC_FORCE_NO_SMALL),
                            std::memory_order_relaxed);
 }
 

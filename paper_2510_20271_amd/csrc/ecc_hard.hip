@@ -380,7 +380,9 @@ static unsigned list_cap(const Shape& s) {  // entries per sub-list
 }
 static size_t counter_bytes(const Shape& s) { return (((size_t)s.batch * list_nsub(s) * 4 + 255) / 256) * 256; }
 size_t hard_workspace_bytes(const Shape& s, int bins) {
-  return kTableOffset + table_bytes(bins) + counter_bytes(s) + (size_t)s.batch * list_nsub(s) * list_cap(s) * sizeof(float2);
+  const size_t lists = counter_bytes(s) + (size_t)s.batch * list_nsub(s) * list_cap(s) * sizeof(float2);
+  const size_t small = small_supported(s, bins) ? small_workspace_bytes(s) : 0;
+  return kTableOffset + table_bytes(bins) + std::max(lists, small);
 }
 
 static int blocks_for(int64_t N) {
@@ -434,6 +436,16 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
   // (a directional call comes here only for shapes the strip / tube sweeps take)
   const bool fast2d = (dir || (!force_generic && !tiny)) && sweep2d_supported(s, bins);
   const bool fast3d = (dir || (!force_generic && !tiny)) && !fast2d && sweep3d_supported(s, bins);
+  // Small float grids without a range: the whole call in two launches.
+  if (device_range && !dir && forced_paths() == 0u && small_supported(s, bins)) {
+    if (dtype >= 3) {
+      hipError_t e = launch_convert(grid, dtype, total, f32_scratch, st);
+      if (e != hipSuccess) return e;
+      grid = f32_scratch;
+    }
+    return launch_hard_small(static_cast<const float*>(grid), s, bins, curve, hdr, table,
+                             wsb + kTableOffset + table_bytes(bins), st, conv);
+  }
   // Element types beyond uint8 / uint16 / float32.  The strip / tube sweeps load float16, bfloat16
   // and int16 as they are (all three widen to float32 exactly); the other kernels, and int32 /
   // float64 everywhere, get a float32 copy rounded to nearest even.

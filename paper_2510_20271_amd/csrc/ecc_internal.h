@@ -40,11 +40,17 @@ void launch_coeff2d(const void* grid, const Shape& s, int dtype, int8_t* c_out, 
 void launch_coeff3d(const void* grid, const Shape& s, int dtype, int8_t* c_out, hipStream_t st);
 
 // Paths forced by ecc_debug_force (bits ECC_FORCE_* of include/ecc.h); 0 in normal operation.
-constexpr unsigned kForceGeneric = 1u, kForceTwoPass = 2u, kForceSoftTiles = 4u;
+constexpr unsigned kForceGeneric = 1u, kForceTwoPass = 2u, kForceSoftTiles = 4u, kForceNoSmall = 8u;
 unsigned forced_paths();
 
 // fast sweeps (one wave per column strip / tube, bit-sliced stencil)
 struct HardHeader;
+// small float32 inputs without a range: the whole call in two launches (ecc_small.hip);
+// `small`: small_workspace_bytes(s) bytes behind the threshold table
+bool small_supported(const Shape& s, int bins);
+size_t small_workspace_bytes(const Shape& s);
+hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_t* curve, HardHeader* hdr, float* table,
+                             void* small, hipStream_t st, int conv);
 // single-pass mode: per-item lists of critical vertices (value, c) in the workspace
 struct ListArgs {
   float2* lists;       // [batch][nsub][cap]

@@ -40,7 +40,7 @@ def _grid(kind, shape, rng):
 
 @pytest.mark.parametrize("kind", ["f16", "bf16", "i16", "i32", "f64"])
 @pytest.mark.parametrize("shape", SHAPES)
-def test_converted_dtypes(kind, shape):
+def test_converted_dtypes(kind, shape, flow):
     rng = np.random.default_rng(len(shape) * 100 + shape[-1])
     g, Y = _grid(kind, shape, rng)
     assert Y.dtype == np.float32
@@ -65,7 +65,7 @@ def test_converted_dtypes(kind, shape):
                                   O.ecc_super_batch(Y, O.thresholds_lower(t, lo)))
 
 
-def test_int32_levels_equal_the_uint16_path():
+def test_int32_levels_equal_the_uint16_path(flow):
     rng = np.random.default_rng(3)
     a = rng.integers(0, 300, size=(2, 70, 131))
     want = host(api.ecc_hard(torch.from_numpy(a.astype(np.int16)).cuda().view(torch.uint16), 2, 256))

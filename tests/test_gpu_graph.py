@@ -24,8 +24,8 @@ def _capture(fn):
     return g
 
 
-@pytest.mark.parametrize("shape", [(300, 700), (40, 70, 131)])
-def test_hard_curve_in_a_graph(shape):
+@pytest.mark.parametrize("shape", [(64, 100), (300, 700), (40, 70, 131)])
+def test_hard_curve_in_a_graph(shape, flow):
     nd = len(shape)
     fields = [np.stack([synth.grf(shape, 2.0, 10 * k + i) for i in range(2)]) for k in range(3)]
     x = dev(fields[0]).clone()

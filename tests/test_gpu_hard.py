@@ -12,8 +12,9 @@ from tests.gpu_util import dev, host
 
 pytestmark = pytest.mark.gpu
 
-# (with the thresholds known up front, inputs of up to 2^16 vertices take the one-thread-per-
-# vertex sweep, larger ones the strip / tube sweeps: both sides of that line are covered)
+# (small inputs take a two-launch flow of their own, see the `flow` fixture; with that flow off and
+# the thresholds known up front, inputs of up to 2^16 vertices take the one-thread-per-vertex sweep,
+# larger ones the strip / tube sweeps: both sides of either line are covered)
 SHAPES_2D = [(1, 1), (1, 7), (7, 1), (2, 2), (3, 3), (5, 64), (64, 5), (17, 65), (63, 129), (130, 257),
              (256, 256), (257, 259), (9, 7300), (300, 1000)]
 SHAPES_3D = [(1, 1, 1), (2, 2, 2), (1, 5, 9), (5, 1, 9), (5, 9, 1), (3, 4, 5), (9, 17, 33), (8, 64, 64),
@@ -42,7 +43,7 @@ def test_coeff_map_matches_oracle(shape, dtype):
 
 @pytest.mark.parametrize("shape", SHAPES_2D + SHAPES_3D)
 @pytest.mark.parametrize("dtype", [np.uint8, np.uint16])
-def test_hard_levels(shape, dtype):
+def test_hard_levels(shape, dtype, flow):
     B, bins = 3, 11  # levels 0..12 -> the top two are above the last threshold and dropped
     X = np.stack([_rand(shape, dtype, 7 + i, levels=13) for i in range(B)])
     got = host(api.ecc_hard(dev(X), len(shape), bins))
@@ -50,7 +51,7 @@ def test_hard_levels(shape, dtype):
 
 
 @pytest.mark.parametrize("shape", SHAPES_2D + SHAPES_3D)
-def test_hard_float_auto_range(shape):
+def test_hard_float_auto_range(shape, flow):
     B, bins = 2, 37
     rng = np.random.default_rng(5)
     X = rng.standard_normal((B,) + shape).astype(np.float32)
@@ -62,7 +63,7 @@ def test_hard_float_auto_range(shape):
 
 @pytest.mark.parametrize("dtype", [np.uint8, np.uint16, np.float32])
 @pytest.mark.parametrize("shape", [(40, 50), (6, 20, 30)])
-def test_hard_supplied_range(shape, dtype):
+def test_hard_supplied_range(shape, dtype, flow):
     X = np.stack([_rand(shape, dtype, 3 + i, levels=40) for i in range(2)])
     for lo, hi, bins in [(-1.5, 7.25, 16), (2.0, 2.0, 4), (0.0, 39.0, 40), (-100.0, 100.0, 1000)]:
         got = host(api.ecc_hard(dev(X), len(shape), bins, range=(lo, hi)))
@@ -70,7 +71,7 @@ def test_hard_supplied_range(shape, dtype):
         np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, t), err_msg=f"{lo} {hi} {bins}")
 
 
-def test_hard_many_bins_and_ties_on_edges():
+def test_hard_many_bins_and_ties_on_edges(flow):
     # values exactly on thresholds; bins up to the maximum
     X = (np.arange(64 * 64, dtype=np.float32).reshape(64, 64) % 97) / 8
     X = X[None]
@@ -79,7 +80,7 @@ def test_hard_many_bins_and_ties_on_edges():
         np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(0.0, 12.0, bins)))
 
 
-def test_constant_and_ramp():
+def test_constant_and_ramp(flow):
     X = np.full((1, 9, 10, 11), 3, np.uint8)
     got = host(api.ecc_hard(dev(X), 3, 5))
     np.testing.assert_array_equal(got[0], [0, 0, 0, 1, 1])
@@ -91,7 +92,7 @@ def test_constant_and_ramp():
     np.testing.assert_array_equal(got[0], 1)
 
 
-def test_depth_one_equals_2d_and_batch_equals_singles():
+def test_depth_one_equals_2d_and_batch_equals_singles(flow):
     rng = np.random.default_rng(12)
     X = rng.integers(0, 32, size=(4, 37, 41), dtype=np.uint8)
     a = host(api.ecc_hard(dev(X), 2, 32))
@@ -101,7 +102,7 @@ def test_depth_one_equals_2d_and_batch_equals_singles():
         np.testing.assert_array_equal(host(api.ecc_hard(dev(X[i:i + 1]), 2, 32))[0], a[i])
 
 
-def test_repeated_calls_are_identical_and_workspace_reusable():
+def test_repeated_calls_are_identical_and_workspace_reusable(flow):
     X = synth.grf((3, 48, 52), 1.5, 77)[None]
     g = dev(X)
     ws = torch.empty(api.ecc_workspace_bytes((3, 48, 52), 1, 128), dtype=torch.uint8, device="cuda")
@@ -123,15 +124,19 @@ def test_single_pass_overflow_fallback(shape):
     rough = rng.standard_normal((2,) + shape).astype(np.float32)   # ~58 % of the vertices critical
     smooth = np.stack([synth.grf(shape, 3.0, 500 + i) for i in range(2)])  # ~1 %
     ws = torch.empty(api.ecc_workspace_bytes(shape, 2, bins), dtype=torch.uint8, device="cuda")
-    for X, want_flag in ((rough, 1), (smooth, 0), (rough, 1)):
-        got = host(api.ecc_hard(dev(X), len(shape), bins, workspace=ws))
-        assert _overflow_flag(ws) == want_flag
-        t = O.thresholds_equal_width(X.min(), X.max(), bins)
-        np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, t))
+    prev = api.ecc_debug_force(api.ECC_FORCE_NO_SMALL)  # the lists of the sweeps, also for the smaller shapes
+    try:
+        for X, want_flag in ((rough, 1), (smooth, 0), (rough, 1)):
+            got = host(api.ecc_hard(dev(X), len(shape), bins, workspace=ws))
+            assert _overflow_flag(ws) == want_flag
+            t = O.thresholds_equal_width(X.min(), X.max(), bins)
+            np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, t))
+    finally:
+        api.ecc_debug_force(prev)
 
 
 @pytest.mark.parametrize("shape", [(70, 300), (9, 40, 130)])
-def test_float_extremes_denormals_and_neighbouring_floats(shape):
+def test_float_extremes_denormals_and_neighbouring_floats(shape, flow):
     # the fast sweeps decide "q before p" from the sign of a float difference: that is
     # exact only with gradual underflow, and must survive overflow of the difference
     tiny = np.float32(1e-45)  # smallest denormal
@@ -183,7 +188,7 @@ def test_largest_batch(shape):
     np.testing.assert_array_equal(gotf, OC.ecc_hard_batch(Xf, O.thresholds_equal_width(Xf.min(), Xf.max(), 5)))
 
 
-def test_one_bin_and_most_bins():
+def test_one_bin_and_most_bins(flow):
     X = synth.grf((70, 90), 2.0, 31)[None]
     for bins in (1, 16384):
         got = host(api.ecc_hard(dev(X), 2, bins))

@@ -1,0 +1,85 @@
+"""The two-launch flow for small float grids without a range (stage: per-block lists of critical
+vertices and value ranges; finish: range, thresholds, histogram and prefix sum in one block per
+item) at the edges of what it takes -- items of 2^16 vertices, 2^18 in the batch, 64 items, 4096
+bins, one to four vertices per thread, lists that are nearly full -- and just beyond them, with
+the same calls repeated with the flow switched off."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import ecc_oracle as O
+from oracle import ecc_oracle_c as OC
+from paper_2510_20271_amd import api, synth
+from tests.gpu_util import dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(fn):
+    a = fn()
+    prev = api.ecc_debug_force(api.ECC_FORCE_NO_SMALL)
+    try:
+        b = fn()
+    finally:
+        api.ecc_debug_force(prev)
+    assert torch.equal(a, b)
+    return host(a)
+
+
+# items of 2^16 vertices (one vertex per thread) and just above (not taken), 2 and 3 items (two /
+# three per thread), 2^18 vertices in all (four) and just above, the largest batch and beyond, 3D
+@pytest.mark.parametrize("B,shape", [(1, (256, 256)), (1, (257, 256)), (2, (200, 300)), (3, (256, 255)), (4, (256, 256)),
+                                      (5, (230, 230)), (64, (64, 64)), (65, (60, 60)), (64, (1, 1)), (2, (40, 40, 40)),
+                                      (7, (3, 70, 150))])
+def test_small_flow_sizes(B, shape):
+    nd = len(shape)
+    rng = np.random.default_rng(B + shape[-1])
+    X = rng.standard_normal((B,) + shape).astype(np.float32)  # white noise: long lists
+    got = _both(lambda: api.ecc_hard(dev(X), nd, 100))
+    np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(X.min(), X.max(), 100)))
+    U = rng.integers(0, 256, size=(B,) + shape, dtype=np.uint8)
+    got = _both(lambda: api.ecc_hard(dev(U), nd, 256))
+    np.testing.assert_array_equal(got, OC.ecc_hard_batch(U, O.thresholds_levels(256)))
+
+
+def test_small_flow_nearly_every_vertex_critical():
+    # a checkerboard: a vertex is a local minimum (c = 1) or closes cells, except on the border;
+    # the stage blocks' lists are full to the last few entries
+    y, x = np.mgrid[0:256, 0:256]
+    X = ((x + y) % 2).astype(np.float32)[None]
+    assert np.mean(OC.coeff(X[0]) != 0) > 0.99
+    got = _both(lambda: api.ecc_hard(dev(X), 2, 2))
+    np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(0.0, 1.0, 2)))
+
+
+@pytest.mark.parametrize("bins", [1, 2, 1023, 1024, 1025, 4096, 4097])
+def test_small_flow_bin_counts_and_scan(bins):
+    X = np.stack([synth.grf((100, 130), 1.0, 60 + i) for i in range(3)])
+    lo, hi = float(X.min()), float(X.max())
+    got = _both(lambda: api.ecc_hard(dev(X), 2, bins))
+    np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(lo, hi, bins)))
+    got = _both(lambda: api.ecc_hard(dev(X), 2, bins, range=(lo / 2, hi / 2)))
+    np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(lo / 2, hi / 2, bins)))
+    t = O.thresholds_lower(O.thresholds_equal_width(lo, hi, bins), lo)
+    got = _both(lambda: api.ecc_hard(dev(X), 2, bins, superlevel=True))
+    np.testing.assert_array_equal(got, O.ecc_super_batch(X, t, False))
+
+
+def test_small_flow_range_is_the_batch_range():
+    # the extremes sit in different items, in vertices that are not critical
+    X = np.stack([synth.grf((90, 70), 2.0, 5 + i) for i in range(4)])
+    X[1, 40, 30] = X.max() + 3.0   # a peak: enters last, closes cells (critical) ...
+    X[3, 0, 0] = X.min() - 2.0     # ... a pit: critical as well
+    X[2, 10:13, 10:13] = X.max() + 1.0  # a plateau: its later vertices are not all critical
+    got = _both(lambda: api.ecc_hard(dev(X), 2, 77))
+    np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(X.min(), X.max(), 77)))
+
+
+def test_small_flow_static_scratch_and_workspace_reuse():
+    X = np.stack([synth.grf((128, 128), 2.0, 15 + i) for i in range(2)])
+    want = OC.ecc_hard_batch(X, O.thresholds_equal_width(X.min(), X.max(), 64))
+    np.testing.assert_array_equal(host(api.ecc_hard_static(dev(X), 2, 64)), want)
+    ws = torch.full((api.ecc_workspace_bytes((128, 128), 2, 64),), 0xff, dtype=torch.uint8, device="cuda")  # garbage
+    for _ in range(3):
+        np.testing.assert_array_equal(host(api.ecc_hard(dev(X), 2, 64, workspace=ws)), want)

@@ -21,7 +21,7 @@ SHAPES = [(1, 1), (1, 9), (9, 1), (3, 3), (17, 65), (130, 257), (257, 259), (9, 
 @pytest.mark.parametrize("top", [False, True])
 @pytest.mark.parametrize("shape", SHAPES)
 @pytest.mark.parametrize("dtype", [np.uint8, np.uint16])
-def test_super_levels(shape, dtype, top):
+def test_super_levels(shape, dtype, top, flow):
     rng = np.random.default_rng(31)
     X = rng.integers(0, 13, size=(2,) + shape, dtype=dtype)
     got = host(api.ecc_hard(dev(X), len(shape), 11, top=top, superlevel=True))  # levels 11, 12 count as X >= 10
@@ -36,7 +36,7 @@ def test_super_levels(shape, dtype, top):
 
 @pytest.mark.parametrize("top", [False, True])
 @pytest.mark.parametrize("shape", SHAPES)
-def test_super_float(shape, top):
+def test_super_float(shape, top, flow):
     rng = np.random.default_rng(37)
     X = (rng.integers(-6, 7, size=(2,) + shape) / 4).astype(np.float32)
     X[X == 0] = rng.choice([0.0, -0.0], size=int((X == 0).sum())).astype(np.float32)
@@ -50,7 +50,7 @@ def test_super_float(shape, top):
 
 
 @pytest.mark.parametrize("top", [False, True])
-def test_super_smooth_fields(top):
+def test_super_smooth_fields(top, flow):
     X = np.stack([synth.grf((200, 520), 3.0, 5 + i) for i in range(2)])
     lo, hi = float(X.min()), float(X.max())
     t = O.thresholds_lower(O.thresholds_equal_width(lo, hi, 200), lo)
@@ -91,7 +91,7 @@ def test_ex_sublevel_is_ecc_hard_and_ecc_hard_top():
     np.testing.assert_array_equal(b, host(api.ecc_hard_top(dev(X), 2, 50)))
 
 
-def test_super_peaks():
+def test_super_peaks(flow):
     # three isolated peaks: the superlevel curve counts them, the sublevel curve never does
     X = np.zeros((1, 5, 5), np.uint8)
     X[0, 1, 1] = X[0, 3, 3] = 5

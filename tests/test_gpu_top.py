@@ -19,7 +19,7 @@ SHAPES = [(1, 1), (1, 9), (9, 1), (3, 3), (17, 65), (130, 257), (257, 259), (9, 
 
 @pytest.mark.parametrize("shape", SHAPES)
 @pytest.mark.parametrize("dtype", [np.uint8, np.uint16])
-def test_top_levels(shape, dtype):
+def test_top_levels(shape, dtype, flow):
     rng = np.random.default_rng(23)
     X = rng.integers(0, 13, size=(2,) + shape, dtype=dtype)
     got = host(api.ecc_hard_top(dev(X), len(shape), 11))  # the two top levels fall above the last threshold
@@ -27,7 +27,7 @@ def test_top_levels(shape, dtype):
 
 
 @pytest.mark.parametrize("shape", SHAPES)
-def test_top_float(shape):
+def test_top_float(shape, flow):
     rng = np.random.default_rng(29)
     X = (rng.integers(-6, 7, size=(2,) + shape) / 4).astype(np.float32)
     X[X == 0] = rng.choice([0.0, -0.0], size=int((X == 0).sum())).astype(np.float32)
@@ -39,7 +39,7 @@ def test_top_float(shape):
     assert np.all(want[:, -1] == 1)
 
 
-def test_top_smooth_fields_and_depth_one():
+def test_top_smooth_fields_and_depth_one(flow):
     X = np.stack([synth.grf((200, 520), 3.0, 5 + i) for i in range(2)])
     t = O.thresholds_equal_width(X.min(), X.max(), 200)
     want = O.ecc_top_batch(X, t)

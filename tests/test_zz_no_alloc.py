@@ -16,7 +16,7 @@ def test_static_scratch_two_calls_in_a_row():
     bins = 200
     big = dev(np.stack([synth.grf((600, 1000), 2.0, 11 + i) for i in range(3)]))      # single-pass list sweep
     small = dev(synth.grf((40, 50, 70), 1.5, 5)[None])                               # 3D, smaller
-    tiny = dev(np.random.default_rng(1).integers(0, 200, (2, 30, 40), dtype=np.uint8))  # levels, generic kernel
+    tiny = dev(np.random.default_rng(1).integers(0, 200, (2, 30, 40), dtype=np.uint8))  # levels, the flow for small inputs
     curve = torch.empty((3, bins), dtype=torch.int64, device="cuda")
     for _ in range(2):  # the scratch keeps the last call's contents: a second round must not see them
         a = api.ecc_hard_static(big, 2, bins, curve=curve)
