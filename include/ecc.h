@@ -334,11 +334,10 @@ int ecc_count_nonfinite(const void* grid, int64_t n, ecc_dtype dtype, unsigned l
  *                         vertices;
  *   ECC_FORCE_SOFT_TILES  soft path: the tile kernels for every shape;
  *   ECC_FORCE_NO_SMALL    hard curves: small float inputs without a range
- *                         (items of up to 2^16 vertices, up to 2^18 in the
- *                         batch, up to 64 items, up to 4096 bins) go through
- *                         the kernels of the large ones instead of the
- *                         two-launch flow made for them (any other bit
- *                         switches that flow off as well).
+ *                         (up to 2^18 vertices in up to 64 items, up to 4096
+ *                         bins) go through the kernels of the large ones
+ *                         instead of the two- / three-launch flow made for
+ *                         them (any other bit switches that flow off as well).
  * 0 restores normal operation.  Returns the previous mask.  The setting is
  * process-wide (one atomic word) and is read when a call is enqueued; results
  * are the same on every path, only the kernels differ.

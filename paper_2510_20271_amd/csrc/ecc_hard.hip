@@ -274,6 +274,11 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(long long* __restrict__ cu
   }
 }
 
+void launch_scan(int64_t* curve, const Shape& s, int bins, int suffix, hipStream_t st) {
+  hipLaunchKernelGGL(scan_kernel, dim3((unsigned)s.batch), dim3(kBlock), 0, st, reinterpret_cast<long long*>(curve), bins,
+                     suffix);
+}
+
 // ---------------------------------------------------------------------------
 // coefficient map (inspection / tests)
 // ---------------------------------------------------------------------------

@@ -49,6 +49,7 @@ struct HardHeader;
 // `small`: small_workspace_bytes(s) bytes behind the threshold table
 bool small_supported(const Shape& s, int bins);
 size_t small_workspace_bytes(const Shape& s);
+void launch_scan(int64_t* curve, const Shape& s, int bins, int suffix, hipStream_t st);  // in-place prefix / suffix sums
 hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_t* curve, HardHeader* hdr, float* table,
                              void* small, hipStream_t st, int conv);
 // single-pass mode: per-item lists of critical vertices (value, c) in the workspace

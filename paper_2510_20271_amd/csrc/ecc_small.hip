@@ -10,10 +10,13 @@
 //            histogram in LDS, the item's lists binned into it, the prefix sum, the int64 curve
 //            written out.
 // Binning, thresholds and conventions are those of the large-input kernels (ecc_device.h).
-// One block per item has to get through all of the item's critical vertices, so items are
-// limited to 2^16 vertices (white noise, 60 % critical: 256^2 in 34 us against 63 us through the
-// five-launch flow; 512^2 would take 94 us against 75 us).  With the thresholds known up front
-// (integer levels, a caller's range) the large-input flow has three launches and is as quick.
+// One block per item has to get through all of the item's critical vertices (white noise, 60 %
+// critical: 256^2 in 34 us against 63 us through the five-launch flow; 512^2 would take 94 us
+// against 75 us), so items of more than 2^16 vertices take three launches instead: the stage
+// blocks also clear the global histogram, the second kernel runs with several blocks per item,
+// each binning a share of the item's lists and adding its histogram to the global one, and the
+// scan is a launch of its own.  With the thresholds known up front (integer levels, a caller's
+// range) the large-input flow has three launches and is as quick.
 #include "ecc_device.h"
 #include "ecc_internal.h"
 
@@ -21,7 +24,8 @@ namespace ecc {
 
 constexpr int kStageBlock = 256, kFinishBlock = 1024;
 constexpr int64_t kSmallTotal = (int64_t)1 << 18;  // vertices in the whole batch
-constexpr int64_t kSmallItem = (int64_t)1 << 16;   // vertices in an item
+constexpr int64_t kSmallItem = (int64_t)1 << 16;   // vertices in an item that one finishing block takes
+constexpr unsigned kSmallShares = 16;              // finishing blocks per larger item
 constexpr int64_t kSmallBatch = 64;                // every finish block reads every stage block's header
 constexpr int kSmallBins = 4096;
 
@@ -52,7 +56,7 @@ static SmallPlan small_plan(const Shape& s) {
 }
 
 bool small_supported(const Shape& s, int bins) {
-  return s.N <= kSmallItem && s.N * s.batch <= kSmallTotal && s.batch <= kSmallBatch && bins <= kSmallBins;
+  return s.N * s.batch <= kSmallTotal && s.batch <= kSmallBatch && bins <= kSmallBins;
 }
 
 // headers and lists, placed behind the threshold table
@@ -65,7 +69,8 @@ template <int ND, int CONV>
 __global__ __launch_bounds__(kStageBlock) void small_stage_kernel(const float* __restrict__ grid, int D, int H, int W,
                                                                   int N, int per_thread,
                                                                   SmallHead* __restrict__ heads,
-                                                                  uint2* __restrict__ entries) {
+                                                                  uint2* __restrict__ entries,
+                                                                  unsigned long long* __restrict__ hist, int bins) {
   constexpr bool TOP = (CONV & kConvTop) != 0, SUPER = (CONV & kConvSuper) != 0;
   __shared__ unsigned s_count, s_min, s_max;
   if (threadIdx.x == 0) {
@@ -74,6 +79,9 @@ __global__ __launch_bounds__(kStageBlock) void small_stage_kernel(const float* _
     s_max = 0u;
   }
   __syncthreads();
+  if (hist)  // (three-launch form) the item's global histogram, cleared by the item's blocks together
+    for (int b = blockIdx.x * kStageBlock + threadIdx.x; b < bins; b += gridDim.x * kStageBlock)
+      hist[(int64_t)blockIdx.y * bins + b] = 0ull;
   const float* g = grid + (int64_t)blockIdx.y * N;
   const unsigned blk = blockIdx.y * gridDim.x + blockIdx.x;
   uint2* out = entries + (size_t)blk * (size_t)(kStageBlock * per_thread);
@@ -123,6 +131,10 @@ __global__ __launch_bounds__(kStageBlock) void small_stage_kernel(const float* _
   }
 }
 
+// ALONE: one block per item, which also scans and writes the curve.  Otherwise block (x, item) takes
+// the x-th share of the item's lists and adds its histogram to the global one (`curve`, cleared
+// by the stage kernel); the scan is a launch of its own.
+template <bool ALONE>
 __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallHead* __restrict__ heads,
                                                                     const uint2* __restrict__ entries,
                                                                     unsigned per_item, unsigned blocks, int per_block,
@@ -137,9 +149,13 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
   __shared__ unsigned wcnt[kFinishBlock / kWave];
   __shared__ unsigned off[kFinishBlock + 1];  // exclusive prefix sums of the lists' lengths
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
-  const unsigned item = blockIdx.x;
-  // length of the item's list number tid (requested before anything waits on memory)
-  const unsigned n_mine = tid < (int)per_item ? min(heads[item * per_item + tid].count, (unsigned)per_block) : 0u;
+  const unsigned item = ALONE ? blockIdx.x : blockIdx.y;
+  // this block's lists: all of the item's, or lists l0 .. l0 + nl of it
+  const unsigned share = ALONE ? per_item : (per_item + gridDim.x - 1) / gridDim.x;
+  const unsigned l0 = ALONE ? 0u : min(per_item, blockIdx.x * share), nl = min(share, per_item - l0);
+  // length of this block's list number tid (requested before anything waits on memory)
+  const unsigned n_mine = tid < (int)nl ? min(heads[item * per_item + l0 + tid].count, (unsigned)per_block) : 0u;
+  const bool first = item == 0 && (ALONE || blockIdx.x == 0);
   // the batch's range: every stage block's header
   if (tid == 0) {
     s_min = 0xffffffffu;
@@ -165,9 +181,9 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
     lhist[b] = 0;
     const float t = super ? threshold_lower_at(b, bins, lo_d, hi_d) : threshold_at(b, bins, lo_d, hi_d);
     ltable[b] = t;
-    if (item == 0) table[b] = t;
+    if (first) table[b] = t;
   }
-  if (item == 0 && tid == 0) {  // the header as the other flows leave it
+  if (first && tid == 0) {  // the header as the other flows leave it
     hdr->min_key = s_min;
     hdr->max_key = s_max;
     hdr->lo = lo;
@@ -194,7 +210,7 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
   }
   __syncthreads();
   const unsigned total = off[kFinishBlock];
-    constexpr unsigned kWaves = kFinishBlock / kWave, kDeep = 4;
+  constexpr unsigned kWaves = kFinishBlock / kWave, kDeep = 4;
   const unsigned piece = ((total + kWaves - 1) / kWaves + kWave - 1) / kWave * kWave;
   const unsigned begin = min(total, (unsigned)wv * piece), end = min(total, begin + piece);
   unsigned l = 0u;  // the last list that starts at or before `begin`
@@ -203,7 +219,7 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
     for (unsigned step = kFinishBlock / 2; step > 0; step >>= 1)
       if (off[l + step] <= begin) l += step;
   }
-  const uint2* mine = entries + (size_t)item * per_item * (size_t)per_block;
+  const uint2* mine = entries + ((size_t)item * per_item + l0) * (size_t)per_block;
   for (unsigned f0 = begin + lane; f0 < end + lane; f0 += kWave * kDeep) {  // (wave-uniform trip count)
     uint2 e[kDeep];
     bool ok[kDeep];
@@ -228,6 +244,14 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
     }
   }
   __syncthreads();
+  if constexpr (!ALONE) {
+    unsigned long long* out = reinterpret_cast<unsigned long long*>(curve) + (int64_t)item * bins;
+    for (int b = tid; b < bins; b += kFinishBlock) {
+      const int v = lhist[b];
+      if (v != 0) atomicAdd(&out[b], (unsigned long long)(long long)v);
+    }
+    return;
+  }
   // inclusive prefix sum over the bins (suffix sum for superlevel sets: the mirrored index)
   const int per = (bins + kFinishBlock - 1) / kFinishBlock;
   const int b0 = min(tid * per, bins), b1 = min(b0 + per, bins);
@@ -258,10 +282,12 @@ hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_
   SmallHead* heads = static_cast<SmallHead*>(small);
   uint2* entries = reinterpret_cast<uint2*>(static_cast<char*>(small) + p.head_bytes);
   const dim3 g(p.per_item, (unsigned)s.batch);
+  const bool alone = s.N <= kSmallItem;
+  unsigned long long* hist = reinterpret_cast<unsigned long long*>(curve);
   profile_mark(st, false);
 #define ECC_GO(ND, CV)                                                                                       \
   hipLaunchKernelGGL((small_stage_kernel<ND, CV>), g, dim3(kStageBlock), 0, st, grid, (int)s.D, (int)s.H,     \
-                     (int)s.W, (int)s.N, p.per_thread, heads, entries)
+                     (int)s.W, (int)s.N, p.per_thread, heads, entries, alone ? nullptr : hist, bins)
 #define ECC_CONV(ND)                   \
   switch (conv) {                      \
     case 1: ECC_GO(ND, 1); break;      \
@@ -273,9 +299,17 @@ hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_
 #undef ECC_CONV
 #undef ECC_GO
   profile_mark(st, true);
-  hipLaunchKernelGGL(small_finish_kernel, dim3((unsigned)s.batch), dim3(kFinishBlock),
-                     (size_t)bins * (sizeof(int) + sizeof(float)), st, heads, entries, p.per_item, p.blocks,
-                     p.per_block, bins, (conv & kConvSuper) ? 1 : 0, hdr, table, reinterpret_cast<long long*>(curve));
+  const size_t lds = (size_t)bins * (sizeof(int) + sizeof(float));
+  const int super = (conv & kConvSuper) ? 1 : 0;
+  if (alone) {
+    hipLaunchKernelGGL(small_finish_kernel<true>, dim3((unsigned)s.batch), dim3(kFinishBlock), lds, st, heads, entries,
+                       p.per_item, p.blocks, p.per_block, bins, super, hdr, table, reinterpret_cast<long long*>(curve));
+  } else {
+    hipLaunchKernelGGL(small_finish_kernel<false>, dim3(kSmallShares, (unsigned)s.batch), dim3(kFinishBlock), lds, st,
+                       heads, entries, p.per_item, p.blocks, p.per_block, bins, super, hdr, table,
+                       reinterpret_cast<long long*>(curve));
+    launch_scan(curve, s, bins, super, st);
+  }
   return hipGetLastError();
 }
 

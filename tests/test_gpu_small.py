@@ -1,8 +1,9 @@
-"""The two-launch flow for small float grids without a range (stage: per-block lists of critical
-vertices and value ranges; finish: range, thresholds, histogram and prefix sum in one block per
-item) at the edges of what it takes -- items of 2^16 vertices, 2^18 in the batch, 64 items, 4096
-bins, one to four vertices per thread, lists that are nearly full -- and just beyond them, with
-the same calls repeated with the flow switched off."""
+"""The flow for small float grids without a range (stage: per-block lists of critical vertices and
+value ranges; finish: range, thresholds, histogram and prefix sum in one block per item, or, for
+items above 2^16 vertices, several blocks per item and the scan as a third launch) at the edges of
+what it takes -- items of 2^16 vertices, 2^18 in the batch, 64 items, 4096 bins, one to four
+vertices per thread, lists that are nearly full -- and just beyond them, with the same calls
+repeated with the flow switched off."""
 import numpy as np
 import pytest
 
@@ -27,11 +28,13 @@ def _both(fn):
     return host(a)
 
 
-# items of 2^16 vertices (one vertex per thread) and just above (not taken), 2 and 3 items (two /
-# three per thread), 2^18 vertices in all (four) and just above, the largest batch and beyond, 3D
+# items of 2^16 vertices (one vertex per thread) and just above (three launches), 2 and 3 items (two /
+# three per thread), 2^18 vertices in all (four) and just above (not taken), larger items (three
+# launches, 16 blocks per item), the largest batch and beyond, 3D
 @pytest.mark.parametrize("B,shape", [(1, (256, 256)), (1, (257, 256)), (2, (200, 300)), (3, (256, 255)), (4, (256, 256)),
-                                      (5, (230, 230)), (64, (64, 64)), (65, (60, 60)), (64, (1, 1)), (2, (40, 40, 40)),
-                                      (7, (3, 70, 150))])
+                                      (5, (230, 230)), (1, (512, 512)), (2, (300, 400)), (1, (500, 524)), (1, (3, 87381)),
+                                      (64, (64, 64)), (65, (60, 60)), (64, (1, 1)), (2, (40, 40, 40)),
+                                      (1, (64, 64, 64)), (7, (3, 70, 150))])
 def test_small_flow_sizes(B, shape):
     nd = len(shape)
     rng = np.random.default_rng(B + shape[-1])
@@ -53,9 +56,10 @@ def test_small_flow_nearly_every_vertex_critical():
     np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(0.0, 1.0, 2)))
 
 
+@pytest.mark.parametrize("shape", [(100, 130), (270, 300)])
 @pytest.mark.parametrize("bins", [1, 2, 1023, 1024, 1025, 4096, 4097])
-def test_small_flow_bin_counts_and_scan(bins):
-    X = np.stack([synth.grf((100, 130), 1.0, 60 + i) for i in range(3)])
+def test_small_flow_bin_counts_and_scan(bins, shape):
+    X = np.stack([synth.grf(shape, 1.0, 60 + i) for i in range(3)])
     lo, hi = float(X.min()), float(X.max())
     got = _both(lambda: api.ecc_hard(dev(X), 2, bins))
     np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(lo, hi, bins)))
