@@ -464,10 +464,19 @@ def main():
             api.ecc_soft_fwd(gv, 3, uv, 0.01, tv, 20.0, workspace=wsv)
             api.ecc_soft_bwd(gv, 3, uv, 0.01, tv, 20.0, grad_chi=Gv, grad_X=gxv, workspace=wsv)
         msv = time_steps(stepv, args.steps, args.warmup)
+        stv = torch.empty(api.ecc_soft_state_bytes(V.shape[1:], 1), dtype=torch.uint8, device="cuda")
+        chv = torch.empty((1, T3), dtype=torch.float32, device="cuda")
+        dtv, duv = torch.empty_like(chv), torch.empty((1, T3, 3), dtype=torch.float32, device="cuda")
+
+        def stepv_saved():
+            api.ecc_soft_fwd_save(gv, 3, uv, 0.01, tv, 20.0, chi=chv, dchi_dtau=dtv, dchi_du=duv, state=stv, workspace=wsv)
+            api.ecc_soft_bwd_saved(gv, 3, uv, 0.01, tv, 20.0, stv, grad_chi=Gv, grad_X=gxv, workspace=wsv)
+        mss = time_steps(stepv_saved, args.steps, args.warmup)
         extra["soft_3d"] = {"workload": "soft fwd+bwd, one 256^3 float32 GRF sigma=3, T=64, lambda=20, alpha=0.01",
-                            "ms_fwd_plus_bwd": round(msv, 4)}
-        log(f"[bench] soft 3D 256^3: fwd+bwd {msv:.4f} ms")
-        del gv, gxv, wsv
+                            "ms_fwd_plus_bwd": round(mss, 4), "entry_points": "ecc_soft_fwd_save + ecc_soft_bwd_saved",
+                            "ms_stateless_fwd_plus_bwd": round(msv, 4)}
+        log(f"[bench] soft 3D 256^3: fwd_save+bwd_saved {mss:.4f} ms, stateless fwd+bwd {msv:.4f} ms")
+        del gv, gxv, wsv, stv
         torch.cuda.empty_cache()
 
     # ---------------- the grid sizes of the paper's Tables 1-2 -------------------

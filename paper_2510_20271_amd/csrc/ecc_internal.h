@@ -108,7 +108,7 @@ struct SavedEntry {
 };
 struct SoftStateHeader {
   unsigned magic;
-  int H, W, batch, nstrip, nseg, rows_per_seg, tiltc;
+  int D, H, W, batch, nstrip, nseg, rows_per_seg, units, tiltc;  // (3D: rows_per_seg holds the planes per segment)
   unsigned cap;  // entries per unit
 };
 constexpr unsigned kSoftStateMagic = 0x45434353u;
@@ -126,6 +126,16 @@ void launch_soft2d_fwd_save(const float* grid, const Shape& s, const float* u, f
                             float lambda, float* chi, float* dtau, float* du, void* state, void* ws, hipStream_t st,
                             bool tiltc);
 void launch_soft2d_bwd_saved(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
+                             float lambda, const float* gup, float* grad_X, const void* state, hipStream_t st,
+                             bool tiltc);
+
+// fused 3D implementation of the two (volumes of fewer than 2^31 vertices that soft3d_supported takes)
+bool soft3d_state_supported(const Shape& s, int T);
+size_t soft3d_state_bytes(const Shape& s);
+void launch_soft3d_fwd_save(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
+                            float lambda, float* chi, float* dtau, float* du, void* state, void* ws, hipStream_t st,
+                            bool tiltc);
+void launch_soft3d_bwd_saved(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
                              float lambda, const float* gup, float* grad_X, const void* state, hipStream_t st,
                              bool tiltc);
 

@@ -386,13 +386,17 @@ hipError_t launch_soft_bwd(const float* grid, const Shape& s, const float* u, fl
 }
 
 // ---- forward pass that saves its critical vertices, backward pass that reuses them ---------------
-size_t soft_state_bytes(const Shape& s) { return soft2d_state_bytes(s); }
+size_t soft_state_bytes(const Shape& s) { return s.ndim == 3 ? soft3d_state_bytes(s) : soft2d_state_bytes(s); }
 
 hipError_t launch_soft_fwd_save(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
                                 int T, float lambda, float* chi, float* dtau, float* du, void* state, void* ws,
                                 hipStream_t st, bool tiltc) {
   if (use_soft2d(s, T)) {
     launch_soft2d_fwd_save(grid, s, u, alpha, tau, T, lambda, chi, dtau, du, state, ws, st, tiltc);
+    return hipGetLastError();
+  }
+  if (use_soft3d(s, T) && soft3d_state_supported(s, T)) {
+    launch_soft3d_fwd_save(grid, s, u, alpha, tau, T, lambda, chi, dtau, du, state, ws, st, tiltc);
     return hipGetLastError();
   }
   // other shapes keep no state: the forward pass, then the threshold / direction sums of the backward one
@@ -407,6 +411,10 @@ hipError_t launch_soft_bwd_saved(const float* grid, const Shape& s, const float*
                                  hipStream_t st, bool tiltc) {
   if (use_soft2d(s, T)) {
     launch_soft2d_bwd_saved(grid, s, u, alpha, tau, T, lambda, gup, grad_X, state, st, tiltc);
+    return hipGetLastError();
+  }
+  if (use_soft3d(s, T) && soft3d_state_supported(s, T)) {
+    launch_soft3d_bwd_saved(grid, s, u, alpha, tau, T, lambda, gup, grad_X, state, st, tiltc);
     return hipGetLastError();
   }
   return launch_soft_bwd(grid, s, u, alpha, tau, T, lambda, gup, grad_X, nullptr, nullptr, ws, st, tiltc);

@@ -23,6 +23,7 @@
 // [min tau, max tau] that every sigmoid is 0 or 1 to 2^-64 is not evaluated at all: it adds
 // c to every threshold (sigma = 1) or nothing, and nothing to the derivatives.
 #include "ecc_sweep2d.h"
+#include "ecc_soft_saved.h"
 
 namespace ecc {
 
@@ -185,48 +186,15 @@ struct SoftBwdSink : SoftCommon {
   }
 };
 
-// ---- state saved by the forward pass for the backward pass -----------------------------------
-// Header as ecc_internal.h describes it, followed by a generation number: every saving forward
-// pass raises it by one (its reduction kernel does, after the sweep), and a unit that runs out
-// of room writes the generation it belongs to into its item's overflow word.  An item's lists
-// are usable when the header matches the shape and that word is not the current generation --
-// so nothing in the state ever needs clearing, whatever it held before.
-struct StateView {
-  SoftStateHeader* hdr;
-  unsigned* gen;       // generation of the lists the state holds
-  unsigned* overflow;  // [batch]: generation in which a unit of the item last ran out of room
-  unsigned* counts;    // [batch][units]: critical vertices each unit found (may exceed cap)
-  SavedEntry* lists;   // [batch][units][cap]
-};
-static size_t align256(size_t n) { return (n + 255) / 256 * 256; }
 static unsigned state_cap(const Plan2d& pl) {
   // room for one vertex in eight of a unit's rows x 248 columns (64 entries at least)
   const unsigned v = (unsigned)pl.rows_per_seg * (unsigned)kStripOut / 8u;
   return (v < 64u ? 64u : v);
 }
-static StateView state_view(void* state, const Shape& s, const Plan2d& pl) {
-  char* b = static_cast<char*>(state);
-  const size_t units = (size_t)pl.nstrip * pl.nseg;
-  StateView v;
-  v.hdr = reinterpret_cast<SoftStateHeader*>(b);
-  v.gen = reinterpret_cast<unsigned*>(b + 128);
-  v.overflow = reinterpret_cast<unsigned*>(b + 256);
-  v.counts = reinterpret_cast<unsigned*>(b + 256 + align256((size_t)s.batch * 4));
-  v.lists = reinterpret_cast<SavedEntry*>(b + 256 + align256((size_t)s.batch * 4) + align256((size_t)s.batch * units * 4));
-  return v;
-}
 size_t soft2d_state_bytes(const Shape& s) {
   if (!soft2d_supported(s, 1)) return 256;
   const Plan2d pl = plan2d<float>(s, true);
-  const size_t units = (size_t)pl.nstrip * pl.nseg;
-  return 256 + align256((size_t)s.batch * 4) + align256((size_t)s.batch * units * 4) +
-         (size_t)s.batch * units * state_cap(pl) * sizeof(SavedEntry);
-}
-__device__ __forceinline__ bool state_usable(const StateView& v, const SoftStateHeader& e, int item) {
-  const SoftStateHeader h = *v.hdr;
-  return h.magic == e.magic && h.H == e.H && h.W == e.W && h.batch == e.batch && h.nstrip == e.nstrip &&
-         h.nseg == e.nseg && h.rows_per_seg == e.rows_per_seg && h.tiltc == e.tiltc && h.cap == e.cap &&
-         v.overflow[item] != *v.gen;
+  return state_bytes(s.batch, (size_t)pl.nstrip * pl.nseg, state_cap(pl));
 }
 
 // LDS: [4 waves] value rings, then [4 waves] queues of SoftEntry
@@ -583,16 +551,6 @@ __global__ __launch_bounds__(kRedWaves * kWave) void soft2d_save_reduce_kernel(
 // the call lasts as long as its busiest unit.
 // An item whose lists cannot be used (header of another shape, a unit ran out of room) is
 // computed from the grid instead, vertex by vertex with the plain stencil: slow, but rare.
-constexpr int kSavedLanes = 8;  // lanes per entry
-struct StagedEntry {
-  float yh, yl, c;
-  int idx;
-};
-__device__ __forceinline__ float soft_dsig(float tau, float yh, float yl, float kneg) {  // sigma (1 - sigma)
-  const float ex = soft_exp_neg((tau - yh) - yl, kneg);
-  const float s = __builtin_amdgcn_rcpf(1.0f + ex);
-  return ex * s * s;
-}
 template <bool TILTC>
 __global__ __launch_bounds__(256) void soft2d_bwd_saved_kernel(const float* __restrict__ grid, int H, int W, int64_t N,
                                                                int nstrip, int nseg, int rows_per_seg,
@@ -681,50 +639,7 @@ __global__ __launch_bounds__(256) void soft2d_bwd_saved_kernel(const float* __re
     return;
   }
 
-  // (<= cap when the forward pass wrote it: the item did not overflow; clamped all the same, and
-  // positions are checked below, so that a state that was never written cannot lead out of bounds)
-  const unsigned cnt = min(cnt_raw, expect.cap);
-  const int q = lane & (kSavedLanes - 1), slot = threadIdx.x / kSavedLanes;  // 32 entries per pass
-  for (unsigned e0 = 0; e0 < cnt; e0 += 256) {
-    bool keep = false;
-    StagedEntry mine;
-    if (e0 + threadIdx.x < cnt) {
-      const SavedEntry en = e0 == 0 ? first : list[e0 + threadIdx.x];
-      mine.yh = (float)en.y;
-      mine.yl = (float)(en.y - (double)mine.yh);
-      mine.c = (float)en.c;
-      mine.idx = en.idx;
-      keep = mine.yh > sat_lo && mine.yh < sat_hi;
-    }
-    const unsigned long long m = __builtin_amdgcn_ballot_w64(keep);
-    if (lane == 0) skept[wv] = __builtin_popcountll(m);
-    __syncthreads();  // (also: the previous round's readers of the stage are done)
-    int base = 0, kept = 0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      if (w < wv) base += skept[w];
-      kept += skept[w];
-    }
-    const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
-    if (keep) stage[pos] = mine;
-    __syncthreads();
-    for (int b = 0; b < kept; b += 256 / kSavedLanes) {
-      const bool on = b + slot < kept;
-      const StagedEntry en = stage[on ? b + slot : 0];
-      float g0 = 0.0f, g1 = 0.0f;  // two independent chains
-      int j = q;
-      for (; j + kSavedLanes < T; j += 2 * kSavedLanes) {
-        g0 += sg[j] * soft_dsig(stau[j], en.yh, en.yl, kneg);
-        g1 += sg[j + kSavedLanes] * soft_dsig(stau[j + kSavedLanes], en.yh, en.yl, kneg);
-      }
-      if (j < T) g0 += sg[j] * soft_dsig(stau[j], en.yh, en.yl, kneg);
-      float gd = g0 + g1;
-      gd += dpp_move<0xB1, 0xf>(gd);   // quad_perm [1,0,3,2]
-      gd += dpp_move<0x4E, 0xf>(gd);   // quad_perm [2,3,0,1]
-      gd += dpp_move<0x141, 0xf>(gd);  // row_half_mirror: the other quad of the eight
-      if (on && q == 0 && (unsigned)en.idx < (unsigned)N) gx[en.idx] = -lambda * en.c * gd;
-    }
-  }
+  saved_lists_to_grad(list, cnt_raw, expect.cap, first, stau, sg, T, kneg, lambda, sat_lo, sat_hi, gx, N, stage, skept);
 }
 
 static float kneg2d(float lambda) { return (float)(-(double)lambda * 1.4426950408889634); }
@@ -782,6 +697,8 @@ void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float 
 static SoftStateHeader state_header(const Shape& s, const Plan2d& pl, bool tiltc) {
   SoftStateHeader h;
   h.magic = kSoftStateMagic;
+  h.D = 1;
+  h.units = pl.nstrip * pl.nseg;
   h.H = (int)s.H;
   h.W = (int)s.W;
   h.batch = (int)s.batch;
@@ -797,7 +714,7 @@ void launch_soft2d_fwd_save(const float* grid, const Shape& s, const float* u, f
                             float lambda, float* chi, float* dtau, float* du, void* state, void* ws, hipStream_t st,
                             bool tiltc) {
   const Plan2d pl = plan2d<float>(s, true);
-  const StateView sv = state_view(state, s, pl);
+  const StateView sv = state_view(state, s.batch, (size_t)pl.nstrip * pl.nseg);
   const SoftStateHeader hdr = state_header(s, pl, tiltc);
   float* partial = static_cast<float*>(ws);
   const bool deriv = dtau || du;
@@ -818,7 +735,7 @@ void launch_soft2d_bwd_saved(const float* grid, const Shape& s, const float* u, 
                              float lambda, const float* gup, float* grad_X, const void* state, hipStream_t st,
                              bool tiltc) {
   const Plan2d pl = plan2d<float>(s, true);
-  const StateView sv = state_view(const_cast<void*>(state), s, pl);
+  const StateView sv = state_view(const_cast<void*>(state), s.batch, (size_t)pl.nstrip * pl.nseg);
   const SoftStateHeader expect = state_header(s, pl, tiltc);
   const dim3 g((unsigned)(pl.nstrip * pl.nseg), (unsigned)s.batch);
   profile_mark(st, false);

@@ -96,9 +96,9 @@ def test_saved_state_of_another_shape_is_noticed():
         _close(gx[i], ref[i], 1e-3, f"grad_X[{i}]")
 
 
-@pytest.mark.parametrize("shape,T", [((9, 30, 70), 5), ((60, 70), 300)])
+@pytest.mark.parametrize("shape,T", [((9, 30, 7), 5), ((60, 70), 300), ((9, 30, 70), 300)])
 def test_saved_state_entry_points_on_shapes_without_state(shape, T):
-    # 3D grids and T > 256 keep no state: the same entry points run the stateless kernels
+    # volumes narrower than 8 and T > 256 keep no state: the same entry points run the stateless kernels
     nd = len(shape)
     Xb = np.stack([synth.grf(shape, 1.5, 60 + i) for i in range(2)])
     u = np.array([0.6, 0.8] if nd == 2 else [0.48, -0.6, 0.64], np.float32)
@@ -127,3 +127,70 @@ def test_saved_state_is_deterministic_and_config_c5():
         _close_sum(dt[i], rdt[i], 1e-3, f"dchi_dtau[{i}]")
         _close_sum(du[i], rdu[i], 1e-3, f"dchi_du[{i}]")
         _close(gx[i], rgx[i], 1e-3, f"grad_X[{i}]")
+
+
+# ---- volumes: the tube sweep keeps its critical vertices the same way ---------------------------
+
+
+@pytest.mark.parametrize("shape", [(2, 2, 8), (5, 6, 9), (9, 30, 70), (40, 33, 129), (70, 20, 64), (3, 131, 200)])
+def test_saved_state_3d_shapes(shape):
+    B, T = 2, 9
+    Xb = np.stack([synth.grf(shape, 1.0, 50 + i) for i in range(B)])
+    tau = np.linspace(Xb.min() - 0.1, Xb.max() + 0.5, T).astype(np.float32)
+    u = np.array([0.48, -0.6, 0.64], np.float32)
+    G = np.random.default_rng(2).standard_normal((B, T)).astype(np.float32)
+    _case(Xb, u, np.float32(0.02), tau, np.float32(8.0), G)
+
+
+@pytest.mark.parametrize("T", [1, 64, 65, 256])
+def test_saved_state_3d_threshold_counts_tilted_and_quantised(T):
+    B = 2
+    Xb = np.stack([np.round(synth.grf((20, 40, 130), 2.0, 7 + i) * 40) / 8 for i in range(B)]).astype(np.float32)
+    u = np.array([-0.8, 0.0, 0.6], np.float32)
+    G = np.random.default_rng(T).standard_normal((B, T)).astype(np.float32)
+    for tilted in (False, True):
+        Y = np.stack([O.tilt_field(x, u, np.float32(0.03)) for x in Xb])
+        tau = np.linspace(Y.min() - 0.1, Y.max() + 0.2, T).astype(np.float32)
+        _case(Xb, u, np.float32(0.03), tau, np.float32(9.0), G, tilted=tilted)
+
+
+def test_saved_state_3d_overflow_other_thresholds_and_reuse():
+    # item 1 is white noise: its lists overflow and its grad_X comes from the grid
+    shape = (30, 24, 130)
+    Xb = np.stack([synth.grf(shape, 2.0, 3), np.random.default_rng(4).standard_normal(shape).astype(np.float32),
+                   synth.grf(shape, 2.0, 5)])
+    tau = np.linspace(-2, 3, 10).astype(np.float32)
+    u = np.array([0.28, 0.0, 0.96], np.float32)
+    G = np.random.default_rng(2).standard_normal((3, 10)).astype(np.float32)
+    state = _case(Xb, u, np.float32(0.004), tau, np.float32(5.0), None,
+                  tau_bwd=(tau[::-1] * 0.9).astype(np.float32).copy()[:7], lam_bwd=np.float32(7.0))
+    gen = int(host(state[128:132]).view(np.uint32)[0])
+    flags = host(state[256:256 + 12]).view(np.uint32)
+    assert [int(f) == gen for f in flags] == [False, True, False]
+    # the same buffer again (its generation moves on), then handed to a backward call of another shape
+    _case(Xb[::-1].copy(), u, np.float32(0.004), tau, np.float32(5.0), G, state=state)
+    Xc = np.stack([synth.grf((30, 24, 66), 2.0, 9 + i) for i in range(3)])
+    big = torch.empty(max(state.numel(), api.ecc_soft_state_bytes((30, 24, 66), 3)), dtype=torch.uint8, device="cuda")
+    big[:state.numel()] = state
+    gx = host(api.ecc_soft_bwd_saved(dev(Xc), 3, dev(u), 0.004, dev(tau), 5.0, big))
+    ref = O.soft_bwd_batch(Xc, u, 0.004, tau, 5.0, None)[0]
+    for i in range(3):
+        _close(gx[i], ref[i], 1e-3, f"grad_X[{i}]")
+
+
+def test_saved_state_3d_is_deterministic_and_agrees_with_the_stateless_pass():
+    Xb = np.stack([synth.grf((48, 50, 70), 1.5, 21 + i) for i in range(2)])
+    u = np.array([0.48, -0.6, 0.64], np.float32)
+    tau = np.linspace(Xb.min(), Xb.max(), 33).astype(np.float32)
+    g, ud, td = dev(Xb), dev(u), dev(tau)
+    a = api.ecc_soft_fwd_save(g, 3, ud, 0.01, td, 20.0)
+    b = api.ecc_soft_fwd_save(g, 3, ud, 0.01, td, 20.0)
+    for x, y in zip(a[:3], b[:3]):
+        assert torch.equal(x, y)
+    assert torch.equal(api.ecc_soft_bwd_saved(g, 3, ud, 0.01, td, 20.0, a[3]),
+                       api.ecc_soft_bwd_saved(g, 3, ud, 0.01, td, 20.0, b[3]))
+    # the stateless backward pass gives the same grad_X (same arithmetic per vertex, other kernels)
+    ref = api.ecc_soft_bwd(g, 3, ud, 0.01, td, 20.0)[0]
+    got = api.ecc_soft_bwd_saved(g, 3, ud, 0.01, td, 20.0, a[3])
+    for i in range(2):
+        _close(host(got)[i], host(ref)[i], 1e-3, "grad_X")
