@@ -214,11 +214,12 @@ int ecc_soft_bwd(const float* grid, int ndim, const int64_t* dims, int64_t batch
  *          grad_chi may differ between the two calls -- and the caller must pass
  *          the same grid (unchanged), u and alpha to ecc_soft_bwd_saved.  A state
  *          written for another shape, and an item with so many vertices of c != 0
- *          (more than one in eight of some unit of rows) that its list overflowed,
- *          are noticed on the device: those items are swept again, as ecc_soft_bwd
- *          would, so the result is right either way.
- * Shapes outside the fused 2D kernels (3D grids, T > 256) keep no state: the two
- * calls then run ecc_soft_fwd + ecc_soft_bwd's kernels.  workspace as ecc_soft_fwd.
+ *          (more than one in eight of some unit of rows / planes) that its list
+ *          overflowed, are noticed on the device: those items are evaluated from
+ *          the grid again, so the result is right either way.
+ * Shapes outside the fused kernels (T > 256, grids narrower than 8, volumes of
+ * 2^31 vertices or more) keep no state: the two calls then run ecc_soft_fwd +
+ * ecc_soft_bwd's kernels.  workspace as ecc_soft_fwd.
  */
 size_t ecc_soft_state_bytes(int ndim, const int64_t* dims /* host */, int64_t batch);
 int ecc_soft_fwd_save(const float* grid, int ndim, const int64_t* dims, int64_t batch, const float* u,
