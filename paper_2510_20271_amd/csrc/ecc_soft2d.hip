@@ -24,6 +24,7 @@
 // c to every threshold (sigma = 1) or nothing, and nothing to the derivatives.
 #include "ecc_sweep2d.h"
 #include "ecc_soft_saved.h"
+#include "ecc_soft_reduce.h"
 
 namespace ecc {
 
@@ -405,141 +406,15 @@ __global__ __launch_bounds__(256) void soft2d_fwd_save_kernel(const float* __res
   }
 }
 
-// Reduction over units: block (x = group of 64 thresholds, y = item) of 16 waves; wave w
-// adds units w, w+16, ... in order (eight loads in flight at a time: a lone large image
-// has thousands of units and one block per 64 thresholds), then wave 0 adds the 16 sums
-// in order.
-constexpr int kRedWaves = 16, kRedUnroll = 8;
-
-__global__ __launch_bounds__(kRedWaves * kWave) void soft2d_fwd_reduce_kernel(const float* __restrict__ partial,
-                                                                              int units, int T,
-                                                                              float* __restrict__ chi) {
-  __shared__ double red[kRedWaves][kWave];
-  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
-  const int j = blockIdx.x * kWave + lane;
-  const float* p = partial + (int64_t)blockIdx.y * units * T + j;
-  double s = 0.0;
-  if (j < T) {
-    int q = wv;
-    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
-      float v[kRedUnroll];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) s += (double)v[k];
-    }
-    for (; q < units; q += kRedWaves) s += (double)p[(int64_t)q * T];
+// origin of a unit's coordinates, for the reduction of ecc_soft_reduce.h
+struct Origin2 {
+  int nstrip, rows_per_seg;
+  __device__ __forceinline__ void operator()(int unit, int (&o)[3]) const {
+    o[0] = (unit % nstrip) * kStripOut - kNC;
+    o[1] = (unit / nstrip) * rows_per_seg;
+    o[2] = 0;
   }
-  red[wv][lane] = s;
-  __syncthreads();
-  if (wv == 0 && j < T) {
-    double r = red[0][lane];
-    for (int w = 1; w < kRedWaves; ++w) r += red[w][lane];
-    chi[(int64_t)blockIdx.y * T + j] = (float)r;
-  }
-}
-
-// dchi_dtau = lambda sum A0;  dchi_du = -alpha lambda sum (origin * A0 + A_xy)
-__global__ __launch_bounds__(kRedWaves * kWave) void soft2d_bwd_reduce_kernel(
-    const float* __restrict__ partial, int units, int nstrip, int rows_per_seg, int T, float alpha, float lambda,
-    float* __restrict__ dtau, float* __restrict__ du) {
-  __shared__ double red[3][kRedWaves][kWave];
-  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
-  const int j = blockIdx.x * kWave + lane;
-  const float4* p = reinterpret_cast<const float4*>(partial) + (int64_t)blockIdx.y * units * T + j;
-  double s0 = 0.0, sx = 0.0, sy = 0.0;
-  auto add = [&](int q, const float4& e) {
-    const double ox = (double)((q % nstrip) * kStripOut - kNC), oy = (double)((q / nstrip) * rows_per_seg);
-    const double a0 = (double)e.x;
-    s0 += a0;
-    sx += ox * a0 + (double)e.y;
-    sy += oy * a0 + (double)e.z;
-  };
-  if (j < T) {
-    int q = wv;
-    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
-      float4 v[kRedUnroll];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) add(q + k * kRedWaves, v[k]);
-    }
-    for (; q < units; q += kRedWaves) add(q, p[(int64_t)q * T]);
-  }
-  red[0][wv][lane] = s0;
-  red[1][wv][lane] = sx;
-  red[2][wv][lane] = sy;
-  __syncthreads();
-  if (wv == 0 && j < T) {
-    const int64_t k = (int64_t)blockIdx.y * T + j;
-    double r[3];
-    for (int c = 0; c < 3; ++c) {
-      r[c] = red[c][0][lane];
-      for (int w = 1; w < kRedWaves; ++w) r[c] += red[c][w][lane];
-    }
-    if (dtau) dtau[k] = (float)((double)lambda * r[0]);
-    if (du) {
-      du[k * 2 + 0] = (float)(-(double)alpha * (double)lambda * r[1]);
-      du[k * 2 + 1] = (float)(-(double)alpha * (double)lambda * r[2]);
-    }
-  }
-}
-
-
-// Reduction of the saving forward pass: chi, dchi_dtau and dchi_du from one set of partial sums
-// (same fixed order as the two reductions above); block (0, 0) writes the header and raises the
-// state's generation.
-__global__ __launch_bounds__(kRedWaves * kWave) void soft2d_save_reduce_kernel(
-    const float* __restrict__ partial, int units, int nstrip, int rows_per_seg, int T, float alpha, float lambda,
-    float* __restrict__ chi, float* __restrict__ dtau, float* __restrict__ du, StateView sv, SoftStateHeader hdr) {
-  __shared__ double red[4][kRedWaves][kWave];
-  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
-  const int j = blockIdx.x * kWave + lane;
-  const float4* p = reinterpret_cast<const float4*>(partial) + (int64_t)blockIdx.y * units * T + j;
-  double sc = 0.0, s0 = 0.0, sx = 0.0, sy = 0.0;
-  auto add = [&](int q, const float4& e) {
-    const double ox = (double)((q % nstrip) * kStripOut - kNC), oy = (double)((q / nstrip) * rows_per_seg);
-    const double a0 = (double)e.y;
-    sc += (double)e.x;
-    s0 += a0;
-    sx += ox * a0 + (double)e.z;
-    sy += oy * a0 + (double)e.w;
-  };
-  if (j < T) {
-    int q = wv;
-    for (; q + (kRedUnroll - 1) * kRedWaves < units; q += kRedUnroll * kRedWaves) {
-      float4 v[kRedUnroll];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) v[k] = p[(int64_t)(q + k * kRedWaves) * T];
-#pragma unroll
-      for (int k = 0; k < kRedUnroll; ++k) add(q + k * kRedWaves, v[k]);
-    }
-    for (; q < units; q += kRedWaves) add(q, p[(int64_t)q * T]);
-  }
-  red[0][wv][lane] = sc;
-  red[1][wv][lane] = s0;
-  red[2][wv][lane] = sx;
-  red[3][wv][lane] = sy;
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-    *sv.hdr = hdr;
-    *sv.gen = *sv.gen + 1u;
-  }
-  __syncthreads();
-  if (wv == 0 && j < T) {
-    const int64_t k = (int64_t)blockIdx.y * T + j;
-    double r[4];
-    for (int c = 0; c < 4; ++c) {
-      r[c] = red[c][0][lane];
-      for (int w = 1; w < kRedWaves; ++w) r[c] += red[c][w][lane];
-    }
-    chi[k] = (float)r[0];
-    if (dtau) dtau[k] = (float)((double)lambda * r[1]);
-    if (du) {
-      du[k * 2 + 0] = (float)(-(double)alpha * (double)lambda * r[2]);
-      du[k * 2 + 1] = (float)(-(double)alpha * (double)lambda * r[3]);
-    }
-  }
-}
+};
 
 // grad_X from the saved lists (Eq. 8 contracted with the upstream gradient).  A block takes one
 // unit of the forward sweep.  It clears the part of grad_X the unit owns (its rows x its 248
@@ -650,10 +525,19 @@ bool soft2d_supported(const Shape& s, int T) {
          s.H <= (1 << 30) && s.N < ((int64_t)1 << 31);
 }
 
+// per-unit partial sums (up to four floats per unit and threshold), a multiple of 256 bytes
+static size_t soft2d_partial_bytes(const Shape& s, const Plan2d& pl, int T) {
+  const size_t n = (size_t)s.batch * pl.nstrip * pl.nseg * (size_t)T * 4 * sizeof(float);
+  return (n + 255) / 256 * 256;
+}
+static double* soft2d_mid(void* ws, const Shape& s, const Plan2d& pl, int T) {
+  return reinterpret_cast<double*>(static_cast<char*>(ws) + soft2d_partial_bytes(s, pl, T));
+}
+
 size_t soft2d_workspace_bytes(const Shape& s, int T) {
   if (!soft2d_supported(s, T)) return 0;
   const Plan2d pl = plan2d<float>(s, true);
-  return (size_t)256 + (size_t)s.batch * pl.nstrip * pl.nseg * (size_t)T * 4 * sizeof(float);
+  return (size_t)256 + soft2d_partial_bytes(s, pl, T) + soft_reduce_mid_bytes(s.batch, T);
 }
 
 void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
@@ -668,8 +552,9 @@ void launch_soft2d_fwd(const float* grid, const Shape& s, const float* u, float 
     hipLaunchKernelGGL(soft2d_fwd_kernel<false>, pl.grid, dim3(256), kSoftLds, st, grid, (int)s.H, (int)s.W, s.N,
                        pl.nstrip, pl.nseg, pl.rows_per_seg, u, alpha, tau, T, kneg2d(lambda), partial);
   profile_mark(st, true);
-  hipLaunchKernelGGL(soft2d_fwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                     dim3(kRedWaves * kWave), 0, st, partial, pl.nstrip * pl.nseg, T, chi);
+  const RedOut out = {chi, nullptr, nullptr, nullptr, nullptr, {}};
+  launch_soft_reduce<1, true, -1>(partial, soft2d_mid(ws, s, pl, T), pl.nstrip * pl.nseg, s.batch, T, alpha, lambda,
+                                  Origin2{pl.nstrip, pl.rows_per_seg}, out, st);
 }
 
 void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau,
@@ -688,9 +573,9 @@ void launch_soft2d_bwd(const float* grid, const Shape& s, const float* u, float 
                        grad_X, partial);
   profile_mark(st, true);
   if (partial) {
-    hipLaunchKernelGGL(soft2d_bwd_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                       dim3(kRedWaves * kWave), 0, st, partial, pl.nstrip * pl.nseg, pl.nstrip, pl.rows_per_seg, T, alpha,
-                       lambda, dtau, du);
+    const RedOut out = {nullptr, dtau, du, nullptr, nullptr, {}};
+    launch_soft_reduce<4, false, 2>(partial, soft2d_mid(ws, s, pl, T), pl.nstrip * pl.nseg, s.batch, T, alpha, lambda,
+                                    Origin2{pl.nstrip, pl.rows_per_seg}, out, st);
   }
 }
 
@@ -726,9 +611,9 @@ void launch_soft2d_fwd_save(const float* grid, const Shape& s, const float* u, f
   else       { if (deriv) ECC_GO(false, true); else ECC_GO(false, false); }
 #undef ECC_GO
   profile_mark(st, true);
-  hipLaunchKernelGGL(soft2d_save_reduce_kernel, dim3((unsigned)((T + kWave - 1) / kWave), (unsigned)s.batch),
-                     dim3(kRedWaves * kWave), 0, st, partial, pl.nstrip * pl.nseg, pl.nstrip, pl.rows_per_seg, T, alpha,
-                     lambda, chi, dtau, du, sv, hdr);
+  const RedOut out = {chi, dtau, du, sv.hdr, sv.gen, hdr};
+  launch_soft_reduce<4, true, 2>(partial, soft2d_mid(ws, s, pl, T), pl.nstrip * pl.nseg, s.batch, T, alpha, lambda,
+                                 Origin2{pl.nstrip, pl.rows_per_seg}, out, st);
 }
 
 void launch_soft2d_bwd_saved(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,

@@ -16,6 +16,7 @@
 // in a fixed order in float64, so results are run-to-run identical.
 #include "ecc_sweep3d.h"
 #include "ecc_soft_saved.h"
+#include "ecc_soft_reduce.h"
 
 #include <cstdlib>
 
@@ -433,154 +434,15 @@ __global__ __launch_bounds__(256) void soft3d_bwd_saved_kernel(const float* __re
   saved_lists_to_grad(list, cnt_raw, expect.cap, first, stau, sg, T, kneg, lambda, sat_lo, sat_hi, gx, N, stage, skept);
 }
 
-// Reduction over units, in float64 and in a fixed order (run-to-run identical).  A lone volume has
-// thousands of units, so the sum is split: block (x = group of 64 thresholds, y = item, z = slice)
-// of 16 waves adds the units of its slice -- wave w takes units begin + w, begin + w + 16, ... in
-// order, then wave 0 adds the 16 sums in order -- and, when there is more than one slice, leaves
-// the slice's sums in `mid`, which the final kernel adds in slice order.
-constexpr int kRedWaves = 16, kRedSlices = 64;
-
-// NV = 1: forward (chi);  NV = 4: backward (A0 and the coordinate-weighted sums, relative to each
-// unit's origin on the way in, absolute on the way out);  NV = 5: the saving forward pass (chi, then
-// the four of the backward pass)
-template <int NV>
-struct RedSums {
-  double v[NV];
+// origin of a unit's coordinates, for the reduction of ecc_soft_reduce.h
+struct Origin3 {
+  int D, H, W, nitems, planes_per_seg;
+  __device__ __forceinline__ void operator()(int unit, int (&o)[3]) const {
+    unit_origin3(unit, D, H, W, nitems, planes_per_seg, kRows3d, o[0], o[1], o[2]);
+  }
 };
-
-// where the results go; a null pointer skips that output.  stamp: the saving forward pass's last
-// reduction kernel writes the state's header and raises its generation
-struct RedOut {
-  float* chi;
-  float* dtau;
-  float* du;
-  SoftStateHeader* hdr;  // null: nothing to stamp
-  unsigned* gen;
-  SoftStateHeader stamp;
-};
-
-template <int NV>
-__device__ __forceinline__ void soft3d_finish(const RedSums<NV>& r, int64_t k, float alpha, float lambda,
-                                              const RedOut& o) {
-  constexpr int A = NV == 5 ? 1 : 0;  // where A0 sits
-  if constexpr (NV != 4) o.chi[k] = (float)r.v[0];
-  if constexpr (NV != 1) {
-    // dchi_dtau = lambda sum A0;  dchi_du = -alpha lambda sum (origin * A0 + A_xyz)
-    if (o.dtau) o.dtau[k] = (float)((double)lambda * r.v[A]);
-    if (o.du)
-      for (int c = 0; c < 3; ++c) o.du[k * 3 + c] = (float)(-(double)alpha * (double)lambda * r.v[A + 1 + c]);
-  }
-}
-__device__ __forceinline__ void soft3d_stamp(const RedOut& o) {
-  if (o.hdr && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
-    *o.hdr = o.stamp;
-    *o.gen = *o.gen + 1u;
-  }
-}
-
-template <int NV>
-__global__ __launch_bounds__(kRedWaves * kWave) void soft3d_reduce_kernel(const float* __restrict__ partial, int units,
-                                                                          int per_slice, int D, int H, int W,
-                                                                          int planes_per_seg, int nitems, int T,
-                                                                          float alpha, float lambda,
-                                                                          double* __restrict__ mid, RedOut out) {
-  __shared__ double red[NV][kRedWaves][kWave];
-  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
-  const int j = blockIdx.x * kWave + lane;
-  const int item = blockIdx.y, slice = blockIdx.z;
-  const int begin = slice * per_slice, end = min(units, begin + per_slice);
-  RedSums<NV> s;
-  for (int c = 0; c < NV; ++c) s.v[c] = 0.0;
-  if (j < T) {
-    for (int q = begin + wv; q < end; q += kRedWaves) {
-      if constexpr (NV == 1) {
-        s.v[0] += (double)partial[((int64_t)item * units + q) * T + j];
-      } else {
-        constexpr int A = NV == 5 ? 1 : 0;
-        float e[NV];
-        if constexpr (NV == 4) {
-          const float4 f = reinterpret_cast<const float4*>(partial)[((int64_t)item * units + q) * T + j];
-          e[0] = f.x, e[1] = f.y, e[2] = f.z, e[3] = f.w;
-        } else {
-          const float* p = partial + (((int64_t)item * units + q) * T + j) * NV;
-#pragma unroll
-          for (int c = 0; c < NV; ++c) e[c] = p[c];
-          s.v[0] += (double)e[0];
-        }
-        int ox, oy, oz;
-        unit_origin3(q, D, H, W, nitems, planes_per_seg, kRows3d, ox, oy, oz);
-        const double a0 = (double)e[A];
-        s.v[A] += a0;
-        s.v[A + 1] += (double)ox * a0 + (double)e[A + 1];
-        s.v[A + 2] += (double)oy * a0 + (double)e[A + 2];
-        s.v[A + 3] += (double)oz * a0 + (double)e[A + 3];
-      }
-    }
-  }
-  for (int c = 0; c < NV; ++c) red[c][wv][lane] = s.v[c];
-  if (gridDim.z == 1) soft3d_stamp(out);
-  __syncthreads();
-  if (wv == 0 && j < T) {
-    RedSums<NV> r;
-    for (int c = 0; c < NV; ++c) {
-      r.v[c] = red[c][0][lane];
-      for (int w = 1; w < kRedWaves; ++w) r.v[c] += red[c][w][lane];
-    }
-    if (gridDim.z == 1) {
-      soft3d_finish<NV>(r, (int64_t)item * T + j, alpha, lambda, out);
-    } else {
-      for (int c = 0; c < NV; ++c) mid[(((int64_t)item * gridDim.z + slice) * T + j) * NV + c] = r.v[c];
-    }
-  }
-}
-
-// wave w adds slices w, w + 16, ... in order, wave 0 adds the 16 sums in order
-template <int NV>
-__global__ __launch_bounds__(kRedWaves * kWave) void soft3d_reduce_final_kernel(const double* __restrict__ mid,
-                                                                                int slices, int T, float alpha,
-                                                                                float lambda, RedOut out) {
-  __shared__ double red[NV][kRedWaves][kWave];
-  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
-  const int j = blockIdx.x * kWave + lane, item = blockIdx.y;
-  RedSums<NV> s;
-  for (int c = 0; c < NV; ++c) s.v[c] = 0.0;
-  if (j < T)
-    for (int sl = wv; sl < slices; sl += kRedWaves)
-      for (int c = 0; c < NV; ++c) s.v[c] += mid[(((int64_t)item * slices + sl) * T + j) * NV + c];
-  for (int c = 0; c < NV; ++c) red[c][wv][lane] = s.v[c];
-  soft3d_stamp(out);
-  __syncthreads();
-  if (wv == 0 && j < T) {
-    RedSums<NV> r;
-    for (int c = 0; c < NV; ++c) {
-      r.v[c] = red[c][0][lane];
-      for (int w = 1; w < kRedWaves; ++w) r.v[c] += red[c][w][lane];
-    }
-    soft3d_finish<NV>(r, (int64_t)item * T + j, alpha, lambda, out);
-  }
-}
-
-// slices a reduction over `units` is split into, and units per slice
-static void red_split(int units, int& slices, int& per_slice) {
-  slices = units / (4 * kRedWaves);
-  slices = slices < 1 ? 1 : (slices > kRedSlices ? kRedSlices : slices);
-  per_slice = (units + slices - 1) / slices;
-  slices = (units + per_slice - 1) / per_slice;
-}
-
-template <int NV>
-static void launch_soft3d_reduce(const float* partial, double* mid, const Shape& s, const Plan3d& pl, int T, float alpha,
-                                 float lambda, const RedOut& out, hipStream_t st) {
-  const int units = (int)pl.grid.x * 4;
-  int slices, per;
-  red_split(units, slices, per);
-  const unsigned tg = (unsigned)((T + kWave - 1) / kWave);
-  hipLaunchKernelGGL(soft3d_reduce_kernel<NV>, dim3(tg, (unsigned)s.batch, (unsigned)slices), dim3(kRedWaves * kWave), 0,
-                     st, partial, units, per, (int)s.D, (int)s.H, (int)s.W, pl.planes_per_seg, (int)s.batch, T, alpha,
-                     lambda, mid, out);
-  if (slices > 1)
-    hipLaunchKernelGGL(soft3d_reduce_final_kernel<NV>, dim3(tg, (unsigned)s.batch), dim3(kRedWaves * kWave), 0, st, mid,
-                       slices, T, alpha, lambda, out);
+static Origin3 origin3(const Shape& s, const Plan3d& pl) {
+  return Origin3{(int)s.D, (int)s.H, (int)s.W, (int)s.batch, pl.planes_per_seg};
 }
 
 static float kneg3d(float lambda) { return (float)(-(double)lambda * 1.4426950408889634); }
@@ -598,7 +460,7 @@ static size_t soft3d_partial_bytes(const Shape& s, const Plan3d& pl, int T) {
 size_t soft3d_workspace_bytes(const Shape& s, int T) {
   if (!soft3d_supported(s, T)) return 0;
   const Plan3d pl = plan3d<float>(s);
-  return (size_t)256 + soft3d_partial_bytes(s, pl, T) + (size_t)s.batch * kRedSlices * (size_t)T * 5 * sizeof(double);
+  return (size_t)256 + soft3d_partial_bytes(s, pl, T) + soft_reduce_mid_bytes(s.batch, T);
 }
 
 void launch_soft3d_fwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
@@ -614,7 +476,7 @@ void launch_soft3d_fwd(const float* grid, const Shape& s, const float* u, float 
 #undef ECC_GO
   double* mid = reinterpret_cast<double*>(static_cast<char*>(ws) + soft3d_partial_bytes(s, pl, T));
   const RedOut out = {chi, nullptr, nullptr, nullptr, nullptr, {}};
-  launch_soft3d_reduce<1>(partial, mid, s, pl, T, alpha, lambda, out, st);
+  launch_soft_reduce<1, true, -1>(partial, mid, (int)pl.grid.x * 4, s.batch, T, alpha, lambda, origin3(s, pl), out, st);
 }
 
 void launch_soft3d_bwd(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
@@ -633,7 +495,7 @@ void launch_soft3d_bwd(const float* grid, const Shape& s, const float* u, float 
   if (partial) {
     double* mid = reinterpret_cast<double*>(static_cast<char*>(ws) + soft3d_partial_bytes(s, pl, T));
     const RedOut out = {nullptr, dtau, du, nullptr, nullptr, {}};
-    launch_soft3d_reduce<4>(partial, mid, s, pl, T, alpha, lambda, out, st);
+    launch_soft_reduce<4, false, 3>(partial, mid, (int)pl.grid.x * 4, s.batch, T, alpha, lambda, origin3(s, pl), out, st);
   }
 }
 
@@ -684,7 +546,7 @@ void launch_soft3d_fwd_save(const float* grid, const Shape& s, const float* u, f
   else       { if (deriv) ECC_GO(false, true); else ECC_GO(false, false); }
 #undef ECC_GO
   const RedOut out = {chi, dtau, du, sv.hdr, sv.gen, hdr};
-  launch_soft3d_reduce<5>(partial, mid, s, pl, T, alpha, lambda, out, st);
+  launch_soft_reduce<5, true, 3>(partial, mid, (int)pl.grid.x * 4, s.batch, T, alpha, lambda, origin3(s, pl), out, st);
 }
 
 void launch_soft3d_bwd_saved(const float* grid, const Shape& s, const float* u, float alpha, const float* tau, int T,
