@@ -46,7 +46,7 @@ struct SmallPlan {
 static SmallPlan small_plan(const Shape& s) {
   SmallPlan p;
   const int64_t total = s.N * s.batch;
-  int64_t pt = (total + 65535) / 65536;  // about 256 blocks for the largest inputs
+  int64_t pt = (total + 131071) / 131072;  // up to 512 blocks of 256 or 512 vertices (measured best at 512^2)
   p.per_thread = (int)(pt < 1 ? 1 : (pt > 4 ? 4 : pt));
   p.per_block = kStageBlock * p.per_thread;
   p.per_item = (unsigned)((s.N + p.per_block - 1) / p.per_block);

@@ -1,7 +1,7 @@
 """The flow for small float grids without a range (stage: per-block lists of critical vertices and
 value ranges; finish: range, thresholds, histogram and prefix sum in one block per item, or, for
 items above 2^16 vertices, several blocks per item and the scan as a third launch) at the edges of
-what it takes -- items of 2^16 vertices, 2^18 in the batch, 64 items, 4096 bins, one to four
+what it takes -- items of 2^16 vertices, 2^18 in the batch, 64 items, 4096 bins, one or two
 vertices per thread, lists that are nearly full -- and just beyond them, with the same calls
 repeated with the flow switched off."""
 import numpy as np
@@ -28,9 +28,9 @@ def _both(fn):
     return host(a)
 
 
-# items of 2^16 vertices (one vertex per thread) and just above (three launches), 2 and 3 items (two /
-# three per thread), 2^18 vertices in all (four) and just above (not taken), larger items (three
-# launches, 16 blocks per item), the largest batch and beyond, 3D
+# items of 2^16 vertices and just above (three launches), 2^17 vertices in all (one vertex per thread) and
+# more (two), 2^18 in all and just above (not taken), larger items (three launches, 16 blocks per
+# item), the largest batch and beyond, 3D
 @pytest.mark.parametrize("B,shape", [(1, (256, 256)), (1, (257, 256)), (2, (200, 300)), (3, (256, 255)), (4, (256, 256)),
                                       (5, (230, 230)), (1, (512, 512)), (2, (300, 400)), (1, (500, 524)), (1, (3, 87381)),
                                       (64, (64, 64)), (65, (60, 60)), (64, (1, 1)), (2, (40, 40, 40)),
