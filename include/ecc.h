@@ -81,7 +81,10 @@ const char* ecc_version(void);
 /*
  * Bytes of device workspace sufficient for any entry point called with these
  * dims / batch and with bins (hard) or T (soft) = bins_or_T.  Host-only
- * arithmetic; returns 0 on invalid arguments.
+ * arithmetic; returns 0 on invalid arguments.  For the hard curves this is
+ * about one byte per vertex, except for batches of up to 2^25 vertices, which
+ * get room for every vertex in a list (about 8.5 bytes per vertex: their calls
+ * then need nothing cleared first and no second sweep in reserve).
  */
 size_t ecc_workspace_bytes(int ndim, const int64_t* dims /* host */, int64_t batch,
                            int bins_or_T);
@@ -129,9 +132,11 @@ int ecc_hard(const void* grid, int ndim, const int64_t* dims, int64_t batch, ecc
  * library, ECC_STATIC_SCRATCH_BYTES long, one copy per GPU, held until the
  * process ends.  The call allocates and frees nothing (the array's address on
  * the current device is looked up once, on the first call on that device).
- * A request whose workspace (ecc_workspace_bytes_dtype) would not fit returns
- * ECC_ERR_UNSUPPORTED -- roughly one byte of scratch per float32 vertex, so
- * about 32 M vertices per call, e.g. two 4096^2 images or 256^3 volumes.
+ * A request that would not fit returns ECC_ERR_UNSUPPORTED -- roughly one byte
+ * of scratch per float32 vertex, so about 32 M vertices per call, e.g. two
+ * 4096^2 images or 256^3 volumes (the larger workspace that ecc_workspace_bytes
+ * asks for on behalf of mid-sized batches is used when it fits and done without
+ * when it does not).
  * Every call on a GPU uses that GPU's one array: calls that may overlap in time
  * on one GPU (different streams, different threads) race and must not be made;
  * calls on one stream are ordered and safe.  Nothing needs to be cleared
@@ -334,11 +339,12 @@ int ecc_count_nonfinite(const void* grid, int64_t n, ecc_dtype dtype, unsigned l
  *                         instead of the single pass that lists the critical
  *                         vertices;
  *   ECC_FORCE_SOFT_TILES  soft path: the tile kernels for every shape;
- *   ECC_FORCE_NO_SMALL    hard curves: small float inputs without a range
- *                         (up to 2^18 vertices in up to 64 items, up to 4096
- *                         bins) go through the kernels of the large ones
- *                         instead of the two- / three-launch flow made for
- *                         them (any other bit switches that flow off as well).
+ *   ECC_FORCE_NO_SMALL    hard curves: small and mid-sized float inputs
+ *                         without a range (up to 2^25 vertices in up to 64
+ *                         items, up to 4096 bins) go through the five-launch
+ *                         flow of the large ones instead of the two- /
+ *                         three-launch flows made for them (any other bit
+ *                         switches those flows off as well).
  * 0 restores normal operation.  Returns the previous mask.  The setting is
  * process-wide (one atomic word) and is read when a call is enqueued; results
  * are the same on every path, only the kernels differ.

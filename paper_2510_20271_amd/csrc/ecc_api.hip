@@ -195,7 +195,13 @@ static int hard_common(int conv, const char* who, const void* grid, int ndim, co
     return fail(ECC_ERR_INVALID_ARG, "grid is not aligned to its element size");
   if (reinterpret_cast<uintptr_t>(curve) % 8)
     return fail(ECC_ERR_INVALID_ARG, "curve is not 8-byte aligned");
-  const size_t base_bytes = ecc::hard_workspace_bytes(s, bins);
+  // the static scratch may hold the smaller workspace only: then no list per block of the sweep
+  size_t base_bytes = ecc::hard_workspace_bytes(s, bins);
+  bool roomy = true;
+  if (use_static && base_bytes + convert_bytes(s, dtype) > (size_t)ECC_STATIC_SCRATCH_BYTES) {
+    base_bytes = ecc::hard_workspace_min_bytes(s, bins);
+    roomy = false;
+  }
   if (use_static) {
     const size_t need = base_bytes + convert_bytes(s, dtype);
     if (need > (size_t)ECC_STATIC_SCRATCH_BYTES)
@@ -220,11 +226,11 @@ static int hard_common(int conv, const char* who, const void* grid, int ndim, co
       hi = super ? (double)bins : (double)bins - 1.0;
     }
     return device_status(ecc::launch_hard(grid, s, dtype, bins, have_range, lo, hi, curve, workspace, st, nullptr,
-                                          conv, f32),
+                                          conv, f32, roomy),
                          who);
   }
   return device_status(ecc::launch_hard(grid, s, dtype, bins, range != nullptr, lo, hi, curve, workspace, st,
-                                        nullptr, conv),
+                                        nullptr, conv, nullptr, roomy),
                        who);
 }
 

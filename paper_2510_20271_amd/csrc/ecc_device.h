@@ -464,4 +464,45 @@ struct WaveRange {
   }
 };
 
+// ---- a list per block (ListArgs::heads) -------------------------------------------------------
+// The four waves of a block append to one list through a fill count in LDS; when the sweep is done
+// the block leaves the count and the range of the values it saw in its head.  own: 4 words of LDS.
+__device__ __forceinline__ void block_list_begin(const ListArgs& la, ListSink& sink, unsigned* own) {
+  const unsigned blk = blockIdx.y * gridDim.x + blockIdx.x;
+  if (threadIdx.x == 0) {
+    own[0] = 0u;
+    own[1] = 0xffffffffu;
+    own[2] = 0u;
+    own[3] = 0u;
+  }
+  // the item's histogram, cleared by the item's blocks together
+  for (int b = blockIdx.x * blockDim.x + threadIdx.x; b < la.bins; b += gridDim.x * blockDim.x)
+    la.zero_hist[(int64_t)blockIdx.y * la.bins + b] = 0ull;
+  __syncthreads();
+  sink.list = la.lists + (size_t)blk * la.cap;
+  sink.counter = &own[0];
+  sink.overflow = &own[3];
+}
+__device__ __forceinline__ void block_list_end(const ListArgs& la, WaveRange& range, unsigned* own) {
+  float lo = range.lo, hi = range.hi;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    lo = fminf(lo, __shfl_xor(lo, o));
+    hi = fmaxf(hi, __shfl_xor(hi, o));
+  }
+  if ((threadIdx.x & (kWave - 1)) == 0 && lo <= hi) {
+    atomicMin(&own[1], float_key(lo));
+    atomicMax(&own[2], float_key(hi));
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    ListHead h;
+    h.count = own[0];
+    h.min_key = own[1];
+    h.max_key = own[2];
+    h.pad = own[3];
+    la.heads[blockIdx.y * gridDim.x + blockIdx.x] = h;
+  }
+}
+
 }  // namespace ecc

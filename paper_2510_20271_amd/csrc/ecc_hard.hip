@@ -384,10 +384,18 @@ static unsigned list_cap(const Shape& s) {  // entries per sub-list
   return (unsigned)cap;
 }
 static size_t counter_bytes(const Shape& s) { return (((size_t)s.batch * list_nsub(s) * 4 + 255) / 256) * 256; }
-size_t hard_workspace_bytes(const Shape& s, int bins) {
+size_t hard_workspace_min_bytes(const Shape& s, int bins) {
   const size_t lists = counter_bytes(s) + (size_t)s.batch * list_nsub(s) * list_cap(s) * sizeof(float2);
   const size_t small = small_supported(s, bins) ? small_workspace_bytes(s) : 0;
   return kTableOffset + table_bytes(bins) + std::max(lists, small);
+}
+// with room for a list per block of the sweep (mid-sized float grids; the launch plans of the
+// four-byte and the two-byte types differ)
+size_t hard_workspace_bytes(const Shape& s, int bins) {
+  size_t mid = 0;
+  for (int dtype : {2, 3})
+    if (mid_supported(s, bins, dtype)) mid = std::max(mid, kTableOffset + table_bytes(bins) + mid_workspace_bytes(s, dtype));
+  return std::max(hard_workspace_min_bytes(s, bins), mid);
 }
 
 static int blocks_for(int64_t N) {
@@ -420,7 +428,7 @@ static void launch_sweep_generic(const void* grid, const Shape& s, bool levels, 
 
 hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
                        double lo, double hi, int64_t* curve, void* ws, hipStream_t st, const DirArgs* dir,
-                       int conv, float* f32_scratch) {
+                       int conv, float* f32_scratch, bool roomy) {
   const int super = (conv & kConvSuper) ? 1 : 0;
   HardHeader* hdr = static_cast<HardHeader*>(ws);
   char* wsb = static_cast<char*>(ws);
@@ -451,6 +459,9 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     return launch_hard_small(static_cast<const float*>(grid), s, bins, curve, hdr, table,
                              wsb + kTableOffset + table_bytes(bins), st, conv);
   }
+  // Mid-sized float grids without a range: the sweep with a list per block, three launches.
+  if (device_range && !dir && roomy && forced_paths() == 0u && (fast2d || fast3d) && mid_supported(s, bins, dtype))
+    return launch_hard_mid(grid, s, dtype, bins, curve, hdr, table, wsb + kTableOffset + table_bytes(bins), st, conv);
   // Element types beyond uint8 / uint16 / float32.  The strip / tube sweeps load float16, bfloat16
   // and int16 as they are (all three widen to float32 exactly); the other kernels, and int32 /
   // float64 everywhere, get a float32 copy rounded to nearest even.
@@ -472,7 +483,7 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
     // range together; the few critical vertices are binned afterwards.  If a list
     // overflows (more than one vertex in eight critical), the histogram-mode sweep
     // that follows runs instead (it is a no-op otherwise).
-    ListArgs la;
+    ListArgs la = {};  // (heads = null: shared sub-lists)
     la.hdr = hdr;
     la.counters = reinterpret_cast<unsigned*>(wsb + kTableOffset + table_bytes(bins));
     la.lists = reinterpret_cast<float2*>(wsb + kTableOffset + table_bytes(bins) + counter_bytes(s));

@@ -22,9 +22,11 @@ constexpr int kConvTop = 1, kConvSuper = 2;
 size_t hard_workspace_bytes(const Shape& s, int bins);
 struct DirArgs;  // directional launch (tilted field, blockIdx.y over directions x items); null: plain
 // dtype: any ecc_dtype code; f32_scratch: room for a float32 copy of the grid (codes 3..7 only)
+// roomy: ws holds hard_workspace_bytes(); otherwise hard_workspace_min_bytes() (no list per block)
+size_t hard_workspace_min_bytes(const Shape& s, int bins);
 hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bool have_range,
                        double lo, double hi, int64_t* curve, void* ws, hipStream_t st,
-                       const DirArgs* dir = nullptr, int conv = 0, float* f32_scratch = nullptr);
+                       const DirArgs* dir = nullptr, int conv = 0, float* f32_scratch = nullptr, bool roomy = true);
 // directional curves; sv: the shape with batch = directions x items, batch: items per direction
 size_t hard_dir_workspace_bytes(const Shape& sv, int bins);
 hipError_t launch_hard_dir(const float* grid, const Shape& sv, const float* u, float alpha, int batch,
@@ -50,15 +52,35 @@ struct HardHeader;
 bool small_supported(const Shape& s, int bins);
 size_t small_workspace_bytes(const Shape& s);
 void launch_scan(int64_t* curve, const Shape& s, int bins, int suffix, hipStream_t st);  // in-place prefix / suffix sums
+// Mid-sized float grids without a range: the strip / tube sweep with a list per block, then the
+// finishing kernel of the small flow and the scan (three launches, nothing cleared beforehand).
+// `room`: mid_workspace_bytes() bytes behind the threshold table.
+bool mid_supported(const Shape& s, int bins, int dtype);
+size_t mid_workspace_bytes(const Shape& s, int dtype);
+hipError_t launch_hard_mid(const void* grid, const Shape& s, int dtype, int bins, int64_t* curve, HardHeader* hdr,
+                           float* table, void* room, hipStream_t st, int conv);
 hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_t* curve, HardHeader* hdr, float* table,
                              void* small, hipStream_t st, int conv);
 // single-pass mode: per-item lists of critical vertices (value, c) in the workspace
+// what a block that keeps a list of its own leaves behind (nothing has to be cleared for it)
+struct ListHead {
+  unsigned count;             // critical vertices the block found
+  unsigned min_key, max_key;  // float_key of the least / greatest value the block saw
+  unsigned pad;
+};
 struct ListArgs {
   float2* lists;       // [batch][nsub][cap]
   unsigned* counters;  // [batch][nsub]
   unsigned cap;        // entries per sub-list
   unsigned nsub;       // sub-lists per item, a power of two
   HardHeader* hdr;
+  // Lists per block (heads != null): block (x, y) of the sweep appends to lists[(y gridDim.x + x) cap ..],
+  // which has room for every vertex the block owns, and leaves its count and value range in
+  // heads[y gridDim.x + x]; counters, nsub and hdr are unused.  The item's blocks also clear its
+  // histogram zero_hist[y bins ..].
+  ListHead* heads;
+  unsigned long long* zero_hist;
+  int bins;
 };
 bool sweep2d_supported(const Shape& s, int bins);
 void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
@@ -67,6 +89,7 @@ void launch_sweep2d(const void* grid, const Shape& s, int dtype, bool levels, in
 void launch_sweep2d_list(const void* grid, int dtype, const Shape& s, const ListArgs& la, hipStream_t st,
                          const DirArgs* dir = nullptr, int conv = 0);
 unsigned sweep2d_list_blocks(const Shape& s, int dtype);  // blocks per item of that launch
+unsigned sweep2d_block_vertices(const Shape& s, int dtype);  // most vertices a block of that launch owns
 
 bool sweep3d_supported(const Shape& s, int bins);
 void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, int bins,
@@ -75,6 +98,7 @@ void launch_sweep3d(const void* grid, const Shape& s, int dtype, bool levels, in
 void launch_sweep3d_list(const void* grid, int dtype, const Shape& s, const ListArgs& la, hipStream_t st,
                          const DirArgs* dir = nullptr, int conv = 0);
 unsigned sweep3d_list_blocks(const Shape& s);
+unsigned sweep3d_block_vertices(const Shape& s);
 
 // ---- sweep-kernel timing (measurement aid) ----------------------------------
 hipError_t profile_begin(int max_launches);

@@ -29,11 +29,7 @@ constexpr unsigned kSmallShares = 16;              // finishing blocks per large
 constexpr int64_t kSmallBatch = 64;                // every finish block reads every stage block's header
 constexpr int kSmallBins = 4096;
 
-struct SmallHead {
-  unsigned count;             // critical vertices the block found
-  unsigned min_key, max_key;  // float_key of the block's least / greatest value
-  unsigned pad;
-};
+typedef ListHead SmallHead;
 
 struct SmallPlan {
   int per_thread;       // vertices per thread of a stage block
@@ -310,6 +306,75 @@ hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_
                        reinterpret_cast<long long*>(curve));
     launch_scan(curve, s, bins, super, st);
   }
+  return hipGetLastError();
+}
+
+// ---- mid-sized grids: the strip / tube sweep with a list per block ----------------------------
+// The five-launch flow clears counters first and keeps a gated second sweep in case a shared list
+// overflows.  Here every block of the sweep has a list with room for all of its vertices and a
+// head of its own, so nothing is cleared and nothing can overflow; the finishing kernel above (a
+// share of the lists per block) and the scan follow.  The price is workspace: 8 bytes per vertex.
+constexpr int64_t kMidTotal = (int64_t)1 << 25;  // vertices in the whole batch (8192^2 measured no faster this way)
+constexpr unsigned kMidBlocks = 8192;            // sweep blocks in all (every finishing block reads every head)
+
+static bool mid_plan(const Shape& s, int dtype, unsigned& per_item, unsigned& cap) {
+  if (s.ndim == 2 && sweep2d_supported(s, 1)) {
+    per_item = sweep2d_list_blocks(s, dtype);
+    cap = sweep2d_block_vertices(s, dtype);
+  } else if (sweep3d_supported(s, 1)) {
+    if (dtype != 2) return false;  // (the tube sweep's list kernels take float32 here)
+    per_item = sweep3d_list_blocks(s);
+    cap = sweep3d_block_vertices(s);
+  } else {
+    return false;
+  }
+  cap = (cap + 63u) / 64u * 64u;
+  return true;
+}
+
+// dtype: float32, float16 or bfloat16 (the types whose range is found on the device)
+bool mid_supported(const Shape& s, int bins, int dtype) {
+  if (!(dtype == 2 || dtype == 3 || dtype == 6) || bins > kSmallBins || s.N * s.batch > kMidTotal || s.batch > kSmallBatch)
+    return false;
+  unsigned per_item, cap;
+  if (!mid_plan(s, dtype, per_item, cap)) return false;
+  return (int64_t)per_item * s.batch <= kMidBlocks && per_item <= 64u * kFinishBlock;
+}
+
+size_t mid_workspace_bytes(const Shape& s, int dtype) {
+  unsigned per_item, cap;
+  if (!mid_plan(s, dtype, per_item, cap)) return 0;
+  const size_t blocks = (size_t)per_item * s.batch;
+  return (blocks * sizeof(ListHead) + 255) / 256 * 256 + blocks * cap * sizeof(float2);
+}
+
+hipError_t launch_hard_mid(const void* grid, const Shape& s, int dtype, int bins, int64_t* curve, HardHeader* hdr,
+                           float* table, void* room, hipStream_t st, int conv) {
+  unsigned per_item, cap;
+  mid_plan(s, dtype, per_item, cap);
+  const unsigned blocks = per_item * (unsigned)s.batch;
+  ListArgs la;
+  la.heads = static_cast<ListHead*>(room);
+  la.lists = reinterpret_cast<float2*>(static_cast<char*>(room) + ((size_t)blocks * sizeof(ListHead) + 255) / 256 * 256);
+  la.cap = cap;
+  la.counters = nullptr;
+  la.nsub = 1;
+  la.hdr = hdr;
+  la.zero_hist = reinterpret_cast<unsigned long long*>(curve);
+  la.bins = bins;
+  profile_mark(st, false);
+  if (s.ndim == 2) launch_sweep2d_list(grid, dtype, s, la, st, nullptr, conv);
+  else launch_sweep3d_list(grid, dtype, s, la, st, nullptr, conv);
+  profile_mark(st, true);
+  // finishing blocks per item: a share of at most 1024 lists each, 16 to 64 of them
+  unsigned shares = (per_item + 7u) / 8u;
+  shares = shares < 16u ? 16u : (shares > 128u ? 128u : shares);
+  const int super = (conv & kConvSuper) ? 1 : 0;
+  hipLaunchKernelGGL(small_finish_kernel<false>, dim3(shares, (unsigned)s.batch), dim3(kFinishBlock),
+                     (size_t)bins * (sizeof(int) + sizeof(float)), st, la.heads,
+                     reinterpret_cast<const uint2*>(la.lists), per_item, blocks, (int)cap, bins, super, hdr, table,
+                     reinterpret_cast<long long*>(curve));
+  launch_scan(curve, s, bins, super, st);
   return hipGetLastError();
 }
 

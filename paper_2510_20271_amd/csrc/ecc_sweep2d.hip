@@ -68,11 +68,16 @@ __global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__
   WaveQueue<ListSink> queue;
   queue.buf = qbuf;
   queue.count = 0;
-  const unsigned sub = blockIdx.y * la.nsub + (blockIdx.x & (la.nsub - 1u));
-  queue.sink.list = la.lists + (size_t)sub * la.cap;
-  queue.sink.counter = la.counters + sub;
+  __shared__ unsigned own[4];  // list per block: fill count, least / greatest key, overflow (never raised)
+  if (la.heads) {              // (block-uniform)
+    block_list_begin(la, queue.sink, own);
+  } else {
+    const unsigned sub = blockIdx.y * la.nsub + (blockIdx.x & (la.nsub - 1u));
+    queue.sink.list = la.lists + (size_t)sub * la.cap;
+    queue.sink.counter = la.counters + sub;
+    queue.sink.overflow = &la.hdr->overflow;
+  }
   queue.sink.cap = la.cap;
-  queue.sink.overflow = &la.hdr->overflow;
   WaveRange range;
   if constexpr (MODE == kTilted) {
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
@@ -82,7 +87,8 @@ __global__ __launch_bounds__(256) void sweep2d_list_kernel(const T* __restrict__
     sweep2d_wave<T>(grid + (int64_t)blockIdx.y * N, H, W, N, nstrip, nseg, rows_per_seg, queue, ring, range,
                     typename ModeTransform<MODE>::type());
   }
-  range.commit(la.hdr);
+  if (la.heads) block_list_end(la, range, own);
+  else range.commit(la.hdr);
 }
 
 constexpr size_t kRingBytes2d = ring_bytes2d<float2>();
@@ -158,6 +164,11 @@ void launch_sweep2d_list(const void* grid, int dtype, const Shape& s, const List
     case 6: launch2d_list_t<Bf16>(grid, s, la, st, nullptr, conv); break;
     default: launch2d_list_t<float>(grid, s, la, st, dir, conv); break;
   }
+}
+
+unsigned sweep2d_block_vertices(const Shape& s, int dtype) {
+  const Plan2d pl = dtype == 2 ? plan2d<float>(s) : plan2d<F16>(s);
+  return 4u * (unsigned)kStripOut * (unsigned)pl.rows_per_seg;  // four wave units of 248 columns x the segment's rows
 }
 
 unsigned sweep2d_list_blocks(const Shape& s, int dtype) {

@@ -63,11 +63,16 @@ __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__
   queue.buf = qbuf;
   queue.tbuf = reinterpret_cast<float*>(smem + kXchInts + 4 * kQueueCap * 2) + (threadIdx.x >> 6) * kQueueCap;
   queue.count = 0;
-  const unsigned sub = blockIdx.y * la.nsub + (blockIdx.x & (la.nsub - 1u));
-  queue.sink.list = la.lists + (size_t)sub * la.cap;
-  queue.sink.counter = la.counters + sub;
+  __shared__ unsigned own[4];  // list per block: fill count, least / greatest key, overflow (never raised)
+  if (la.heads) {              // (block-uniform)
+    block_list_begin(la, queue.sink, own);
+  } else {
+    const unsigned sub = blockIdx.y * la.nsub + (blockIdx.x & (la.nsub - 1u));
+    queue.sink.list = la.lists + (size_t)sub * la.cap;
+    queue.sink.counter = la.counters + sub;
+    queue.sink.overflow = &la.hdr->overflow;
+  }
   queue.sink.cap = la.cap;
-  queue.sink.overflow = &la.hdr->overflow;
   WaveRange range;
   if constexpr (MODE == kTilted) {
     const int d = blockIdx.y / dir.batch, item = blockIdx.y - d * dir.batch;
@@ -77,7 +82,8 @@ __global__ __launch_bounds__(256) void sweep3d_list_kernel(const T* __restrict__
     sweep3d_wave<T, R>(grid + (int64_t)blockIdx.y * N, D, H, W, N, nstrip, ngroup, nseg, planes_per_seg,
                        queue, xch, range, typename ModeTransform<MODE>::type());
   }
-  range.commit(la.hdr);
+  if (la.heads) block_list_end(la, range, own);
+  else range.commit(la.hdr);
 }
 
 // LV: the type also comes with one bin per level (uint8 / uint16 grids without a range)
@@ -156,6 +162,10 @@ void launch_sweep3d_list(const void* grid, int dtype, const Shape& s, const List
 }
 
 unsigned sweep3d_list_blocks(const Shape& s) { return plan3d<float>(s).grid.x; }
+unsigned sweep3d_block_vertices(const Shape& s) {
+  // four wave units of at most 62 columns x 4 rows (a folded unit: several row groups of fewer columns) x the segment's planes
+  return 4u * (unsigned)s3::kOut * (unsigned)kRows3d * (unsigned)plan3d<float>(s).planes_per_seg;
+}
 
 bool sweep3d_supported(const Shape& s, int bins) {
   // 32-bit element offsets inside a chunk of up to 31 planes (and so one plane stays far

@@ -19,8 +19,8 @@ def golden_dir():
 
 @pytest.fixture(params=["default flow", "large-input kernels"])
 def flow(request):
-    """Hard curves of small float grids without a range (up to 2^18 vertices in up to 64 items, up
-    to 4096 bins) take a two- or three-launch flow of their own.  A test that asks for this fixture runs twice: as a caller gets
+    """Hard curves of small and mid-sized float grids without a range (up to 2^25 vertices in up to
+    64 items, up to 4096 bins) take two- or three-launch flows of their own.  A test that asks for this fixture runs twice: as a caller gets
     it, and with that flow switched off, so that the strip / tube sweeps, the lists and the generic
     kernels still meet the same small and ragged shapes."""
     from paper_2510_20271_amd import api

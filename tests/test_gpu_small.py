@@ -87,3 +87,52 @@ def test_small_flow_static_scratch_and_workspace_reuse():
     ws = torch.full((api.ecc_workspace_bytes((128, 128), 2, 64),), 0xff, dtype=torch.uint8, device="cuda")  # garbage
     for _ in range(3):
         np.testing.assert_array_equal(host(api.ecc_hard(dev(X), 2, 64, workspace=ws)), want)
+
+
+# ---- mid-sized grids: the strip / tube sweep with a list per block, the same finishing kernel --------
+
+
+@pytest.mark.parametrize("B,shape", [(1, (1024, 1024)), (3, (700, 1300)), (64, (100, 650)), (65, (100, 650)),
+                                      (1, (4096, 8192)), (1, (4096, 8200)), (1, (128, 128, 128)), (2, (60, 200, 300)),
+                                      (1, (9, 1000, 1000))])
+def test_mid_flow_sizes(B, shape):
+    nd = len(shape)
+    X = np.stack([synth.grf(shape, 2.0, 70 + i) if np.prod(shape) < (1 << 24) else
+                  np.tile(synth.grf(tuple(n // 2 for n in shape), 2.0, 70 + i), (2,) * nd) for i in range(min(B, 3))])
+    X = X[np.arange(B) % X.shape[0]] + (np.arange(B, dtype=np.float32) * 0.01).reshape((B,) + (1,) * nd)
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    got = _both(lambda: api.ecc_hard(dev(X), nd, 300))
+    np.testing.assert_array_equal(got, OC.ecc_hard_batch(X, O.thresholds_equal_width(X.min(), X.max(), 300)))
+    assert np.all(got[:, -1] == 1)
+
+
+@pytest.mark.parametrize("shape", [(1500, 1500), (100, 120, 250)])
+def test_mid_flow_white_noise_fills_the_lists(shape):
+    # 60 % of the vertices are critical: far beyond the room of the shared lists of the large-input flow
+    X = np.random.default_rng(9).standard_normal((2,) + shape).astype(np.float32)
+    for kw in ({}, {"top": True}, {"superlevel": True}):
+        got = _both(lambda: api.ecc_hard(dev(X), len(shape), 129, **kw))
+        lo, hi = float(X.min()), float(X.max())
+        if kw.get("superlevel"):
+            want = O.ecc_super_batch(X, O.thresholds_lower(O.thresholds_equal_width(lo, hi, 129), lo), False)
+        elif kw.get("top"):
+            want = np.stack([O.ecc_top(x, O.thresholds_equal_width(lo, hi, 129)) for x in X])
+        else:
+            want = OC.ecc_hard_batch(X, O.thresholds_equal_width(lo, hi, 129))
+        np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("bins", [1, 4096, 4097])
+def test_mid_flow_bins_half_precision_and_static_scratch(bins):
+    X = np.stack([synth.grf((900, 1100), 2.0, 80 + i) for i in range(2)])
+    H = X.astype(np.float16)
+    want = OC.ecc_hard_batch(H.astype(np.float32), O.thresholds_equal_width(float(H.min()), float(H.max()), bins))
+    got = _both(lambda: api.ecc_hard(dev(H), 2, bins))
+    np.testing.assert_array_equal(got, want)
+    want = OC.ecc_hard_batch(X, O.thresholds_equal_width(X.min(), X.max(), bins))
+    np.testing.assert_array_equal(host(api.ecc_hard_static(dev(X), 2, bins)), want)
+    # a batch whose lists per block do not fit the static scratch goes through the shared lists there
+    Y = np.stack([synth.grf((1500, 2000), 2.0, 90 + i) for i in range(2)])
+    assert api.ecc_workspace_bytes((1500, 2000), 2, bins) > 32 << 20
+    np.testing.assert_array_equal(host(api.ecc_hard_static(dev(Y), 2, bins)),
+                                  OC.ecc_hard_batch(Y, O.thresholds_equal_width(Y.min(), Y.max(), bins)))

@@ -71,7 +71,7 @@ def test_super_smooth_fields(top, flow):
             O.ecc_super_batch(V, t, top))
 
 
-def test_super_overflowing_lists_fall_back():
+def test_super_overflowing_lists_fall_back(flow):
     # i.i.d. float grids: most vertices are critical, the single-pass lists overflow
     rng = np.random.default_rng(41)
     for shape in ((300, 700), (30, 64, 130)):

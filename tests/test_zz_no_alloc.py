@@ -26,7 +26,7 @@ def test_static_scratch_two_calls_in_a_row():
         np.testing.assert_array_equal(host(api.ecc_hard_static(tiny, 2, bins)), host(api.ecc_hard(tiny, 2, bins)))
         np.testing.assert_array_equal(host(api.ecc_hard_static(small, 3, bins, range=(-0.2, 0.3))),
                                       host(api.ecc_hard(small, 3, bins, range=(-0.2, 0.3))))
-    # rough field: the lists overflow and the histogram-mode sweep redoes the work, all inside the scratch
+    # rough field: most vertices are critical (long lists), all inside the scratch
     rough = dev(np.random.default_rng(2).standard_normal((2, 300, 1000)).astype(np.float32))
     np.testing.assert_array_equal(host(api.ecc_hard_static(rough, 2, bins)), host(api.ecc_hard(rough, 2, bins)))
     # a converted element type (float16 -> float32 copy inside the scratch)
