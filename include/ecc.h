@@ -82,9 +82,10 @@ const char* ecc_version(void);
  * Bytes of device workspace sufficient for any entry point called with these
  * dims / batch and with bins (hard) or T (soft) = bins_or_T.  Host-only
  * arithmetic; returns 0 on invalid arguments.  For the hard curves this is
- * about one byte per vertex, except for batches of up to 2^25 vertices, which
- * get room for every vertex in a list (about 8.5 bytes per vertex: their calls
- * then need nothing cleared first and no second sweep in reserve).
+ * about one byte per vertex, except for batches of up to 2^27 vertices (2^25
+ * in volumes), which get room for every vertex in a list (about 8.5 bytes per
+ * vertex: their calls then need nothing cleared first and no second sweep in
+ * reserve).
  */
 size_t ecc_workspace_bytes(int ndim, const int64_t* dims /* host */, int64_t batch,
                            int bins_or_T);
@@ -340,8 +341,8 @@ int ecc_count_nonfinite(const void* grid, int64_t n, ecc_dtype dtype, unsigned l
  *                         vertices;
  *   ECC_FORCE_SOFT_TILES  soft path: the tile kernels for every shape;
  *   ECC_FORCE_NO_SMALL    hard curves: small and mid-sized float inputs
- *                         without a range (up to 2^25 vertices in up to 64
- *                         items, up to 4096 bins) go through the five-launch
+ *                         without a range (up to 2^27 vertices, 2^25 in
+ *                         volumes, up to 4096 bins) go through the five-launch
  *                         flow of the large ones instead of the two- /
  *                         three-launch flows made for them (any other bit
  *                         switches those flows off as well).

@@ -314,8 +314,13 @@ hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_
 // overflows.  Here every block of the sweep has a list with room for all of its vertices and a
 // head of its own, so nothing is cleared and nothing can overflow; the finishing kernel above (a
 // share of the lists per block) and the scan follow.  The price is workspace: 8 bytes per vertex.
-constexpr int64_t kMidTotal = (int64_t)1 << 25;  // vertices in the whole batch (8192^2 measured no faster this way)
-constexpr unsigned kMidBlocks = 8192;            // sweep blocks in all (every finishing block reads every head)
+// Measured against the five launches (1024 bins, smoothed fields): 32 x 512^2 54 -> 35 us, 16 x 1024^2
+// 74 -> 52 us, 8 x 4096^2 199 -> 182 us, 2 x 8192^2 196 -> 174 us, but 16 x 4096^2 314 -> 322 us; volumes
+// 2 x 256^3 82 -> 73 us, 4 x 256^3 118 -> 121 us, 512^3 205 -> 216 us (the lists of the blocks lie far
+// apart in a workspace of 8 bytes per vertex): hence the limits.
+constexpr int64_t kMidTotal2d = (int64_t)1 << 27, kMidTotal3d = (int64_t)1 << 25;  // vertices in the whole batch
+constexpr int64_t kMidBatch = 4096;
+constexpr unsigned kMidBlocks = 9216;            // sweep blocks in all (every finishing block reads every head)
 
 static bool mid_plan(const Shape& s, int dtype, unsigned& per_item, unsigned& cap) {
   if (s.ndim == 2 && sweep2d_supported(s, 1)) {
@@ -334,7 +339,7 @@ static bool mid_plan(const Shape& s, int dtype, unsigned& per_item, unsigned& ca
 
 // dtype: float32, float16 or bfloat16 (the types whose range is found on the device)
 bool mid_supported(const Shape& s, int bins, int dtype) {
-  if (!(dtype == 2 || dtype == 3 || dtype == 6) || bins > kSmallBins || s.N * s.batch > kMidTotal || s.batch > kSmallBatch)
+  if (!(dtype == 2 || dtype == 3 || dtype == 6) || bins > kSmallBins || s.N * s.batch > (s.ndim == 2 ? kMidTotal2d : kMidTotal3d) || s.batch > kMidBatch)
     return false;
   unsigned per_item, cap;
   if (!mid_plan(s, dtype, per_item, cap)) return false;
@@ -366,9 +371,10 @@ hipError_t launch_hard_mid(const void* grid, const Shape& s, int dtype, int bins
   if (s.ndim == 2) launch_sweep2d_list(grid, dtype, s, la, st, nullptr, conv);
   else launch_sweep3d_list(grid, dtype, s, la, st, nullptr, conv);
   profile_mark(st, true);
-  // finishing blocks per item: a share of at most 1024 lists each, 16 to 64 of them
+  // finishing blocks per item: about 8 lists each (1024 at most), up to 128 blocks; a lone item gets 16 at least
   unsigned shares = (per_item + 7u) / 8u;
-  shares = shares < 16u ? 16u : (shares > 128u ? 128u : shares);
+  const unsigned least = s.batch >= 16 ? 1u : 16u / (unsigned)s.batch;
+  shares = shares < least ? least : (shares > 128u ? 128u : shares);
   const int super = (conv & kConvSuper) ? 1 : 0;
   hipLaunchKernelGGL(small_finish_kernel<false>, dim3(shares, (unsigned)s.batch), dim3(kFinishBlock),
                      (size_t)bins * (sizeof(int) + sizeof(float)), st, la.heads,

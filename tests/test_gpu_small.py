@@ -93,8 +93,9 @@ def test_small_flow_static_scratch_and_workspace_reuse():
 
 
 @pytest.mark.parametrize("B,shape", [(1, (1024, 1024)), (3, (700, 1300)), (64, (100, 650)), (65, (100, 650)),
-                                      (1, (4096, 8192)), (1, (4096, 8200)), (1, (128, 128, 128)), (2, (60, 200, 300)),
-                                      (1, (9, 1000, 1000))])
+                                      (4096, (8, 16)), (4097, (8, 16)), (1, (4096, 8192)), (1, (4096, 8200)),
+                                      (1, (128, 128, 128)), (2, (60, 200, 300)), (1, (9, 1000, 1000)),
+                                      (1, (256, 256, 512)), (1, (256, 256, 520))])
 def test_mid_flow_sizes(B, shape):
     nd = len(shape)
     X = np.stack([synth.grf(shape, 2.0, 70 + i) if np.prod(shape) < (1 << 24) else
