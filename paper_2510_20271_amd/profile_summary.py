@@ -39,6 +39,9 @@ WORKLOADS = {
            [("c5_fwd", "soft2d_fwd_kernel", 32 * 512 * 512, 248), ("c5_bwd", "soft2d_bwd_kernel", 32 * 512 * 512, 248),
             ("c5_fwd_save", "soft2d_fwd_save_kernel", 32 * 512 * 512, 248),
             ("c5_bwd_saved", "soft2d_bwd_saved_kernel", 32 * 512 * 512, 248)]),
+    # kernel trace only: the launches behind every row of the size table
+    "sizes": ("hard ECC, the grid sizes of the paper's Tables 1-2 (one float32 field per size, 1024 bins, range found on "
+              "the device): two launches up to 256^2, three up to 8192^2 / 256^3, five beyond", "hard_sizes.md", []),
 }
 
 
@@ -48,6 +51,8 @@ def commands(out):
         base = f"-- python3 bench.py --only {wl}"
         if wl != "calib":
             rows.append(f"rocprofv3 --kernel-trace --stats --output-format csv -d {out}/{wl}_trace -o {wl} {base} --steps 20")
+            if not WORKLOADS[wl][2]:
+                continue
             rows.append(f"rocprofv3 --pmc {SQ} --output-format csv -d {out}/{wl}_sq -o {wl} {base} --steps 3 --warmup 1")
         rows.append(f"rocprofv3 --pmc FETCH_SIZE --output-format csv -d {out}/{wl}_fetch -o {wl} {base} --steps 3 --warmup 1")
         rows.append(f"rocprofv3 --pmc WRITE_SIZE --output-format csv -d {out}/{wl}_write -o {wl} {base} --steps 3 --warmup 1")
@@ -123,8 +128,10 @@ def main():
         for c in cmds:
             if f"--only {wl} " in c:
                 s += f"- `{c}`\n"
-        s += f"- calibration of the size counters: the FETCH_SIZE / WRITE_SIZE commands with `--only calib` (a plain 1 GiB "
-        s += f"device copy): scale factors {sf:.3f} (fetch) and {sw:.3f} (write).\n\n"
+        if kernels:
+            s += f"- calibration of the size counters: the FETCH_SIZE / WRITE_SIZE commands with `--only calib` (a plain 1 GiB "
+            s += f"device copy): scale factors {sf:.3f} (fetch) and {sw:.3f} (write).\n"
+        s += "\n"
         if stats:
             s += "Kernel durations (kernel trace):\n\n| kernel | calls | avg us | min us | max us | % |\n|---|---|---|---|---|---|\n"
             for n, c, a, mi, ma, p in stats:
