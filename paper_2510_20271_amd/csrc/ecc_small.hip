@@ -127,6 +127,38 @@ __global__ __launch_bounds__(kStageBlock) void small_stage_kernel(const float* _
   }
 }
 
+// The batch's range from all the heads, for launches with so many heads that every finishing
+// block reading all of them would cost more than this extra launch.
+__global__ __launch_bounds__(kFinishBlock) void small_range_kernel(const SmallHead* __restrict__ heads, unsigned blocks,
+                                                                   HardHeader* __restrict__ hdr) {
+  __shared__ unsigned s_min, s_max;
+  if (threadIdx.x == 0) {
+    s_min = 0xffffffffu;
+    s_max = 0u;
+  }
+  __syncthreads();
+  unsigned kmin = 0xffffffffu, kmax = 0u;
+  for (unsigned b = threadIdx.x; b < blocks; b += kFinishBlock) {
+    const SmallHead h = heads[b];
+    kmin = min(kmin, h.min_key);
+    kmax = max(kmax, h.max_key);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    kmin = min(kmin, (unsigned)__shfl_xor((int)kmin, o));
+    kmax = max(kmax, (unsigned)__shfl_xor((int)kmax, o));
+  }
+  if ((threadIdx.x & (kWave - 1)) == 0 && kmin <= kmax) {
+    atomicMin(&s_min, kmin);
+    atomicMax(&s_max, kmax);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    hdr->min_key = s_min;
+    hdr->max_key = s_max;
+  }
+}
+
 // ALONE: one block per item, which also scans and writes the curve.  Otherwise block (x, item) takes
 // the x-th share of the item's lists and adds its histogram to the global one (`curve`, cleared
 // by the stage kernel); the scan is a launch of its own.
@@ -152,10 +184,10 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
   // length of this block's list number tid (requested before anything waits on memory)
   const unsigned n_mine = tid < (int)nl ? min(heads[item * per_item + l0 + tid].count, (unsigned)per_block) : 0u;
   const bool first = item == 0 && (ALONE || blockIdx.x == 0);
-  // the batch's range: every stage block's header
+  // the batch's range: every stage block's header (blocks = 0: small_range_kernel has left it in hdr)
   if (tid == 0) {
-    s_min = 0xffffffffu;
-    s_max = 0u;
+    s_min = blocks ? 0xffffffffu : hdr->min_key;
+    s_max = blocks ? 0u : hdr->max_key;
   }
   __syncthreads();
   {
@@ -315,12 +347,15 @@ hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_
 // head of its own, so nothing is cleared and nothing can overflow; the finishing kernel above (a
 // share of the lists per block) and the scan follow.  The price is workspace: 8 bytes per vertex.
 // Measured against the five launches (1024 bins, smoothed fields): 32 x 512^2 54 -> 35 us, 16 x 1024^2
-// 74 -> 52 us, 8 x 4096^2 199 -> 182 us, 2 x 8192^2 196 -> 174 us, but 16 x 4096^2 314 -> 322 us; volumes
-// 2 x 256^3 82 -> 73 us, 4 x 256^3 118 -> 121 us, 512^3 205 -> 216 us (the lists of the blocks lie far
-// apart in a workspace of 8 bytes per vertex): hence the limits.
+// 74 -> 52 us, 8 x 4096^2 199 -> 179 us, 2 x 8192^2 196 -> 175 us, 16 x 4096^2 313 -> 301 us, but the
+// smoother fields of the 16 x 4096^2 benchmark batch 254 -> 257 us (8 of them 153 -> 152, 4 of them
+// 95 -> 81); volumes 2 x 256^3 82 -> 73 us, 4 x 256^3 118 -> 121 us, 512^3 205 -> 216 us (the lists of
+// the blocks lie far apart in a workspace of 8 bytes per vertex): hence the limits.
 constexpr int64_t kMidTotal2d = (int64_t)1 << 27, kMidTotal3d = (int64_t)1 << 25;  // vertices in the whole batch
 constexpr int64_t kMidBatch = 4096;
-constexpr unsigned kMidBlocks = 9216;            // sweep blocks in all (every finishing block reads every head)
+constexpr int64_t kMidFinishBlocks = 512;         // finishing blocks in all, about (8 to 128 per item)
+constexpr unsigned kMidHeads = 4096;             // more heads than this: a launch of its own reduces the range
+constexpr unsigned kMidBlocks = 65536;           // sweep blocks in all
 
 static bool mid_plan(const Shape& s, int dtype, unsigned& per_item, unsigned& cap) {
   if (s.ndim == 2 && sweep2d_supported(s, 1)) {
@@ -374,12 +409,17 @@ hipError_t launch_hard_mid(const void* grid, const Shape& s, int dtype, int bins
   // finishing blocks per item: about 8 lists each (1024 at most), up to 128 blocks; a lone item gets 16 at least
   unsigned shares = (per_item + 7u) / 8u;
   const unsigned least = s.batch >= 16 ? 1u : 16u / (unsigned)s.batch;
-  shares = shares < least ? least : (shares > 128u ? 128u : shares);
+  unsigned most = (unsigned)(kMidFinishBlocks / s.batch);  // about this many finishing blocks in all
+  most = most < 8u ? 8u : (most > 128u ? 128u : most);
+  shares = shares < least ? least : (shares > most ? most : shares);
+  if (shares * kFinishBlock < per_item) shares = (per_item + kFinishBlock - 1) / kFinishBlock;  // (1024 lists a block at most)
   const int super = (conv & kConvSuper) ? 1 : 0;
+  const bool range_first = blocks > kMidHeads;
+  if (range_first) hipLaunchKernelGGL(small_range_kernel, dim3(1), dim3(kFinishBlock), 0, st, la.heads, blocks, hdr);
   hipLaunchKernelGGL(small_finish_kernel<false>, dim3(shares, (unsigned)s.batch), dim3(kFinishBlock),
                      (size_t)bins * (sizeof(int) + sizeof(float)), st, la.heads,
-                     reinterpret_cast<const uint2*>(la.lists), per_item, blocks, (int)cap, bins, super, hdr, table,
-                     reinterpret_cast<long long*>(curve));
+                     reinterpret_cast<const uint2*>(la.lists), per_item, range_first ? 0u : blocks, (int)cap, bins, super,
+                     hdr, table, reinterpret_cast<long long*>(curve));
   launch_scan(curve, s, bins, super, st);
   return hipGetLastError();
 }
