@@ -1,4 +1,4 @@
-// Hard Euler Characteristic Curve of small float32 inputs without a range, in two launches.
+// Hard Euler Characteristic Curve of small and mid-sized float32 inputs without a range, in two or three launches.
 //
 // Below a few hundred thousand vertices a call is bound by its chain of dependent launches
 // (clear, sweep with the range, bin, gated second sweep, scan: five links of 4 to 5 us each),
