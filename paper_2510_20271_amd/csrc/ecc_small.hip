@@ -22,7 +22,7 @@
 
 namespace ecc {
 
-constexpr int kStageBlock = 256, kFinishBlock = 1024;
+constexpr int kStageBlock = 256, kFinishBlock = 1024, kFewThreads = 256;
 constexpr int64_t kSmallTotal = (int64_t)1 << 18;  // vertices in the whole batch
 constexpr int64_t kSmallItem = (int64_t)1 << 16;   // vertices in an item that one finishing block takes
 constexpr unsigned kSmallShares = 16;              // finishing blocks per larger item
@@ -159,11 +159,12 @@ __global__ __launch_bounds__(kFinishBlock) void small_range_kernel(const SmallHe
   }
 }
 
+// BLOCK: threads of a block (1024, or 256 for batches of many small items).
 // ALONE: one block per item, which also scans and writes the curve.  Otherwise block (x, item) takes
 // the x-th share of the item's lists and adds its histogram to the global one (`curve`, cleared
 // by the stage kernel); the scan is a launch of its own.
-template <bool ALONE>
-__global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallHead* __restrict__ heads,
+template <bool ALONE, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void small_finish_kernel(const SmallHead* __restrict__ heads,
                                                                     const uint2* __restrict__ entries,
                                                                     unsigned per_item, unsigned blocks, int per_block,
                                                                     int bins, int super,
@@ -173,9 +174,9 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
   extern __shared__ int lhist[];
   float* ltable = reinterpret_cast<float*>(lhist + bins);
   __shared__ unsigned s_min, s_max;
-  __shared__ long long wsum[kFinishBlock / kWave];
-  __shared__ unsigned wcnt[kFinishBlock / kWave];
-  __shared__ unsigned off[kFinishBlock + 1];  // exclusive prefix sums of the lists' lengths
+  __shared__ long long wsum[BLOCK / kWave];
+  __shared__ unsigned wcnt[BLOCK / kWave];
+  __shared__ unsigned off[BLOCK + 1];  // exclusive prefix sums of the lists' lengths
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
   const unsigned item = ALONE ? blockIdx.x : blockIdx.y;
   // this block's lists: all of the item's, or lists l0 .. l0 + nl of it
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
   __syncthreads();
   {
     unsigned kmin = 0xffffffffu, kmax = 0u;
-    for (unsigned b = tid; b < blocks; b += kFinishBlock) {
+    for (unsigned b = tid; b < blocks; b += BLOCK) {
       const SmallHead h = heads[b];
       kmin = min(kmin, h.min_key);
       kmax = max(kmax, h.max_key);
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
   __syncthreads();
   const double lo_d = (double)key_float(s_min), hi_d = (double)key_float(s_max);
   const float lo = __double2float_rn(lo_d), scale = bin_scale(bins, lo_d, hi_d);
-  for (int b = tid; b < bins; b += kFinishBlock) {
+  for (int b = tid; b < bins; b += BLOCK) {
     lhist[b] = 0;
     const float t = super ? threshold_lower_at(b, bins, lo_d, hi_d) : threshold_at(b, bins, lo_d, hi_d);
     ltable[b] = t;
@@ -237,14 +238,14 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
     if (tid == 0) off[0] = 0u;
   }
   __syncthreads();
-  const unsigned total = off[kFinishBlock];
-  constexpr unsigned kWaves = kFinishBlock / kWave, kDeep = 4;
+  const unsigned total = off[BLOCK];
+  constexpr unsigned kWaves = BLOCK / kWave, kDeep = 4;
   const unsigned piece = ((total + kWaves - 1) / kWaves + kWave - 1) / kWave * kWave;
   const unsigned begin = min(total, (unsigned)wv * piece), end = min(total, begin + piece);
   unsigned l = 0u;  // the last list that starts at or before `begin`
   if (begin < end) {
 #pragma unroll
-    for (unsigned step = kFinishBlock / 2; step > 0; step >>= 1)
+    for (unsigned step = BLOCK / 2; step > 0; step >>= 1)
       if (off[l + step] <= begin) l += step;
   }
   const uint2* mine = entries + ((size_t)item * per_item + l0) * (size_t)per_block;
@@ -274,14 +275,14 @@ __global__ __launch_bounds__(kFinishBlock) void small_finish_kernel(const SmallH
   __syncthreads();
   if constexpr (!ALONE) {
     unsigned long long* out = reinterpret_cast<unsigned long long*>(curve) + (int64_t)item * bins;
-    for (int b = tid; b < bins; b += kFinishBlock) {
+    for (int b = tid; b < bins; b += BLOCK) {
       const int v = lhist[b];
       if (v != 0) atomicAdd(&out[b], (unsigned long long)(long long)v);
     }
     return;
   }
   // inclusive prefix sum over the bins (suffix sum for superlevel sets: the mirrored index)
-  const int per = (bins + kFinishBlock - 1) / kFinishBlock;
+  const int per = (bins + BLOCK - 1) / BLOCK;
   const int b0 = min(tid * per, bins), b1 = min(b0 + per, bins);
   long long s = 0;
   for (int b = b0; b < b1; ++b) s += (long long)lhist[super ? bins - 1 - b : b];
@@ -330,10 +331,10 @@ hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_
   const size_t lds = (size_t)bins * (sizeof(int) + sizeof(float));
   const int super = (conv & kConvSuper) ? 1 : 0;
   if (alone) {
-    hipLaunchKernelGGL(small_finish_kernel<true>, dim3((unsigned)s.batch), dim3(kFinishBlock), lds, st, heads, entries,
+    hipLaunchKernelGGL((small_finish_kernel<true, kFinishBlock>), dim3((unsigned)s.batch), dim3(kFinishBlock), lds, st, heads, entries,
                        p.per_item, p.blocks, p.per_block, bins, super, hdr, table, reinterpret_cast<long long*>(curve));
   } else {
-    hipLaunchKernelGGL(small_finish_kernel<false>, dim3(kSmallShares, (unsigned)s.batch), dim3(kFinishBlock), lds, st,
+    hipLaunchKernelGGL((small_finish_kernel<false, kFinishBlock>), dim3(kSmallShares, (unsigned)s.batch), dim3(kFinishBlock), lds, st,
                        heads, entries, p.per_item, p.blocks, p.per_block, bins, super, hdr, table,
                        reinterpret_cast<long long*>(curve));
     launch_scan(curve, s, bins, super, st);
@@ -406,6 +407,23 @@ hipError_t launch_hard_mid(const void* grid, const Shape& s, int dtype, int bins
   if (s.ndim == 2) launch_sweep2d_list(grid, dtype, s, la, st, nullptr, conv);
   else launch_sweep3d_list(grid, dtype, s, la, st, nullptr, conv);
   profile_mark(st, true);
+  const int super = (conv & kConvSuper) ? 1 : 0;
+  const size_t lds = (size_t)bins * (sizeof(int) + sizeof(float));
+  const uint2* entries = reinterpret_cast<const uint2*>(la.lists);
+  long long* out = reinterpret_cast<long long*>(curve);
+  if (s.N <= kSmallItem && per_item <= (unsigned)kFewThreads) {
+    // Items one block can finish alone, prefix sum included: no third launch.  Every finishing block
+    // would read every head for the range; from about 16 MB of that on a launch of its own is cheaper.
+    const bool range_first = (int64_t)blocks * s.batch > ((int64_t)1 << 20);
+    if (range_first) hipLaunchKernelGGL(small_range_kernel, dim3(1), dim3(kFinishBlock), 0, st, la.heads, blocks, hdr);
+    if (s.batch >= 64 && s.N <= 4096)  // many small items: small blocks
+      hipLaunchKernelGGL((small_finish_kernel<true, kFewThreads>), dim3((unsigned)s.batch), dim3(kFewThreads), lds, st,
+                         la.heads, entries, per_item, range_first ? 0u : blocks, (int)cap, bins, super, hdr, table, out);
+    else
+      hipLaunchKernelGGL((small_finish_kernel<true, kFinishBlock>), dim3((unsigned)s.batch), dim3(kFinishBlock), lds, st,
+                         la.heads, entries, per_item, range_first ? 0u : blocks, (int)cap, bins, super, hdr, table, out);
+    return hipGetLastError();
+  }
   // finishing blocks per item: about 8 lists each (1024 at most), up to 128 blocks; a lone item gets 16 at least
   unsigned shares = (per_item + 7u) / 8u;
   const unsigned least = s.batch >= 16 ? 1u : 16u / (unsigned)s.batch;
@@ -413,13 +431,10 @@ hipError_t launch_hard_mid(const void* grid, const Shape& s, int dtype, int bins
   most = most < 8u ? 8u : (most > 128u ? 128u : most);
   shares = shares < least ? least : (shares > most ? most : shares);
   if (shares * kFinishBlock < per_item) shares = (per_item + kFinishBlock - 1) / kFinishBlock;  // (1024 lists a block at most)
-  const int super = (conv & kConvSuper) ? 1 : 0;
-  const bool range_first = blocks > kMidHeads;
+  const bool range_first = blocks > kMidHeads || (int64_t)blocks * shares * s.batch > ((int64_t)1 << 20);
   if (range_first) hipLaunchKernelGGL(small_range_kernel, dim3(1), dim3(kFinishBlock), 0, st, la.heads, blocks, hdr);
-  hipLaunchKernelGGL(small_finish_kernel<false>, dim3(shares, (unsigned)s.batch), dim3(kFinishBlock),
-                     (size_t)bins * (sizeof(int) + sizeof(float)), st, la.heads,
-                     reinterpret_cast<const uint2*>(la.lists), per_item, range_first ? 0u : blocks, (int)cap, bins, super,
-                     hdr, table, reinterpret_cast<long long*>(curve));
+  hipLaunchKernelGGL((small_finish_kernel<false, kFinishBlock>), dim3(shares, (unsigned)s.batch), dim3(kFinishBlock), lds, st,
+                     la.heads, entries, per_item, range_first ? 0u : blocks, (int)cap, bins, super, hdr, table, out);
   launch_scan(curve, s, bins, super, st);
   return hipGetLastError();
 }

@@ -93,7 +93,8 @@ def test_small_flow_static_scratch_and_workspace_reuse():
 
 
 @pytest.mark.parametrize("B,shape", [(1, (1024, 1024)), (3, (700, 1300)), (64, (100, 650)), (65, (100, 650)),
-                                      (4096, (8, 16)), (4097, (8, 16)), (1, (4096, 8192)), (1, (4096, 8200)),
+                                      (4096, (8, 16)), (4097, (8, 16)), (300, (64, 64)), (1024, (28, 28)), (70, (64, 65)),
+                                      (1, (4096, 8192)), (1, (4096, 8200)),
                                       (1, (128, 128, 128)), (2, (60, 200, 300)), (1, (9, 1000, 1000)),
                                       (1, (256, 256, 512)), (1, (256, 256, 520))])
 def test_mid_flow_sizes(B, shape):
@@ -107,10 +108,11 @@ def test_mid_flow_sizes(B, shape):
     assert np.all(got[:, -1] == 1)
 
 
-@pytest.mark.parametrize("shape", [(1500, 1500), (100, 120, 250)])
-def test_mid_flow_white_noise_fills_the_lists(shape):
+@pytest.mark.parametrize("B,shape", [(2, (1500, 1500)), (2, (100, 120, 250)), (70, (200, 300)), (200, (60, 60))])
+def test_mid_flow_white_noise_fills_the_lists(B, shape):
     # 60 % of the vertices are critical: far beyond the room of the shared lists of the large-input flow
-    X = np.random.default_rng(9).standard_normal((2,) + shape).astype(np.float32)
+    # (the two batches of many small items are finished by one block per item, prefix sum included)
+    X = np.random.default_rng(9).standard_normal((B,) + shape).astype(np.float32)
     for kw in ({}, {"top": True}, {"superlevel": True}):
         got = _both(lambda: api.ecc_hard(dev(X), len(shape), 129, **kw))
         lo, hi = float(X.min()), float(X.max())
