@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2510_20271_amd import _lib
@@ -47,6 +48,25 @@ def test_workspace_bytes_host_only():
     # soft partials dominate for many tiles
     big = lib.ecc_workspace_bytes(2, _dims(512, 512), 32, 128)
     assert big >= 32 * 128 * 128 * 16
+
+
+def test_workspace_bytes_of_the_hard_flows():
+    # small inputs: a list slot per vertex (8 bytes) and a head per stage block
+    lib = _lib.load()
+    n = 256 * 256
+    # (a 256-wide image is two strips of 248 columns to the sweep: its blocks own up to twice its vertices)
+    assert 8 * n <= lib.ecc_workspace_bytes(2, _dims(256, 256), 1, 64) <= 16 * n + (1 << 16)
+    # mid-sized batches (up to 2^27 vertices in images, 2^25 in volumes): room for every vertex of every
+    # sweep block, rounded up to whole blocks
+    for nd, dims, batch in ((2, (1024, 1024), 1), (2, (512, 512), 32), (2, (4096, 4096), 8), (3, (256, 256, 256), 2)):
+        n = int(np.prod(dims)) * batch
+        w = lib.ecc_workspace_bytes(nd, _dims(*dims), batch, 1024)
+        assert 8 * n <= w <= 12 * n, (dims, batch, w / n)
+    # beyond: one byte per vertex for the shared lists (the soft partial sums of a call with T = 1024 aside)
+    for nd, dims, batch in ((2, (4096, 4096), 16), (3, (512, 512, 512), 1), (2, (224, 224), 5000)):
+        n = int(np.prod(dims)) * batch
+        w = lib.ecc_workspace_bytes(nd, _dims(*dims), batch, 8)
+        assert n <= w <= 2 * n, (dims, batch, w / n)
 
 
 INVALID, UNSUPPORTED, WORKSPACE, RANGE = -1, -2, -3, -4
