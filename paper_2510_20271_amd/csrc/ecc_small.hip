@@ -26,7 +26,7 @@ constexpr int kStageBlock = 256, kFinishBlock = 1024, kFewThreads = 256;
 constexpr int64_t kSmallTotal = (int64_t)1 << 18;  // vertices in the whole batch
 constexpr int64_t kSmallItem = (int64_t)1 << 16;   // vertices in an item that one finishing block takes
 constexpr unsigned kSmallShares = 16;              // finishing blocks per larger item
-constexpr int64_t kSmallBatch = 64;                // every finish block reads every stage block's header
+constexpr int64_t kSmallBatch = 64;                // items (larger batches: the mid-sized flow below)
 constexpr int kSmallBins = 4096;
 
 typedef ListHead SmallHead;
@@ -331,12 +331,13 @@ hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_
   const size_t lds = (size_t)bins * (sizeof(int) + sizeof(float));
   const int super = (conv & kConvSuper) ? 1 : 0;
   if (alone) {
-    hipLaunchKernelGGL((small_finish_kernel<true, kFinishBlock>), dim3((unsigned)s.batch), dim3(kFinishBlock), lds, st, heads, entries,
-                       p.per_item, p.blocks, p.per_block, bins, super, hdr, table, reinterpret_cast<long long*>(curve));
-  } else {
-    hipLaunchKernelGGL((small_finish_kernel<false, kFinishBlock>), dim3(kSmallShares, (unsigned)s.batch), dim3(kFinishBlock), lds, st,
+    hipLaunchKernelGGL((small_finish_kernel<true, kFinishBlock>), dim3((unsigned)s.batch), dim3(kFinishBlock), lds, st,
                        heads, entries, p.per_item, p.blocks, p.per_block, bins, super, hdr, table,
                        reinterpret_cast<long long*>(curve));
+  } else {
+    hipLaunchKernelGGL((small_finish_kernel<false, kFinishBlock>), dim3(kSmallShares, (unsigned)s.batch),
+                       dim3(kFinishBlock), lds, st, heads, entries, p.per_item, p.blocks, p.per_block, bins, super, hdr,
+                       table, reinterpret_cast<long long*>(curve));
     launch_scan(curve, s, bins, super, st);
   }
   return hipGetLastError();
@@ -354,7 +355,7 @@ hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_
 // the blocks lie far apart in a workspace of 8 bytes per vertex): hence the limits.
 constexpr int64_t kMidTotal2d = (int64_t)1 << 27, kMidTotal3d = (int64_t)1 << 25;  // vertices in the whole batch
 constexpr int64_t kMidBatch = 4096;
-constexpr int64_t kMidFinishBlocks = 512;         // finishing blocks in all, about (8 to 128 per item)
+constexpr int64_t kMidFinishBlocks = 512;          // finishing blocks in all, about (8 to 128 per item)
 constexpr unsigned kMidHeads = 4096;             // more heads than this: a launch of its own reduces the range
 constexpr unsigned kMidBlocks = 65536;           // sweep blocks in all
 
@@ -375,7 +376,8 @@ static bool mid_plan(const Shape& s, int dtype, unsigned& per_item, unsigned& ca
 
 // dtype: float32, float16 or bfloat16 (the types whose range is found on the device)
 bool mid_supported(const Shape& s, int bins, int dtype) {
-  if (!(dtype == 2 || dtype == 3 || dtype == 6) || bins > kSmallBins || s.N * s.batch > (s.ndim == 2 ? kMidTotal2d : kMidTotal3d) || s.batch > kMidBatch)
+  const int64_t most = s.ndim == 2 ? kMidTotal2d : kMidTotal3d;
+  if (!(dtype == 2 || dtype == 3 || dtype == 6) || bins > kSmallBins || s.N * s.batch > most || s.batch > kMidBatch)
     return false;
   unsigned per_item, cap;
   if (!mid_plan(s, dtype, per_item, cap)) return false;
