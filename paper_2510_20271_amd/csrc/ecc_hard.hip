@@ -460,8 +460,8 @@ hipError_t launch_hard(const void* grid, const Shape& s, int dtype, int bins, bo
                              wsb + kTableOffset + table_bytes(bins), st, conv);
   }
   // Mid-sized float grids without a range: the sweep with a list per block, three launches.
-  if (device_range && !dir && roomy && forced_paths() == 0u && (fast2d || fast3d) && mid_supported(s, bins, dtype))
-    return launch_hard_mid(grid, s, dtype, bins, curve, hdr, table, wsb + kTableOffset + table_bytes(bins), st, conv);
+  if (device_range && roomy && forced_paths() == 0u && (fast2d || fast3d) && mid_supported(s, bins, dtype))
+    return launch_hard_mid(grid, s, dtype, bins, curve, hdr, table, wsb + kTableOffset + table_bytes(bins), st, conv, dir);
   // Element types beyond uint8 / uint16 / float32.  The strip / tube sweeps load float16, bfloat16
   // and int16 as they are (all three widen to float32 exactly); the other kernels, and int32 /
   // float64 everywhere, get a float32 copy rounded to nearest even.

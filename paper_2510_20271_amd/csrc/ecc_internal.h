@@ -57,8 +57,9 @@ void launch_scan(int64_t* curve, const Shape& s, int bins, int suffix, hipStream
 // `room`: mid_workspace_bytes() bytes behind the threshold table.
 bool mid_supported(const Shape& s, int bins, int dtype);
 size_t mid_workspace_bytes(const Shape& s, int dtype);
+// dir (may be null): a directional call, s.batch = directions x items
 hipError_t launch_hard_mid(const void* grid, const Shape& s, int dtype, int bins, int64_t* curve, HardHeader* hdr,
-                           float* table, void* room, hipStream_t st, int conv);
+                           float* table, void* room, hipStream_t st, int conv, const DirArgs* dir);
 hipError_t launch_hard_small(const float* grid, const Shape& s, int bins, int64_t* curve, HardHeader* hdr, float* table,
                              void* small, hipStream_t st, int conv);
 // single-pass mode: per-item lists of critical vertices (value, c) in the workspace

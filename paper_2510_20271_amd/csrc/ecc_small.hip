@@ -392,7 +392,7 @@ size_t mid_workspace_bytes(const Shape& s, int dtype) {
 }
 
 hipError_t launch_hard_mid(const void* grid, const Shape& s, int dtype, int bins, int64_t* curve, HardHeader* hdr,
-                           float* table, void* room, hipStream_t st, int conv) {
+                           float* table, void* room, hipStream_t st, int conv, const DirArgs* dir) {
   unsigned per_item, cap;
   mid_plan(s, dtype, per_item, cap);
   const unsigned blocks = per_item * (unsigned)s.batch;
@@ -406,8 +406,8 @@ hipError_t launch_hard_mid(const void* grid, const Shape& s, int dtype, int bins
   la.zero_hist = reinterpret_cast<unsigned long long*>(curve);
   la.bins = bins;
   profile_mark(st, false);
-  if (s.ndim == 2) launch_sweep2d_list(grid, dtype, s, la, st, nullptr, conv);
-  else launch_sweep3d_list(grid, dtype, s, la, st, nullptr, conv);
+  if (s.ndim == 2) launch_sweep2d_list(grid, dtype, s, la, st, dir, conv);
+  else launch_sweep3d_list(grid, dtype, s, la, st, dir, conv);
   profile_mark(st, true);
   const int super = (conv & kConvSuper) ? 1 : 0;
   const size_t lds = (size_t)bins * (sizeof(int) + sizeof(float));

@@ -27,7 +27,7 @@ def _range(Xb, U, alpha):
 
 
 @pytest.mark.parametrize("shape", SHAPES)
-def test_directional_curves_match_the_oracle(shape):
+def test_directional_curves_match_the_oracle(shape, flow):
     nd = len(shape)
     rng = np.random.default_rng(41)
     B, K, bins, alpha = 2, 3, 29, 0.37
@@ -45,7 +45,7 @@ def test_directional_curves_match_the_oracle(shape):
     assert np.all(got[..., -1] == 1)
 
 
-def test_zero_alpha_gives_the_plain_curves_for_every_direction():
+def test_zero_alpha_gives_the_plain_curves_for_every_direction(flow):
     X = np.stack([synth.grf((90, 300), 2.0, 3 + i) for i in range(2)])
     U = np.array([[1.0, 0.0], [0.6, -0.8]], np.float32)
     got = host(api.ecc_hard_dir(dev(X), 2, dev(U), 0.0, 64))
@@ -55,7 +55,7 @@ def test_zero_alpha_gives_the_plain_curves_for_every_direction():
 
 
 @pytest.mark.parametrize("shape", [(1024, 1024), (96, 128, 160)])
-def test_directional_curves_of_smooth_fields(shape):
+def test_directional_curves_of_smooth_fields(shape, flow):
     nd = len(shape)
     X = synth.grf(shape, 3.0, 77)[None]
     th = np.linspace(0.0, np.pi, 5, endpoint=False)
