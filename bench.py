@@ -152,13 +152,43 @@ def size_rows(args, np, torch, api, synth, field_2d=None, field_3d=None):
     return rows
 
 
+def batch_rows(args, np, torch, api, synth):
+    """Batches of small float32 images and sets of directions (what a topological layer or a directional
+    transform calls with; not a workload of the paper): whole calls, 256 bins, range found on the device."""
+    rows = []
+    cases = [("hard", 1024, (28, 28), 0), ("hard", 256, (64, 64), 0), ("hard", 256, (256, 256), 0), ("hard", 32, (512, 512), 0),
+             ("hard", 16, (1024, 1024), 0), ("hard", 16, (64, 64, 64), 0), ("dir", 1, (256, 256), 64), ("dir", 8, (128, 128), 32)]
+    for kind, B, shape, ndir in cases:
+        nd = len(shape)
+        base = np.stack([synth.grf(shape, 2.0, 900 + i) for i in range(min(B, 4))])
+        g = torch.from_numpy(np.ascontiguousarray(base[np.arange(B) % base.shape[0]])).cuda()
+        rows_out = B * max(ndir, 1)
+        cv = torch.empty((rows_out, 256) if not ndir else (ndir, B, 256), dtype=torch.int64, device="cuda")
+        if ndir:
+            U = np.random.default_rng(5).standard_normal((ndir, nd)).astype(np.float32)
+            u = torch.from_numpy(U / np.linalg.norm(U, axis=1, keepdims=True)).cuda()
+            ws = torch.empty(api.ecc_workspace_bytes_dir(shape, B, ndir, 256), dtype=torch.uint8, device="cuda")
+            step = lambda: api.ecc_hard_dir(g, nd, u, 1e-3, 256, curve=cv, workspace=ws)
+        else:
+            ws = torch.empty(api.ecc_workspace_bytes(shape, B, 256), dtype=torch.uint8, device="cuda")
+            step = lambda: api.ecc_hard(g, nd, 256, curve=cv, workspace=ws)
+        ms = time_steps(step, args.steps, args.warmup)
+        n = int(np.prod(shape)) * rows_out
+        name = (f"{ndir} directions x " if ndir else "") + f"{B} x " + "x".join(map(str, shape))
+        rows.append({"workload": name, "ms": round(ms, 4), "gvoxel_per_s": round(n / ms / 1e6, 1)})
+        log(f"[bench] batch {name:>32}: {ms:8.4f} ms  {rows[-1]['gvoxel_per_s']:8.1f} Gvoxel/s")
+        del g, ws, cv
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--quick", action="store_true", help="C2 only: skip the other workloads and the CPU baseline")
-    ap.add_argument("--only", default="", help="profiling aid: run one of c1, c2, c2r, c3, c4, c4r, c5, dir, sizes, "
+    ap.add_argument("--only", default="", help="profiling aid: run one of c1, c2, c2r, c3, c4, c4r, c5, dir, sizes, batches, "
                                                "calib (a plain 1 GiB copy); no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -486,6 +516,14 @@ def main():
                                            "fields tiled 2x",
                                "rows": size_rows(args, np, torch, api, synth, field_2d, field_3d)}
         if only == "sizes":
+            return
+
+    # ---------------- batches of small images, sets of directions ----------------
+    if want("batches"):
+        extra["batches"] = {"workload": "batches of small float32 smoothed random fields and sets of directions, 256 bins, "
+                                        "range found on the device (whole call)",
+                            "rows": batch_rows(args, np, torch, api, synth)}
+        if only == "batches":
             return
 
     extra["rooflines"] = rooflines
